@@ -1,0 +1,120 @@
+/*
+ * fftconv -- frequency-domain convolution for CNN layers on AMD gfx950 (MI355X).
+ *
+ * C ABI of the hot path of "Fast Convolutional Nets With fbfft" (arXiv 1412.7580):
+ * the three convolution passes of Section 2 computed as in Section 3.1 / Table 1
+ * (2-D real FFT of both zero-padded operands -> per-frequency complex product that
+ * reduces over planes -> inverse FFT clipped to the valid region), plus the batched
+ * small 1-D / 2-D real FFTs of Section 5 as stand-alone calls.
+ *
+ * Conventions common to every call
+ *  - All tensor pointers are DEVICE pointers to dense, row-major fp32 memory owned by
+ *    the caller ("BDHW", innermost = image row, Section 3.1).  Inputs are never
+ *    modified; outputs are fully overwritten (except fft_conv_accgrad with
+ *    accumulate != 0).  Input and output ranges must not overlap.
+ *  - Work is enqueued on the handle's stream and the call returns without waiting for
+ *    it.  A handle must not be used from two threads at once, nor may two of its calls
+ *    overlap on different streams: the frequency-domain buffers are one reused set per
+ *    handle (the buffer policy of Section 3.3).
+ *  - Every function returns an fftconv_status; arguments are validated before anything
+ *    is launched, so on an error other than FFTCONV_HIP_ERROR no device work was issued.
+ *  - The Fourier basis is square with N = the smallest power of two >= max(h, w),
+ *    at least 8 and at most 128 (the range of the paper's 2-D kernels, Section 5.3).
+ */
+#ifndef FFTCONV_H
+#define FFTCONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fftconv_ctx *fftconv_handle;
+
+typedef enum {
+    FFTCONV_OK = 0,
+    FFTCONV_INVALID_ARG = 1,         /* null pointer, non-positive size, kernel larger than input, n_in > n ... */
+    FFTCONV_UNSUPPORTED = 2,         /* Fourier basis outside {8,16,32,64,128} */
+    FFTCONV_WORKSPACE_TOO_SMALL = 3, /* caller-supplied workspace smaller than fftconv_workspace_bytes() */
+    FFTCONV_HIP_ERROR = 4            /* allocation or launch failure reported by the HIP runtime */
+} fftconv_status;
+
+enum { FFTCONV_FPROP = 0, FFTCONV_BPROP = 1, FFTCONV_ACCGRAD = 2 };
+
+/* Create a handle bound to HIP device `device` (made current for the call).  The handle
+ * starts on the null stream and owns no workspace until one is needed. */
+int fftconv_create(fftconv_handle *out, int device);
+/* Free the handle and any workspace it owns.  Pending work must have completed. */
+int fftconv_destroy(fftconv_handle h);
+/* `stream` is a hipStream_t passed as void*; NULL selects the null stream. */
+int fftconv_set_stream(fftconv_handle h, void *stream);
+const char *fftconv_status_string(int status);
+
+/* Bytes of device scratch one pass needs: the three frequency-domain tensors of Table 1
+ * (both operands and the product), Hermitian half, complex fp32, in the library's private
+ * bin-major layout.  Returns 0 for invalid or unsupported shapes. */
+size_t fftconv_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw);
+
+/*
+ * The three passes (Section 2; pipeline of Table 1; clipping sizes of Section 3.1).
+ *   S minibatch, f input planes, fo output planes (f'), h x w input, kh x kw kernel,
+ *   oh = h-kh+1, ow = w-kw+1.  Stride 1, no margin padding (Section 2 excludes strides).
+ * `ws`/`ws_bytes`: optional caller-owned device scratch of at least
+ * fftconv_workspace_bytes(); with ws == NULL the handle grows and reuses its own buffer
+ * (hipMalloc on first use or growth only).
+ */
+
+/* fprop: y(s,j) = sum_i x(s,i) (star) w(j,i)  -- valid cross-correlation.
+ * x[S,f,h,w], wt[fo,f,kh,kw] -> y[S,fo,oh,ow]. */
+int fft_conv_fprop(fftconv_handle hd, const float *x, const float *wt, float *y,
+                   int S, int f, int fo, int h, int w, int kh, int kw,
+                   void *ws, size_t ws_bytes);
+
+/* bprop: dL/dx(s,i) = sum_j dL/dy(s,j) * w(j,i)  -- full convolution, reduces over fo.
+ * gy[S,fo,oh,ow], wt[fo,f,kh,kw] -> gx[S,f,h,w]. */
+int fft_conv_bprop(fftconv_handle hd, const float *gy, const float *wt, float *gx,
+                   int S, int f, int fo, int h, int w, int kh, int kw,
+                   void *ws, size_t ws_bytes);
+
+/* accGrad: dL/dw(j,i) = sum_s dL/dy(s,j) (star) x(s,i)  -- reduces over the minibatch.
+ * x[S,f,h,w], gy[S,fo,oh,ow] -> gw[fo,f,kh,kw] = scale * result (+ previous gw if
+ * accumulate != 0). */
+int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *gw,
+                     int S, int f, int fo, int h, int w, int kh, int kw,
+                     float scale, int accumulate, void *ws, size_t ws_bytes);
+
+/*
+ * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
+ * (Supplement, DFT definition); n in {8,16,32,64,128}.  Inputs shorter than n are
+ * zero-padded implicitly while loading (the clipping of Section 5.1), no padded copy is
+ * made.  Complex data are interleaved (re,im) fp32; only the Hermitian half
+ * k = 0..n/2 along the innermost axis is stored (Table 1), in natural bin order.
+ * The inverse calls are true inverses (scaled by 1/n per dimension) that keep the first
+ * n_out (h_out x w_out) samples.  Their input must be the transform of a real signal;
+ * imaginary parts of self-conjugate bins are not looked at.  B = 0 is a no-op that
+ * returns FFTCONV_OK (pointers may then be NULL).
+ */
+/* in[B,n_in] -> out[B,n/2+1,2];  1 <= n_in <= n. */
+int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in, int n);
+/* in[B,n/2+1,2] -> out[B,n_out];  1 <= n_out <= n. */
+int fft_c2r_1d(fftconv_handle hd, const float *in, float *out, long B, int n, int n_out);
+/* in[B,h_in,w_in] -> out[B,n,n/2+1,2]. */
+int fft_r2c_2d(fftconv_handle hd, const float *in, float *out, long B, int h_in, int w_in, int n);
+/* in[B,n,n/2+1,2] -> out[B,h_out,w_out]. */
+int fft_c2r_2d(fftconv_handle hd, const float *in, float *out, long B, int n, int h_out, int w_out);
+
+/*
+ * Per-stage timing of the last convolution pass, for roofline reporting.
+ * With profiling enabled each pass records HIP events on the handle's stream around its
+ * four stages (FFT of operand A, FFT of operand B, per-bin contraction, inverse FFT);
+ * fftconv_last_stage_ms() waits for the last pass and returns the four durations in
+ * milliseconds.  Off by default; enabling it adds event records to the stream.
+ */
+int fftconv_set_profiling(fftconv_handle h, int enabled);
+int fftconv_last_stage_ms(fftconv_handle h, float ms_out[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFTCONV_H */

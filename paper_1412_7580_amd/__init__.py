@@ -1,0 +1,202 @@
+"""Thin Python binding of libfftconv.so (the C ABI declared in include/fftconv.h).
+
+Argument marshalling only: torch is used for device memory and streams, every step of the
+computation runs in the HIP kernels.  There is no CPU or PyTorch fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBPATH = os.path.join(_HERE, "libfftconv.so")
+_lib = None
+
+SYMBOLS = [
+    "fftconv_create", "fftconv_destroy", "fftconv_set_stream", "fftconv_status_string",
+    "fftconv_workspace_bytes", "fft_conv_fprop", "fft_conv_bprop", "fft_conv_accgrad",
+    "fft_r2c_1d", "fft_c2r_1d", "fft_r2c_2d", "fft_c2r_2d",
+    "fftconv_set_profiling", "fftconv_last_stage_ms",
+]
+
+
+class FFTConvError(RuntimeError):
+    pass
+
+
+def load_library():
+    """dlopen libfftconv.so (building it first only if it does not exist) and set prototypes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIBPATH):
+        from . import build as _build
+        _build.build(force=True)
+    lib = ctypes.CDLL(_LIBPATH)
+    vp, i, l, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
+    lib.fftconv_create.argtypes = [ctypes.POINTER(vp), i]
+    lib.fftconv_destroy.argtypes = [vp]
+    lib.fftconv_set_stream.argtypes = [vp, vp]
+    lib.fftconv_status_string.argtypes = [i]
+    lib.fftconv_status_string.restype = ctypes.c_char_p
+    lib.fftconv_workspace_bytes.argtypes = [i] * 8
+    lib.fftconv_workspace_bytes.restype = sz
+    lib.fft_conv_fprop.argtypes = [vp, vp, vp, vp] + [i] * 7 + [vp, sz]
+    lib.fft_conv_bprop.argtypes = [vp, vp, vp, vp] + [i] * 7 + [vp, sz]
+    lib.fft_conv_accgrad.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i, vp, sz]
+    lib.fft_r2c_1d.argtypes = [vp, vp, vp, l, i, i]
+    lib.fft_c2r_1d.argtypes = [vp, vp, vp, l, i, i]
+    lib.fft_r2c_2d.argtypes = [vp, vp, vp, l, i, i, i]
+    lib.fft_c2r_2d.argtypes = [vp, vp, vp, l, i, i, i]
+    lib.fftconv_set_profiling.argtypes = [vp, i]
+    lib.fftconv_last_stage_ms.argtypes = [vp, ctypes.POINTER(f * 4)]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        msg = load_library().fftconv_status_string(rc).decode()
+        raise FFTConvError(f"{what}: {msg} (status {rc})")
+
+
+def _dev_f32(t, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise FFTConvError(f"{name} must be a contiguous float32 tensor in device memory")
+    return t.data_ptr()
+
+
+FPROP, BPROP, ACCGRAD = 0, 1, 2
+
+
+class Handle:
+    """Owner of one fftconv_handle; the methods mirror the C entry points one to one."""
+
+    def __init__(self, device: int = 0):
+        import torch
+        if not torch.cuda.is_available():
+            raise FFTConvError("no GPU visible: the HIP library cannot run (there is no CPU fallback)")
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        _check(self._lib.fftconv_create(ctypes.byref(self._h), device), "fftconv_create")
+        self.device = device
+
+    def close(self):
+        if self._h:
+            self._lib.fftconv_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _sync_stream(self):
+        import torch
+        s = torch.cuda.current_stream().cuda_stream
+        _check(self._lib.fftconv_set_stream(self._h, ctypes.c_void_p(s)), "fftconv_set_stream")
+
+    def workspace_bytes(self, pass_, S, f, fo, h, w, kh, kw) -> int:
+        return int(self._lib.fftconv_workspace_bytes(pass_, S, f, fo, h, w, kh, kw))
+
+    def set_profiling(self, on: bool):
+        _check(self._lib.fftconv_set_profiling(self._h, 1 if on else 0), "fftconv_set_profiling")
+
+    def last_stage_ms(self):
+        buf = (ctypes.c_float * 4)()
+        _check(self._lib.fftconv_last_stage_ms(self._h, ctypes.byref(buf)), "fftconv_last_stage_ms")
+        return [float(v) for v in buf]
+
+    # ---- convolution passes -------------------------------------------------------------
+    def fft_conv_fprop(self, x, wt, y=None, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f:
+            raise FFTConvError("x and wt disagree on the number of input planes")
+        if y is None:
+            y = torch.empty((S, fo, h - kh + 1, w - kw + 1), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
+                                        S, f, fo, h, w, kh, kw, *self._ws(ws)), "fft_conv_fprop")
+        return y
+
+    def fft_conv_bprop(self, gy, wt, h, w, gx=None, ws=None):
+        import torch
+        S, fo, oh, ow = gy.shape
+        fo2, f, kh, kw = wt.shape
+        if fo2 != fo or oh != h - kh + 1 or ow != w - kw + 1:
+            raise FFTConvError("gy, wt and (h, w) disagree")
+        if gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_bprop(self._h, _dev_f32(gy, "gy"), _dev_f32(wt, "wt"), _dev_f32(gx, "gx"),
+                                        S, f, fo, h, w, kh, kw, *self._ws(ws)), "fft_conv_bprop")
+        return gx
+
+    def fft_conv_accgrad(self, x, gy, gw=None, scale=1.0, accumulate=False, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        S2, fo, oh, ow = gy.shape
+        if S2 != S:
+            raise FFTConvError("x and gy disagree on the minibatch size")
+        kh, kw = h - oh + 1, w - ow + 1
+        if gw is None:
+            if accumulate:
+                raise FFTConvError("accumulate needs an existing gw")
+            gw = torch.empty((fo, f, kh, kw), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_accgrad(self._h, _dev_f32(x, "x"), _dev_f32(gy, "gy"), _dev_f32(gw, "gw"),
+                                          S, f, fo, h, w, kh, kw, float(scale), 1 if accumulate else 0,
+                                          *self._ws(ws)), "fft_conv_accgrad")
+        return gw
+
+    @staticmethod
+    def _ws(ws):
+        if ws is None:
+            return ctypes.c_void_p(0), 0
+        return ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+    # ---- stand-alone FFTs ---------------------------------------------------------------
+    def fft_r2c_1d(self, x, n, out=None):
+        import torch
+        B, n_in = x.shape
+        if out is None:
+            out = torch.empty((B, n // 2 + 1, 2), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_r2c_1d(self._h, _dev_f32(x, "in"), _dev_f32(out, "out"), B, n_in, n), "fft_r2c_1d")
+        return out
+
+    def fft_c2r_1d(self, X, n, n_out, out=None):
+        import torch
+        B = X.shape[0]
+        if tuple(X.shape[1:]) != (n // 2 + 1, 2):
+            raise FFTConvError("in must be [B, n/2+1, 2]")
+        if out is None:
+            out = torch.empty((B, n_out), device=X.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_c2r_1d(self._h, _dev_f32(X, "in"), _dev_f32(out, "out"), B, n, n_out), "fft_c2r_1d")
+        return out
+
+    def fft_r2c_2d(self, x, n, out=None):
+        import torch
+        B, h_in, w_in = x.shape
+        if out is None:
+            out = torch.empty((B, n, n // 2 + 1, 2), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_r2c_2d(self._h, _dev_f32(x, "in"), _dev_f32(out, "out"), B, h_in, w_in, n), "fft_r2c_2d")
+        return out
+
+    def fft_c2r_2d(self, X, n, h_out, w_out, out=None):
+        import torch
+        B = X.shape[0]
+        if tuple(X.shape[1:]) != (n, n // 2 + 1, 2):
+            raise FFTConvError("in must be [B, n, n/2+1, 2]")
+        if out is None:
+            out = torch.empty((B, h_out, w_out), device=X.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_c2r_2d(self._h, _dev_f32(X, "in"), _dev_f32(out, "out"), B, n, h_out, w_out), "fft_c2r_2d")
+        return out

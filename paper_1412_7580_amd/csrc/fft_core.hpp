@@ -1,0 +1,182 @@
+// In-register small FFT building blocks for gfx950 (wave64).
+//
+// A length-N line (N = L*G, G in {1,2}) is transformed by G adjacent lanes.  Lane g holds
+// the decimated samples x[g + G*m], m < L, in L complex registers, runs an L-point FFT on
+// them with fully static register indexing (straight-line code, twiddles are immediates),
+// and, for G = 2, finishes with one radix-2 decimation-in-time step across the lane pair
+// through DPP quad-permutes.  Afterwards lane q holds bins k + L*q in register k.
+//
+// This replaces the one-element-per-lane warp-shuffle butterflies of Section 5.2 of the
+// fbfft paper: on CDNA every cross-lane permute other than DPP goes through the LDS pipe,
+// the very bottleneck Section 6 reports, so the butterflies stay inside a lane and only the
+// last stage of the two largest sizes crosses lanes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <type_traits>
+
+namespace fc {
+
+// ---------------------------------------------------------------- compile-time twiddles
+constexpr double kPi = 3.14159265358979323846264338327950288;
+
+constexpr double sin_small(double x) {  // |x| <= pi/4, Taylor, error < 1e-17
+    double x2 = x * x, term = x, sum = x;
+    for (int i = 1; i < 14; ++i) { term *= -x2 / double((2 * i) * (2 * i + 1)); sum += term; }
+    return sum;
+}
+constexpr double cos_small(double x) {
+    double x2 = x * x, term = 1.0, sum = 1.0;
+    for (int i = 1; i < 14; ++i) { term *= -x2 / double((2 * i - 1) * (2 * i)); sum += term; }
+    return sum;
+}
+struct cplx_d { double re, im; };
+// exp(+2 pi i k / n) for n a power of two <= 1024, by octant reduction so that exact
+// values (0, +-1) and symmetries come out exactly.
+constexpr cplx_d unit_root(int k, int n) {
+    int K = ((k % n) + n) % n * (1024 / n);
+    int q = K / 256, r = K % 256;
+    double c = 0, s = 0;
+    if (r <= 128) { double a = 2.0 * kPi * r / 1024.0; c = cos_small(a); s = sin_small(a); }
+    else { double a = 2.0 * kPi * (256 - r) / 1024.0; c = sin_small(a); s = cos_small(a); }
+    if (r == 0) { c = 1.0; s = 0.0; }
+    switch (q) {
+        case 0: return {c, s};
+        case 1: return {-s, c};
+        case 2: return {-c, -s};
+        default: return {s, -c};
+    }
+}
+
+template <int I, int E, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < E) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, E>(f);
+    }
+}
+
+// ---------------------------------------------------------------- L-point FFT in registers
+// DIR = -1 forward (exp(-2 pi i jk/L)), +1 inverse (unscaled).  Natural order in and out.
+template <int L, int DIR>
+__device__ __forceinline__ void fft_leaf(float (&re)[L], float (&im)[L]) {
+    if constexpr (L == 2) {
+        float ar = re[0], ai = im[0], br = re[1], bi = im[1];
+        re[0] = ar + br; im[0] = ai + bi;
+        re[1] = ar - br; im[1] = ai - bi;
+    } else if constexpr (L == 4) {
+        // radix-4 butterfly
+        float s0r = re[0] + re[2], s0i = im[0] + im[2];
+        float d0r = re[0] - re[2], d0i = im[0] - im[2];
+        float s1r = re[1] + re[3], s1i = im[1] + im[3];
+        float d1r = re[1] - re[3], d1i = im[1] - im[3];
+        re[0] = s0r + s1r; im[0] = s0i + s1i;
+        re[2] = s0r - s1r; im[2] = s0i - s1i;
+        if constexpr (DIR < 0) {   // X1 = d0 - i d1, X3 = d0 + i d1
+            re[1] = d0r + d1i; im[1] = d0i - d1r;
+            re[3] = d0r - d1i; im[3] = d0i + d1r;
+        } else {                   // X1 = d0 + i d1, X3 = d0 - i d1
+            re[1] = d0r - d1i; im[1] = d0i + d1r;
+            re[3] = d0r + d1i; im[3] = d0i - d1r;
+        }
+    } else {
+        constexpr int H = L / 2;
+        float er[H], ei[H], pr[H], pi[H];
+#pragma unroll
+        for (int m = 0; m < H; ++m) {
+            er[m] = re[2 * m]; ei[m] = im[2 * m];
+            pr[m] = re[2 * m + 1]; pi[m] = im[2 * m + 1];
+        }
+        fft_leaf<H, DIR>(er, ei);
+        fft_leaf<H, DIR>(pr, pi);
+        static_for<0, H>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            float tr, ti;
+            if constexpr (k == 0) {
+                tr = pr[k]; ti = pi[k];
+            } else if constexpr (4 * k == L) {          // multiply by DIR * i
+                if constexpr (DIR < 0) { tr = pi[k]; ti = -pr[k]; }
+                else { tr = -pi[k]; ti = pr[k]; }
+            } else {
+                constexpr cplx_d w = unit_root(DIR * k, L);
+                constexpr float wr = (float)w.re, wi = (float)w.im;
+                tr = wr * pr[k] - wi * pi[k];
+                ti = wr * pi[k] + wi * pr[k];
+            }
+            re[k] = er[k] + tr; im[k] = ei[k] + ti;
+            re[k + H] = er[k] - tr; im[k + H] = ei[k] - ti;
+        });
+    }
+}
+
+// ---------------------------------------------------------------- cross-lane helpers
+// Value held by the neighbouring lane (lane ^ 1): DPP quad_perm [1,0,3,2].
+__device__ __forceinline__ float lane_xor1(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+}
+
+// N = L*G point FFT over G lanes.  On entry lane g holds x[g + G*m] in register m; on exit
+// lane q holds X[k + L*q] in register k.  All G lanes of a group must be active together.
+template <int L, int G, int DIR>
+__device__ __forceinline__ void fft_group(float (&re)[L], float (&im)[L], int g) {
+    static_assert(G == 1 || G == 2, "one lane or a lane pair per line");
+    fft_leaf<L, DIR>(re, im);
+    if constexpr (G == 2) {
+        const float sgn = g ? -1.0f : 1.0f;
+        static_for<0, L>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            constexpr cplx_d w = unit_root(DIR * k, 2 * L);
+            constexpr float cr = (float)w.re, ci = (float)w.im;
+            const float wr = g ? cr : 1.0f, wi = g ? ci : 0.0f;
+            const float tr = wr * re[k] - wi * im[k];
+            const float ti = wr * im[k] + wi * re[k];
+            const float qr = lane_xor1(tr), qi = lane_xor1(ti);
+            re[k] = qr + sgn * tr;
+            im[k] = qi + sgn * ti;
+        });
+    }
+}
+
+// After a forward fft_group of z = a + i b (a, b real lines), split the spectrum into the
+// spectra of a and b (the standard two-for-one trick the paper cites in Section 5.2).
+// Result, with NH = L*G/2 "slots" per line, slot 0 holding the two real bins (X_0, X_{N/2})
+// as (re, im):
+//   G == 1: are/aim[k], bre/bim[k] for k < NH are slot k of a and of b.
+//   G == 2: lane 0 gets line a with slot k in register k; lane 1 gets line b with slot
+//           (k == 0 ? 0 : L - k) in register k.  Both are returned in are/aim.
+template <int L, int G>
+__device__ __forceinline__ void split_two_real(const float (&re)[L], const float (&im)[L], int g,
+                                               float (&are)[G == 1 ? L / 2 : L],
+                                               float (&aim)[G == 1 ? L / 2 : L],
+                                               float (&bre)[G == 1 ? L / 2 : 1],
+                                               float (&bim)[G == 1 ? L / 2 : 1]) {
+    if constexpr (G == 1) {
+        constexpr int NH = L / 2;
+        are[0] = re[0]; aim[0] = re[NH];
+        bre[0] = im[0]; bim[0] = im[NH];
+#pragma unroll
+        for (int k = 1; k < NH; ++k) {
+            const float xr = re[k], xi = im[k], yr = re[L - k], yi = im[L - k];
+            are[k] = 0.5f * (xr + yr); aim[k] = 0.5f * (xi - yi);
+            bre[k] = 0.5f * (xi + yi); bim[k] = 0.5f * (yr - xr);
+        }
+    } else {
+        // lane 0: own = Z[k], other = Z[N-k];  lane 1: own = Z[L+k], other = Z[L-k]
+        const float o0r = lane_xor1(re[0]), o0i = lane_xor1(im[0]);
+        are[0] = g ? o0i : re[0];
+        aim[0] = g ? im[0] : o0r;
+        static_for<1, L>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            const float orr = lane_xor1(re[L - k]), oi = lane_xor1(im[L - k]);
+            // lane 0: A[k]   = (own + conj(other)) / 2
+            // lane 1: B[L-k] = (other - conj(own)) / (2i)
+            const float a_r = 0.5f * (re[k] + orr), a_i = 0.5f * (im[k] - oi);
+            const float b_r = 0.5f * (oi + im[k]), b_i = 0.5f * (re[k] - orr);
+            are[k] = g ? b_r : a_r;
+            aim[k] = g ? b_i : a_i;
+        });
+        bre[0] = 0.f; bim[0] = 0.f;
+    }
+}
+
+}  // namespace fc

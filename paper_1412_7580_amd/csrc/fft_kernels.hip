@@ -1,0 +1,600 @@
+// Batched small real FFT kernels for gfx950: 2-D R2C, 2-D C2R with crop, 1-D R2C, 1-D C2R.
+//
+// What is computed: Section 5 of the fbfft paper (batched 1-D / 2-D FFTs of size 8..128 with
+// implicit zero padding by clipped loads, Hermitian-half output, two real lines packed into
+// one complex transform, n/2 instead of n/2+1 column transforms), and the clipped inverse of
+// Section 3.1.  How: one workgroup owns T consecutive planes; planes are staged through LDS
+// with coalesced global accesses, each lane (or lane pair) transforms a whole line in
+// registers (fft_core.hpp), and the row <-> column transpose is an LDS round trip.
+#include "fft_core.hpp"
+#include "kernels.hpp"
+
+namespace fc {
+
+// ------------------------------------------------------------------ small helpers
+struct MagicDiv {
+    unsigned long long m;   // ceil(2^32 / d); exact quotient for x * d < 2^32
+};
+static MagicDiv make_magic(unsigned d) { return MagicDiv{((1ull << 32) + d - 1) / d}; }
+__device__ __forceinline__ unsigned mdiv(unsigned x, MagicDiv md) {
+    return (unsigned)(((unsigned long long)x * md.m) >> 32);
+}
+
+static hipError_t allow_big_lds(const void *fn, size_t bytes) {
+    if (bytes <= 64 * 1024) return hipSuccess;
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+// ------------------------------------------------------------------ 2-D forward
+struct Fwd2dParams {
+    const float *in;
+    float *out;
+    long planes;
+    int h_in, w_in;
+    int RS, IPS;      // LDS row / plane stride of the staged input (floats, odd)
+    int MPS;          // LDS plane stride of the row-transformed data (float2, odd)
+    MagicDiv div_hw, div_w;
+    FreqLayout lay;
+    float im_sign;    // -1 to store the conjugate
+};
+
+// Store helpers for the two output layouts.
+template <int N, bool CONV>
+struct BinStore {
+    float *base;        // CONV: tile base + lane's plane offset; natural: plane base
+    int tsh;
+    float im_sign;
+    __device__ __forceinline__ void operator()(int k1, int k2, float re, float im) const {
+        constexpr int NB = N / 2 + 1;
+        if constexpr (CONV) {
+            float *q = base + ((size_t)((k1 * NB + k2) * 2) << tsh);
+            q[0] = re;
+            q[(size_t)1 << tsh] = im_sign * im;
+        } else {
+            reinterpret_cast<float2 *>(base)[k1 * NB + k2] = make_float2(re, im);
+        }
+    }
+};
+
+template <int L, int G, int T, bool CONV>
+__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dParams prm) {
+    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
+    constexpr int NA = (G == 1) ? NH : L;   // registers of split spectrum per lane
+    constexpr int NBR = (G == 1) ? NH : 1;
+    extern __shared__ float smem[];
+    float *sin = smem;
+    float2 *mid = reinterpret_cast<float2 *>(smem);
+
+    const int tid = threadIdx.x;
+    const long p0 = (long)blockIdx.x * T;
+    const int h_in = prm.h_in, w_in = prm.w_in, hw = h_in * w_in;
+    const long left = prm.planes - p0;
+    const int np = left < T ? (int)left : T;
+
+    // ---- stage the contiguous block of np planes into LDS (coalesced reads)
+    {
+        const float *src = prm.in + p0 * hw;
+        const unsigned total = (unsigned)np * hw;
+        for (unsigned e = tid; e < total; e += BT) {
+            const unsigned pl = mdiv(e, prm.div_hw);
+            const unsigned r = e - pl * hw;
+            const unsigned row = mdiv(r, prm.div_w);
+            const unsigned col = r - row * w_in;
+            sin[pl * prm.IPS + row * prm.RS + col] = src[e];
+        }
+    }
+    __syncthreads();
+
+    // ---- row phase: lane (pair) = (plane p, rows ra and rb packed as ra + i rb)
+    const int H2 = (h_in + 1) >> 1;
+    const int g = tid % G, p = (tid / G) % T, rp = tid / (G * T);
+    const bool row_active = rp < H2 && p < np;
+    const int ra = rp, rb = rp + H2;
+    const bool hasb = rb < h_in;
+    float are[NA], aim[NA], bre[NBR], bim[NBR];
+    if (row_active) {
+        float re[L], im[L];
+        const float *pa = sin + p * prm.IPS + ra * prm.RS;
+        const float *pb = sin + p * prm.IPS + rb * prm.RS;
+#pragma unroll
+        for (int m = 0; m < L; ++m) {
+            const int j = g + G * m;
+            const bool in = j < w_in;
+            re[m] = in ? pa[j] : 0.0f;
+            im[m] = (in && hasb) ? pb[j] : 0.0f;
+        }
+        fft_group<L, G, -1>(re, im, g);
+        split_two_real<L, G>(re, im, g, are, aim, bre, bim);
+    }
+    __syncthreads();   // every lane has read its rows; the staging area may be overwritten
+    if (row_active) {
+        float2 *mp = mid + p * prm.MPS;
+        if constexpr (G == 1) {
+#pragma unroll
+            for (int k = 0; k < NH; ++k) mp[ra * NH + k] = make_float2(are[k], aim[k]);
+            if (hasb) {
+#pragma unroll
+                for (int k = 0; k < NH; ++k) mp[rb * NH + k] = make_float2(bre[k], bim[k]);
+            }
+        } else {
+            const int row = g ? rb : ra;
+            if (!g || hasb) {
+#pragma unroll
+                for (int k = 0; k < L; ++k) {
+                    const int slot = (g && k) ? L - k : k;
+                    mp[row * NH + slot] = make_float2(are[k], aim[k]);
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- column phase: lane (pair) = (plane cp, column slot cc); slot 0 is the packed pair
+    //      of real columns k2 = 0 and k2 = N/2.
+    int cg, cp, cc;
+    if constexpr (CONV) { cg = tid % G; cp = (tid / G) % T; cc = tid / (G * T); }
+    else { cg = tid % G; cc = (tid / G) % NH; cp = tid / (G * NH); }
+    if (cp >= np) return;
+
+    float re[L], im[L];
+    {
+        const float2 *mp = mid + cp * prm.MPS + cc;
+#pragma unroll
+        for (int m = 0; m < L; ++m) {
+            const int r = cg + G * m;
+            float2 v = make_float2(0.f, 0.f);
+            if (r < h_in) v = mp[r * NH];
+            re[m] = v.x; im[m] = v.y;
+        }
+    }
+    fft_group<L, G, -1>(re, im, cg);
+
+    BinStore<N, CONV> st;
+    st.tsh = prm.lay.tsh;
+    st.im_sign = prm.im_sign;
+    if constexpr (CONV) st.base = prm.out + prm.lay.index(p0, 0, 0) + cp;
+    else st.base = prm.out + (size_t)(p0 + cp) * N * NB * 2;
+
+    if (cc != 0) {
+#pragma unroll
+        for (int k = 0; k < L; ++k) st(k + L * cg, cc, re[k], im[k]);
+    } else {
+        float ur[NA], ui[NA], vr[NBR], vi[NBR];
+        split_two_real<L, G>(re, im, cg, ur, ui, vr, vi);
+        if constexpr (G == 1) {
+            st(0, 0, ur[0], 0.f);  st(NH, 0, ui[0], 0.f);
+            st(0, NH, vr[0], 0.f); st(NH, NH, vi[0], 0.f);
+#pragma unroll
+            for (int k = 1; k < NH; ++k) {
+                st(k, 0, ur[k], ui[k]);  st(N - k, 0, ur[k], -ui[k]);
+                st(k, NH, vr[k], vi[k]); st(N - k, NH, vr[k], -vi[k]);
+            }
+        } else {
+            const int k2 = cg ? NH : 0;
+            st(0, k2, ur[0], 0.f);
+            st(L, k2, ui[0], 0.f);
+#pragma unroll
+            for (int k = 1; k < L; ++k) {
+                const int k1 = cg ? L - k : k;
+                st(k1, k2, ur[k], ui[k]);
+                st(N - k1, k2, ur[k], -ui[k]);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ 2-D inverse + crop
+struct Inv2dParams {
+    const float *in;
+    float *out;
+    long planes;
+    int h_out, w_out;
+    int MPS;          // LDS plane stride of the column-transformed data (float2, odd)
+    FreqLayout lay;
+    float scale;
+    int accumulate;
+};
+
+template <int L, int G, int T, bool CONV>
+__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dParams prm) {
+    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
+    extern __shared__ float smem[];
+    float2 *mid = reinterpret_cast<float2 *>(smem);
+    float *sout = smem;
+
+    const int tid = threadIdx.x;
+    const long p0 = (long)blockIdx.x * T;
+    const long left = prm.planes - p0;
+    const int np = left < T ? (int)left : T;
+    const int h_out = prm.h_out, w_out = prm.w_out;
+
+    // ---- column phase (inverse along k1) for column slot cc of plane cp
+    {
+        int cg, cp, cc;
+        if constexpr (CONV) { cg = tid % G; cp = (tid / G) % T; cc = tid / (G * T); }
+        else { cg = tid % G; cc = (tid / G) % NH; cp = tid / (G * NH); }
+        if (cp < np) {
+            float re[L], im[L];
+            if constexpr (CONV) {
+                const float *base = prm.in + prm.lay.index(p0, 0, 0) + cp;
+                const int tsh = prm.lay.tsh;
+#pragma unroll
+                for (int m = 0; m < L; ++m) {
+                    const int k1 = cg + G * m;
+                    const float *q = base + ((size_t)((k1 * NB + cc) * 2) << tsh);
+                    float xr = q[0], xi = q[(size_t)1 << tsh];
+                    if (cc == 0) {   // pack columns 0 and N/2:  z = y0 + i yN
+                        const float *qn = base + ((size_t)((k1 * NB + NH) * 2) << tsh);
+                        const float nr = qn[0], ni = qn[(size_t)1 << tsh];
+                        xr -= ni; xi += nr;
+                    }
+                    re[m] = xr; im[m] = xi;
+                }
+            } else {
+                const float2 *base = reinterpret_cast<const float2 *>(prm.in) + (size_t)(p0 + cp) * N * NB;
+#pragma unroll
+                for (int m = 0; m < L; ++m) {
+                    const int k1 = cg + G * m;
+                    float2 v = base[k1 * NB + cc];
+                    if (cc == 0) {
+                        const float2 u = base[k1 * NB + NH];
+                        v.x -= u.y; v.y += u.x;
+                    }
+                    re[m] = v.x; im[m] = v.y;
+                }
+            }
+            fft_group<L, G, +1>(re, im, cg);
+            float2 *mp = mid + cp * prm.MPS + cc;
+#pragma unroll
+            for (int k = 0; k < L; ++k) {
+                const int a = k + L * cg;
+                if (a < h_out) mp[a * NH] = make_float2(re[k], im[k]);
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- row phase (inverse along k2), rows ra and rb packed as ra + i rb
+    const int H2 = (h_out + 1) >> 1;
+    const int g = tid % G, p = (tid / G) % T, rp = tid / (G * T);
+    const bool active = rp < H2 && p < np;
+    const int ra = rp, rb = rp + H2;
+    const bool hasb = rb < h_out;
+    float re[L], im[L];
+    if (active) {
+        const float2 *A = mid + p * prm.MPS + ra * NH;
+        const float2 *B = mid + p * prm.MPS + rb * NH;
+#pragma unroll
+        for (int m = 0; m < L; ++m) {
+            const int k2 = g + G * m;
+            const int slot = (k2 == NH) ? 0 : (k2 < NH ? k2 : N - k2);
+            const float2 a = A[slot];
+            float2 b = make_float2(0.f, 0.f);
+            if (hasb) b = B[slot];
+            float xr, xi;
+            if (k2 == 0) { xr = a.x; xi = b.x; }
+            else if (k2 == NH) { xr = a.y; xi = b.y; }
+            else if (k2 < NH) { xr = a.x - b.y; xi = a.y + b.x; }
+            else { xr = a.x + b.y; xi = b.x - a.y; }
+            re[m] = xr; im[m] = xi;
+        }
+        fft_group<L, G, +1>(re, im, g);
+    }
+    __syncthreads();   // all reads of `mid` done; reuse the area as the output block
+    if (active) {
+        float *oa = sout + (p * h_out + ra) * w_out;
+        float *ob = sout + (p * h_out + rb) * w_out;
+#pragma unroll
+        for (int k = 0; k < L; ++k) {
+            const int b = k + L * g;
+            if (b < w_out) {
+                oa[b] = re[k] * prm.scale;
+                if (hasb) ob[b] = im[k] * prm.scale;
+            }
+        }
+    }
+    __syncthreads();
+    {
+        float *dst = prm.out + p0 * (long)h_out * w_out;
+        const unsigned total = (unsigned)np * h_out * w_out;
+        if (prm.accumulate) {
+            for (unsigned e = tid; e < total; e += BT) dst[e] += sout[e];
+        } else {
+            for (unsigned e = tid; e < total; e += BT) dst[e] = sout[e];
+        }
+    }
+}
+
+// ------------------------------------------------------------------ 1-D forward
+struct Fwd1dParams {
+    const float *in;
+    float *out;
+    long B;
+    int n_in, RS;
+    MagicDiv div_n;
+};
+
+template <int L, int G, int TB>
+__global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) {
+    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = TB / 2 * G;
+    constexpr int NA = (G == 1) ? NH : L;
+    constexpr int NBR = (G == 1) ? NH : 1;
+    extern __shared__ float smem[];
+    float *sin = smem;
+    float2 *sout = reinterpret_cast<float2 *>(smem);
+
+    const int tid = threadIdx.x;
+    const long b0 = (long)blockIdx.x * TB;
+    const long left = prm.B - b0;
+    const int nb = left < TB ? (int)left : TB;
+    const int n_in = prm.n_in;
+    {
+        const float *src = prm.in + b0 * n_in;
+        const unsigned total = (unsigned)nb * n_in;
+        for (unsigned e = tid; e < total; e += BT) {
+            const unsigned s = mdiv(e, prm.div_n);
+            sin[s * prm.RS + (e - s * n_in)] = src[e];
+        }
+    }
+    __syncthreads();
+    const int g = tid % G, pr = tid / G;
+    const int sa = 2 * pr, sb = 2 * pr + 1;
+    const bool active = sa < nb, hasb = sb < nb;
+    float are[NA], aim[NA], bre[NBR], bim[NBR];
+    if (active) {
+        float re[L], im[L];
+        const float *pa = sin + sa * prm.RS, *pb = sin + sb * prm.RS;
+#pragma unroll
+        for (int m = 0; m < L; ++m) {
+            const int j = g + G * m;
+            const bool in = j < n_in;
+            re[m] = in ? pa[j] : 0.f;
+            im[m] = (in && hasb) ? pb[j] : 0.f;
+        }
+        fft_group<L, G, -1>(re, im, g);
+        split_two_real<L, G>(re, im, g, are, aim, bre, bim);
+    }
+    __syncthreads();
+    if (active) {
+        if constexpr (G == 1) {
+            float2 *oa = sout + sa * NB, *ob = sout + sb * NB;
+            oa[0] = make_float2(are[0], 0.f); oa[NH] = make_float2(aim[0], 0.f);
+#pragma unroll
+            for (int k = 1; k < NH; ++k) oa[k] = make_float2(are[k], aim[k]);
+            if (hasb) {
+                ob[0] = make_float2(bre[0], 0.f); ob[NH] = make_float2(bim[0], 0.f);
+#pragma unroll
+                for (int k = 1; k < NH; ++k) ob[k] = make_float2(bre[k], bim[k]);
+            }
+        } else {
+            if (!g || hasb) {
+                float2 *o = sout + (g ? sb : sa) * NB;
+                o[0] = make_float2(are[0], 0.f); o[NH] = make_float2(aim[0], 0.f);
+#pragma unroll
+                for (int k = 1; k < L; ++k) o[g ? L - k : k] = make_float2(are[k], aim[k]);
+            }
+        }
+    }
+    __syncthreads();
+    {
+        float2 *dst = reinterpret_cast<float2 *>(prm.out) + b0 * NB;
+        const unsigned total = (unsigned)nb * NB;
+        for (unsigned e = tid; e < total; e += BT) dst[e] = sout[e];
+    }
+}
+
+// ------------------------------------------------------------------ 1-D inverse
+struct Inv1dParams {
+    const float *in;
+    float *out;
+    long B;
+    int n_out;
+    float scale;
+};
+
+template <int L, int G, int TB>
+__global__ void __launch_bounds__(TB / 2 * G) fft1d_c2r_kernel(Inv1dParams prm) {
+    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = TB / 2 * G;
+    extern __shared__ float smem[];
+    float2 *sin = reinterpret_cast<float2 *>(smem);
+    float *sout = smem;
+
+    const int tid = threadIdx.x;
+    const long b0 = (long)blockIdx.x * TB;
+    const long left = prm.B - b0;
+    const int nb = left < TB ? (int)left : TB;
+    const int n_out = prm.n_out;
+    {
+        const float2 *src = reinterpret_cast<const float2 *>(prm.in) + b0 * NB;
+        const unsigned total = (unsigned)nb * NB;
+        for (unsigned e = tid; e < total; e += BT) sin[e] = src[e];
+    }
+    __syncthreads();
+    const int g = tid % G, pr = tid / G;
+    const int sa = 2 * pr, sb = 2 * pr + 1;
+    const bool active = sa < nb, hasb = sb < nb;
+    float re[L], im[L];
+    if (active) {
+        const float2 *A = sin + sa * NB, *Bp = sin + sb * NB;
+#pragma unroll
+        for (int m = 0; m < L; ++m) {
+            const int k2 = g + G * m;
+            const int slot = k2 <= NH ? k2 : N - k2;
+            float2 a = A[slot];
+            float2 b = make_float2(0.f, 0.f);
+            if (hasb) b = Bp[slot];
+            if (k2 == 0 || k2 == NH) { a.y = 0.f; b.y = 0.f; }
+            else if (k2 > NH) { a.y = -a.y; b.y = -b.y; }
+            re[m] = a.x - b.y;
+            im[m] = a.y + b.x;
+        }
+        fft_group<L, G, +1>(re, im, g);
+    }
+    __syncthreads();
+    if (active) {
+        float *oa = sout + sa * n_out, *ob = sout + sb * n_out;
+#pragma unroll
+        for (int k = 0; k < L; ++k) {
+            const int b = k + L * g;
+            if (b < n_out) {
+                oa[b] = re[k] * prm.scale;
+                if (hasb) ob[b] = im[k] * prm.scale;
+            }
+        }
+    }
+    __syncthreads();
+    {
+        float *dst = prm.out + b0 * n_out;
+        const unsigned total = (unsigned)nb * n_out;
+        for (unsigned e = tid; e < total; e += BT) dst[e] = sout[e];
+    }
+}
+
+// ------------------------------------------------------------------ launchers
+int fft2d_tile_log2(int N) {
+    switch (N) {
+        case 8: return 6;
+        case 16: return 5;
+        case 32: return 4;
+        case 64: return 2;
+        case 128: return 0;
+        default: return -1;
+    }
+}
+
+template <int L, int G, int T>
+static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, int w_in,
+                            bool conv, bool conj, hipStream_t st) {
+    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+    Fwd2dParams prm;
+    prm.in = in; prm.out = out; prm.planes = planes; prm.h_in = h_in; prm.w_in = w_in;
+    prm.RS = w_in | 1;
+    prm.IPS = (h_in * prm.RS) | 1;
+    prm.MPS = (h_in * NH) | 1;
+    prm.div_hw = make_magic((unsigned)(h_in * w_in));
+    prm.div_w = make_magic((unsigned)w_in);
+    prm.lay.tsh = fft2d_tile_log2(N);
+    prm.lay.bins = N * (NH + 1);
+    prm.im_sign = conj ? -1.f : 1.f;
+    const size_t a = (size_t)T * prm.IPS * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
+    const size_t lds = a > b ? a : b;
+    const unsigned grid = (unsigned)((planes + T - 1) / T);
+    hipError_t e;
+    if (conv) {
+        auto k = fft2d_r2c_kernel<L, G, T, true>;
+        if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
+    } else {
+        auto k = fft2d_r2c_kernel<L, G, T, false>;
+        if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
+                            bool conv, bool conj, hipStream_t st) {
+    if (planes <= 0) return hipSuccess;
+    switch (N) {
+        case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, conj, st);
+        case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, conj, st);
+        case 32: return run_fwd2d<32, 1, 16>(in, out, planes, h_in, w_in, conv, conj, st);
+        case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, conj, st);
+        case 128: return run_fwd2d<64, 2, 1>(in, out, planes, h_in, w_in, conv, conj, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int L, int G, int T>
+static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out, int w_out,
+                            bool conv, float scale, bool accumulate, hipStream_t st) {
+    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+    Inv2dParams prm;
+    prm.in = in; prm.out = out; prm.planes = planes; prm.h_out = h_out; prm.w_out = w_out;
+    prm.MPS = (h_out * NH) | 1;
+    prm.lay.tsh = fft2d_tile_log2(N);
+    prm.lay.bins = N * (NH + 1);
+    prm.scale = scale; prm.accumulate = accumulate ? 1 : 0;
+    const size_t a = (size_t)T * prm.MPS * sizeof(float2), b = (size_t)T * h_out * w_out * sizeof(float);
+    const size_t lds = a > b ? a : b;
+    const unsigned grid = (unsigned)((planes + T - 1) / T);
+    hipError_t e;
+    if (conv) {
+        auto k = fft2d_c2r_kernel<L, G, T, true>;
+        if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
+    } else {
+        auto k = fft2d_c2r_kernel<L, G, T, false>;
+        if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
+        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int h_out, int w_out,
+                            bool conv, float scale, bool accumulate, hipStream_t st) {
+    if (planes <= 0) return hipSuccess;
+    switch (N) {
+        case 8: return run_inv2d<8, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 16: return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 32: return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 64: return run_inv2d<32, 2, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 128: return run_inv2d<64, 2, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int L, int G, int TB>
+static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, hipStream_t st) {
+    constexpr int N = L * G, NB = N / 2 + 1, BT = TB / 2 * G;
+    Fwd1dParams prm;
+    prm.in = in; prm.out = out; prm.B = B; prm.n_in = n_in; prm.RS = n_in | 1;
+    prm.div_n = make_magic((unsigned)n_in);
+    const size_t a = (size_t)TB * prm.RS * sizeof(float), b = (size_t)TB * NB * sizeof(float2);
+    const size_t lds = a > b ? a : b;
+    auto k = fft1d_r2c_kernel<L, G, TB>;
+    hipError_t e;
+    if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL(k, dim3((unsigned)((B + TB - 1) / TB)), dim3(BT), lds, st, prm);
+    return hipGetLastError();
+}
+
+hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, hipStream_t st) {
+    if (B <= 0) return hipSuccess;
+    switch (n) {
+        case 8: return run_fwd1d<8, 1, 512>(in, out, B, n_in, st);
+        case 16: return run_fwd1d<16, 1, 512>(in, out, B, n_in, st);
+        case 32: return run_fwd1d<32, 1, 256>(in, out, B, n_in, st);
+        case 64: return run_fwd1d<32, 2, 128>(in, out, B, n_in, st);
+        case 128: return run_fwd1d<64, 2, 64>(in, out, B, n_in, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int L, int G, int TB>
+static hipError_t run_inv1d(const float *in, float *out, long B, int n_out, hipStream_t st) {
+    constexpr int N = L * G, NB = N / 2 + 1, BT = TB / 2 * G;
+    Inv1dParams prm;
+    prm.in = in; prm.out = out; prm.B = B; prm.n_out = n_out; prm.scale = 1.0f / (float)N;
+    const size_t a = (size_t)TB * NB * sizeof(float2), b = (size_t)TB * n_out * sizeof(float);
+    const size_t lds = a > b ? a : b;
+    auto k = fft1d_c2r_kernel<L, G, TB>;
+    hipError_t e;
+    if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL(k, dim3((unsigned)((B + TB - 1) / TB)), dim3(BT), lds, st, prm);
+    return hipGetLastError();
+}
+
+hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, hipStream_t st) {
+    if (B <= 0) return hipSuccess;
+    switch (n) {
+        case 8: return run_inv1d<8, 1, 512>(in, out, B, n_out, st);
+        case 16: return run_inv1d<16, 1, 512>(in, out, B, n_out, st);
+        case 32: return run_inv1d<32, 1, 256>(in, out, B, n_out, st);
+        case 64: return run_inv1d<32, 2, 128>(in, out, B, n_out, st);
+        case 128: return run_inv1d<64, 2, 64>(in, out, B, n_out, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace fc

@@ -1,0 +1,57 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+namespace fc {
+
+// Private frequency-domain layout used between the FFT stages and the contraction
+// ("plane-tiled, bin-major, planar"):
+//     F[plane / T][bin][c][plane % T],   bin = k1 * (N/2+1) + k2,  c = 0 real, 1 imaginary
+// T (a power of two) is the number of consecutive planes one FFT workgroup transforms, so
+// every workgroup writes one contiguous block and, for one bin, a run of T floats.  The
+// contraction gathers such runs.  This plays the role of the paper's HWBD tensors of Table 1
+// without ever materialising the BDHW frequency tensors or the three transposes.
+struct FreqLayout {
+    int tsh;    // log2(T)
+    int bins;   // N * (N/2 + 1)
+    __host__ __device__ size_t index(long plane, int bin, int c) const {
+        const long pt = plane >> tsh;
+        const long pl = plane & ((1L << tsh) - 1);
+        return (size_t)((((pt * bins + bin) * 2 + c) << tsh) + pl);
+    }
+    size_t floats(long planes) const {
+        const long T = 1L << tsh;
+        return (size_t)((planes + T - 1) / T) * T * bins * 2;
+    }
+};
+
+// Planes per workgroup (= layout tile) of the 2-D kernels for basis N.
+int fft2d_tile_log2(int N);
+
+// 2-D R2C of `planes` planes [h_in x w_in] zero-padded to N x N.
+//   conv layout: out = FreqLayout buffer (tile = fft2d_tile_log2(N)); conj_out negates the
+//                imaginary parts on store (used where a pass needs the conjugate operand).
+//   natural layout: out = [planes][N][N/2+1][2].
+hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
+                            bool conv_layout, bool conj_out, hipStream_t st);
+
+// 2-D C2R + crop.  out[planes][h_out][w_out] = scale * real inverse (the caller folds 1/N^2
+// into `scale`), added to the previous contents when accumulate is set.
+hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int h_out, int w_out,
+                            bool conv_layout, float scale, bool accumulate, hipStream_t st);
+
+hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, hipStream_t st);
+hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, hipStream_t st);
+
+// Per-bin complex contraction  C[b](m,n) = sum_k A[b](m,k) * B[b](k,n)  over all bins.
+// Operand element (row r, col c) of X lives at plane  r * X_rs + c * X_cs  of its layout.
+struct GemmOperand {
+    const float *ptr;
+    FreqLayout lay;
+    long rs, cs;       // plane strides of the (row, col) indices
+};
+hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
+                             long C_cs, int M, int N, int K, int bins, hipStream_t st);
+
+}  // namespace fc

@@ -1,0 +1,148 @@
+"""Parity of fft_conv_fprop / bprop / accgrad against the time-domain oracle (GPU, C ABI).
+
+Bound: max|err| / max|ref| <= 1e-4 over the whole output tensor."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1412_7580_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def hd(lib):
+    h = lib.Handle(0)
+    yield h
+    h.close()
+
+
+def _relerr(got, ref):
+    return float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def _np(t):
+    return t.cpu().numpy().astype(np.float64)
+
+
+def _run_all(hd, cfg, seed, passes=("fprop", "bprop", "accgrad")):
+    x, w, gy = synth.conv_inputs(seed=seed, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    errs = {}
+    if "fprop" in passes:
+        errs["fprop"] = _relerr(_np(hd.fft_conv_fprop(dx, dw)), oracle.conv_fprop(x, w))
+    if "bprop" in passes:
+        errs["bprop"] = _relerr(_np(hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"])),
+                                oracle.conv_bprop(gy, w, cfg["h"], cfg["w"]))
+    if "accgrad" in passes:
+        errs["accgrad"] = _relerr(_np(hd.fft_conv_accgrad(dx, dgy)), oracle.conv_accgrad(x, gy))
+    return errs
+
+
+# Small shapes spanning every basis size, ragged plane counts (not multiples of the plane
+# tile or of the MFMA tile), rectangular inputs/kernels, kernel == input, 1x1 kernels.
+SMALL = [
+    dict(S=1, f=1, fo=1, h=5, w=5, kh=3, kw=3),
+    dict(S=2, f=3, fo=5, h=8, w=8, kh=3, kw=3),
+    dict(S=3, f=2, fo=4, h=7, w=6, kh=2, kw=4),
+    dict(S=5, f=7, fo=3, h=13, w=13, kh=3, kw=3),
+    dict(S=2, f=33, fo=35, h=16, w=16, kh=5, kw=5),
+    dict(S=34, f=5, fo=6, h=12, w=9, kh=12, kw=9),
+    dict(S=4, f=6, fo=5, h=27, w=27, kh=5, kw=5),
+    dict(S=3, f=5, fo=2, h=32, w=20, kh=1, kw=1),
+    dict(S=2, f=3, fo=4, h=33, w=40, kh=7, kw=3),
+    dict(S=3, f=2, fo=3, h=64, w=64, kh=31, kw=31),
+    dict(S=2, f=2, fo=2, h=100, w=128, kh=9, kw=11),
+    dict(S=70, f=40, fo=72, h=9, w=9, kh=3, kw=3),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=lambda c: "S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c))
+def test_small_shapes(hd, cfg):
+    errs = _run_all(hd, cfg, seed=100)
+    for k, e in errs.items():
+        assert e <= TOL, (k, e)
+
+
+def test_config_c1_fprop(hd):
+    cfg = synth.CONV_CONFIGS["C1"]
+    errs = _run_all(hd, cfg, seed=synth.CONV_SEEDS["C1"], passes=cfg["passes"])
+    assert errs["fprop"] <= TOL
+
+
+@pytest.mark.parametrize("name", ["C2", "C3"])
+def test_config_full_tensor(hd, name):
+    cfg = synth.CONV_CONFIGS[name]
+    errs = _run_all(hd, cfg, seed=synth.CONV_SEEDS[name])
+    for k, e in errs.items():
+        assert e <= TOL, (name, k, e)
+
+
+def test_config_c4_sampled_planes(hd):
+    """Large-kernel layer at full size; the oracle evaluates a seeded sample of output planes
+    (all pixels of each), the GPU computes everything in the benchmark's launch configuration."""
+    cfg = synth.CONV_CONFIGS["C4"]
+    seed = synth.CONV_SEEDS["C4"]
+    x, w, gy = synth.conv_inputs(seed=seed, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    S, f, fo, h, wd = cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"]
+    rng = np.random.default_rng(7)
+    sel = np.unique(np.concatenate([[0, S * fo - 1], rng.integers(0, S * fo, 46)]))
+    y = _np(hd.fft_conv_fprop(dx, dw)).reshape(S * fo, *[cfg["h"] - cfg["kh"] + 1] * 2)
+    ref = oracle.conv_fprop(x, w, sel)
+    assert np.max(np.abs(y[sel] - ref)) / np.max(np.abs(ref)) <= TOL
+    sel = np.unique(np.concatenate([[0, S * f - 1], rng.integers(0, S * f, 46)]))
+    gx = _np(hd.fft_conv_bprop(dgy, dw, h, wd)).reshape(S * f, h, wd)
+    ref = oracle.conv_bprop(gy, w, h, wd, sel)
+    assert np.max(np.abs(gx[sel] - ref)) / np.max(np.abs(ref)) <= TOL
+    sel = np.unique(np.concatenate([[0, fo * f - 1], rng.integers(0, fo * f, 200)]))
+    gw = _np(hd.fft_conv_accgrad(dx, dgy)).reshape(fo * f, cfg["kh"], cfg["kw"])
+    ref = oracle.conv_accgrad(x, gy, sel)
+    assert np.max(np.abs(gw[sel] - ref)) / np.max(np.abs(ref)) <= TOL
+
+
+def test_accgrad_scale_and_accumulate(hd):
+    cfg = dict(S=4, f=3, fo=5, h=10, w=10, kh=3, kw=3)
+    x, w, gy = synth.conv_inputs(seed=101, **cfg)
+    ref = oracle.conv_accgrad(x, gy)
+    gw0 = synth.uniform_pm1(102, 0, w.shape)
+    g = _dev(gw0)
+    hd.fft_conv_accgrad(_dev(x), _dev(gy), gw=g, scale=0.25, accumulate=True)
+    assert _relerr(_np(g), gw0.astype(np.float64) + 0.25 * ref) <= TOL
+    g = _dev(gw0)
+    hd.fft_conv_accgrad(_dev(x), _dev(gy), gw=g, scale=-2.0, accumulate=False)
+    assert _relerr(_np(g), -2.0 * ref) <= TOL
+
+
+def test_caller_workspace_and_errors(hd, lib):
+    import torch
+    cfg = dict(S=2, f=3, fo=4, h=9, w=9, kh=3, kw=3)
+    x, w, gy = synth.conv_inputs(seed=103, **cfg)
+    need = hd.workspace_bytes(lib.FPROP, 2, 3, 4, 9, 9, 3, 3)
+    assert need > 0
+    ws = torch.empty(need // 4, device="cuda", dtype=torch.float32)
+    y = hd.fft_conv_fprop(_dev(x), _dev(w), ws=ws)
+    assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
+    with pytest.raises(lib.FFTConvError, match="workspace too small"):
+        hd.fft_conv_fprop(_dev(x), _dev(w), ws=ws[: need // 8])
+    with pytest.raises(lib.FFTConvError, match="unsupported"):
+        hd.fft_conv_fprop(torch.zeros((1, 1, 130, 130), device="cuda"), torch.zeros((1, 1, 3, 3), device="cuda"))
+    with pytest.raises(lib.FFTConvError, match="invalid"):
+        hd.fft_conv_fprop(torch.zeros((1, 1, 4, 4), device="cuda"), torch.zeros((1, 1, 5, 5), device="cuda"),
+                          y=torch.zeros((1, 1, 1, 1), device="cuda"))
+
+
+def test_repeat_calls_are_deterministic(hd):
+    import torch
+    cfg = synth.CONV_CONFIGS["C1"]
+    x, w, _ = synth.conv_inputs(seed=0, **cfg)
+    dx, dw = _dev(x), _dev(w)
+    a = hd.fft_conv_fprop(dx, dw).clone()
+    b = hd.fft_conv_fprop(dx, dw)
+    assert torch.equal(a, b)
