@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the frequency-domain convolution hot path on one MI355X.
+
+One step = fprop + bprop + accGrad of the headline layer (S=128, f=f'=64, 27x27 input,
+5x5 kernel, 32x32 Fourier basis), i.e. twelve kernel launches: for each pass the FFT of
+both operands, the per-bin complex contraction and the inverse FFT with crop.  Inputs are
+seeded synthetic fp32 tensors already resident in device memory.
+
+Prints ONE JSON line: effective TFLOP/s (direct-convolution FLOP count over measured time),
+the roofline of the dominant kernel (durations from HIP events recorded by the library on its
+own stream around each stage), and the fp64 CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
+
+STAGES = ("fft_a", "fft_b", "contraction", "ifft")
+
+
+def stage_model(cfg, pass_name):
+    """Algorithmic bytes (FFT stages) and executed flops (contraction) of one pass."""
+    S, f, fo, h, w, kh, kw, N = (cfg[k] for k in ("S", "f", "fo", "h", "w", "kh", "kw", "N"))
+    oh, ow = h - kh + 1, w - kw + 1
+    bins = N * (N // 2 + 1)
+    x = (S * f, h, w); wt = (fo * f, kh, kw); gy = (S * fo, oh, ow)
+    if pass_name == "fprop":
+        A, B, C, (M, Nn, K) = x, wt, gy, (S, fo, f)
+    elif pass_name == "bprop":
+        A, B, C, (M, Nn, K) = gy, wt, x, (S, f, fo)
+    else:
+        A, B, C, (M, Nn, K) = gy, x, wt, (fo, f, S)
+    fwd = lambda t: t[0] * (4 * t[1] * t[2] + 8 * bins)
+    return {
+        "fft_a": {"bytes": fwd(A)},
+        "fft_b": {"bytes": fwd(B)},
+        "contraction": {"flops": 8 * M * Nn * K * bins,
+                        "bytes": 8 * bins * (A[0] + B[0] + C[0])},
+        "ifft": {"bytes": C[0] * (8 * bins + 4 * C[1] * C[2])},
+    }
+
+
+def direct_flops(cfg):
+    S, f, fo, h, w, kh, kw = (cfg[k] for k in ("S", "f", "fo", "h", "w", "kh", "kw"))
+    return 2 * S * f * fo * kh * kw * (h - kh + 1) * (w - kw + 1)
+
+
+def run_step(hd, t, cfg, passes):
+    if "fprop" in passes:
+        hd.fft_conv_fprop(t["x"], t["w"], y=t["y"])
+    if "bprop" in passes:
+        hd.fft_conv_bprop(t["gy"], t["w"], cfg["h"], cfg["w"], gx=t["gx"])
+    if "accgrad" in passes:
+        hd.fft_conv_accgrad(t["x"], t["gy"], gw=t["gw"])
+
+
+def device_tensors(cfg, seed):
+    import torch
+    from paper_1412_7580_amd import synth
+    x, w, gy = synth.conv_inputs(seed=seed, **cfg)
+    t = {"x": torch.from_numpy(x).cuda(), "w": torch.from_numpy(w).cuda(), "gy": torch.from_numpy(gy).cuda()}
+    t["y"] = torch.empty_like(t["gy"]); t["gx"] = torch.empty_like(t["x"]); t["gw"] = torch.empty_like(t["w"])
+    return t, (x, w, gy)
+
+
+def time_steps(hd, t, cfg, passes, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        run_step(hd, t, cfg, passes)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_step(hd, t, cfg, passes)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def profile_stages(hd, t, cfg, passes, steps):
+    """Average duration (ms) of each stage of each pass over `steps` repetitions of the timed
+    region, from the HIP events the library records on its stream around every launch."""
+    import torch
+    hd.set_profiling(True)
+    acc = {p: [0.0] * 4 for p in passes}
+    for _ in range(steps):
+        for p in passes:
+            run_step(hd, t, cfg, (p,))
+            ms = hd.last_stage_ms()
+            for i in range(4):
+                acc[p][i] += ms[i]
+    hd.set_profiling(False)
+    torch.cuda.synchronize()
+    return {p: [v / steps for v in acc[p]] for p in passes}
+
+
+def cpu_baseline(cfg, host_inputs, budget_s=12.0):
+    """fp64 oracle on a bounded sample of output planes of each pass, scaled to TFLOP/s."""
+    import numpy as np
+    import oracle
+    x, w, gy = host_inputs
+    S, f, fo = cfg["S"], cfg["f"], cfg["fo"]
+    per_pass = direct_flops(cfg)
+    rng = np.random.default_rng(0)
+    done_flops, spent, parts = 0.0, 0.0, []
+    for name, nplanes in (("fprop", S * fo), ("bprop", S * f), ("accgrad", fo * f)):
+        k = max(8, min(nplanes, nplanes // 16))
+        while True:
+            sel = np.sort(rng.choice(nplanes, size=k, replace=False))
+            t0 = time.perf_counter()
+            if name == "fprop":
+                oracle.conv_fprop(x, w, sel)
+            elif name == "bprop":
+                oracle.conv_bprop(gy, w, cfg["h"], cfg["w"], sel)
+            else:
+                oracle.conv_accgrad(x, gy, sel)
+            dt = time.perf_counter() - t0
+            if dt >= budget_s / 6 or k == nplanes:
+                break
+            k = min(nplanes, max(k * 2, int(k * (budget_s / 4) / max(dt, 1e-3))))
+        done_flops += per_pass * k / nplanes
+        spent += dt
+        parts.append(f"{name}: {k}/{nplanes} planes in {dt:.2f}s")
+    return {"value": done_flops / spent / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": "fp64 direct convolution, seeded sample of output planes; " + "; ".join(parts)}
+
+
+def fft_sweep(hd, max_bytes=1 << 28, reps=3):
+    """Stand-alone FFT sweep: R2C then C2R, input sized to 256 MiB, algorithmic GB/s."""
+    import torch
+    from paper_1412_7580_amd import synth
+    out = {}
+    for dim in (1, 2):
+        for n in synth.FFT_SWEEP_SIZES:
+            B = synth.fft_sweep_batch(dim, n, max_bytes)
+            ni = n - 3
+            shape = (B, ni) if dim == 1 else (B, ni, ni)
+            x = torch.randn(shape, device="cuda", dtype=torch.float32)
+            nbins = (n // 2 + 1) * (1 if dim == 1 else n)
+            X = torch.empty((B, n // 2 + 1, 2) if dim == 1 else (B, n, n // 2 + 1, 2), device="cuda")
+            y = torch.empty_like(x)
+            fwd = (lambda: hd.fft_r2c_1d(x, n, out=X)) if dim == 1 else (lambda: hd.fft_r2c_2d(x, n, out=X))
+            inv = (lambda: hd.fft_c2r_1d(X, n, ni, out=y)) if dim == 1 else (lambda: hd.fft_c2r_2d(X, n, ni, ni, out=y))
+            res = {}
+            for name, fn in (("r2c", fwd), ("c2r", inv)):
+                fn(); torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record(); torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                byts = B * (4 * ni ** dim + 8 * nbins)
+                res[name] = {"ms": round(ms, 4), "GBps": round(byts / ms / 1e6, 1)}
+            out[f"{dim}d_n{n}"] = res
+            del x, X, y
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the FFT sweep")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU; run with --gpus 1 (value is one GPU's throughput)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    import paper_1412_7580_amd as pkg
+    from paper_1412_7580_amd import synth
+
+    hd = pkg.Handle(0)
+    name = args.workload
+    cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k != "passes"}
+    passes = synth.CONV_CONFIGS[name]["passes"]
+    t, host = device_tensors(cfg, synth.CONV_SEEDS[name])
+
+    sec = time_steps(hd, t, cfg, passes, args.steps, args.warmup)
+    flops = direct_flops(cfg) * len(passes)
+    value = flops / sec / 1e12
+
+    # Per-kernel durations over a second run of the same region, with the library's events on.
+    prof_steps = max(1, min(args.steps, 50))
+    stage_ms = profile_stages(hd, t, cfg, passes, prof_steps)
+    kernels = {}
+    for p in passes:
+        model = stage_model(cfg, p)
+        for i, s in enumerate(STAGES):
+            ms = stage_ms[p][i]
+            ent = {"ms": round(ms, 5)}
+            if s == "contraction":
+                ent["TFLOPs"] = round(model[s]["flops"] / ms / 1e9, 2)
+                ent["GBps"] = round(model[s]["bytes"] / ms / 1e6, 1)
+            else:
+                ent["GBps"] = round(model[s]["bytes"] / ms / 1e6, 1)
+            kernels[f"{p}.{s}"] = ent
+    dom = max(kernels, key=lambda k: kernels[k]["ms"])
+    dp, ds = dom.split(".")
+    model = stage_model(cfg, dp)[ds]
+    dms = kernels[dom]["ms"]
+    if ds == "contraction":
+        ach = model["flops"] / dms / 1e9
+        roof = {"kernel": dom + " (cgemm_bins_kernel)", "bound": "mfma", "achieved": round(ach, 2),
+                "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
+                "traffic": None}
+    else:
+        ach = model["bytes"] / dms / 1e6
+        kn = "fft2d_c2r_kernel" if ds == "ifft" else "fft2d_r2c_kernel"
+        roof = {"kernel": f"{dom} ({kn})", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+    roof["avg_launch_ms"] = dms
+    roof["launches_averaged"] = prof_steps
+
+    out = {
+        "metric": "effective conv TFLOP/s (direct-conv FLOPs), fprop+bprop+accGrad",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{name}: S={cfg['S']} f={cfg['f']} f'={cfg['fo']} input {cfg['h']}x{cfg['w']} "
+                               f"kernel {cfg['kh']}x{cfg['kw']} FFT {cfg['N']}x{cfg['N']}, passes " + "+".join(passes),
+                   "seed": synth.CONV_SEEDS[name]},
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, host)
+    if not args.no_extra:
+        extra = {}
+        for other in ("C1", "C3", "C4"):
+            if other == name:
+                continue
+            del t
+            torch.cuda.empty_cache()
+            ocfg = {k: v for k, v in synth.CONV_CONFIGS[other].items() if k != "passes"}
+            opasses = synth.CONV_CONFIGS[other]["passes"]
+            t, _ = device_tensors(ocfg, synth.CONV_SEEDS[other])
+            n = 20 if other == "C4" else 50
+            s = time_steps(hd, t, ocfg, opasses, n, 5)
+            sm = profile_stages(hd, t, ocfg, opasses, 5)
+            extra[other] = {"ms_per_step": round(s * 1e3, 4),
+                            "effective_TFLOPs": round(direct_flops(ocfg) * len(opasses) / s / 1e12, 2),
+                            "stage_ms": {p: [round(v, 4) for v in sm[p]] for p in opasses}}
+        del t
+        torch.cuda.empty_cache()
+        extra["fft_sweep_256MiB"] = fft_sweep(hd)
+        out["extra"] = extra
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

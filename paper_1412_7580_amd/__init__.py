@@ -33,6 +33,9 @@ def load_library():
     if not os.path.exists(_LIBPATH):
         from . import build as _build
         _build.build(force=True)
+    # torch ships its own HIP runtime; import it first so that the library binds to the same
+    # runtime instance that owns the tensors and streams it is handed.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIBPATH)
     vp, i, l, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
     lib.fftconv_create.argtypes = [ctypes.POINTER(vp), i]
