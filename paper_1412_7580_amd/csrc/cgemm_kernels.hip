@@ -7,7 +7,16 @@
 //     Cr += Ar*Br + (-Ai)*Bi ,   Ci += Ar*Bi + Ai*Br
 // Operands are gathered straight from the FFT kernels' plane-tiled layout (kernels.hpp), so
 // the three explicit transposes of the paper's pipeline never exist.
+//
+// Workgroup = 4 waves (WGM x WGN), each wave owns FM x FN MFMA tiles of 32x32 (re and im
+// accumulators).  K is walked in tiles of TK through a double-buffered LDS image
+// As[c][k][m], Bs[c][k][n]; the next tile's global loads are in flight while the current
+// one is multiplied.  Bins are dealt to the 8 XCDs in contiguous chunks (workgroup i runs
+// on XCD i % 8), so that the tiles of one bin, and neighbouring bins that share cache
+// lines in the plane-tiled layout, meet in the same L2.
 #include "kernels.hpp"
+
+#include <cstdlib>
 
 namespace fc {
 
@@ -20,28 +29,113 @@ struct GemmParams {
     long a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;
     int M, N, K, bins;
     int tiles_m, tiles_n;
-    int a_kfast, b_kfast;   // which index is contiguous in planes (coalescing of the gather)
 };
 
-constexpr int GEMM_TK = 16;
-constexpr int GEMM_PAD = 4;
+constexpr int kXcds = 8;
 
-// Workgroup = 4 waves arranged WGM x WGN; each wave owns FM x FN MFMA tiles of 32x32.
-template <int WGM, int WGN, int FM, int FN>
-__global__ void __launch_bounds__(256) cgemm_bins_kernel(GemmParams prm) {
-    static_assert(WGM * WGN == 4, "four waves per workgroup");
-    constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32, TK = GEMM_TK;
-    constexpr int SA = TM + GEMM_PAD, SB = TN + GEMM_PAD;
-    constexpr int EA = TM * TK / 256, EB = TN * TK / 256;
-    __shared__ float As[2][TK][SA];
-    __shared__ float Bs[2][TK][SB];
+// Loader of one operand tile (ROWS x TK) with the "row" index being m (or n) and the
+// reduction index k.  KF: k is the contiguous plane index (else the row index is).
+// VEC: 16-byte gathers (needs plane runs of >= 4, aligned starts and extents).
+template <int ROWS, int TK, int STRIDE, bool KF, bool VEC, int NT>
+struct TileLoader {
+    static constexpr int NV = VEC ? (ROWS * TK / 4 + NT - 1) / NT : (ROWS * TK + NT - 1) / NT;
+    float4 vr[VEC ? NV : 1], vi[VEC ? NV : 1];
+    float sr[VEC ? 1 : NV], si[VEC ? 1 : NV];
+
+    __device__ __forceinline__ void load(const float *base, const FreqLayout &lay, long rs, long cs,
+                                         int bin, int r0, int k0, int R, int K, int tid) {
+        const size_t im_off = (size_t)1 << lay.tsh;
+        if constexpr (VEC) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int v = tid + i * NT;
+                int rr, kk;
+                if constexpr (KF) { kk = (v % (TK / 4)) * 4; rr = v / (TK / 4); }
+                else { rr = (v % (ROWS / 4)) * 4; kk = v / (ROWS / 4); }
+                vr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                vi[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (v < ROWS * TK / 4 && r0 + rr < R && k0 + kk < K) {
+                    const size_t idx = lay.index((r0 + rr) * rs + (k0 + kk) * cs, bin, 0);
+                    vr[i] = *reinterpret_cast<const float4 *>(base + idx);
+                    vi[i] = *reinterpret_cast<const float4 *>(base + idx + im_off);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int e = tid + i * NT;
+                int rr, kk;
+                if constexpr (KF) { kk = e % TK; rr = e / TK; }
+                else { rr = e % ROWS; kk = e / ROWS; }
+                sr[i] = 0.f; si[i] = 0.f;
+                if (e < ROWS * TK && r0 + rr < R && k0 + kk < K) {
+                    const size_t idx = lay.index((r0 + rr) * rs + (k0 + kk) * cs, bin, 0);
+                    sr[i] = base[idx];
+                    si[i] = base[idx + im_off];
+                }
+            }
+        }
+    }
+
+    // LDS image: dst[c][k][row], row stride STRIDE, component stride TK*STRIDE.
+    __device__ __forceinline__ void store(float *dst, int tid) const {
+        float *d0 = dst, *d1 = dst + TK * STRIDE;
+        if constexpr (VEC) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int v = tid + i * NT;
+                if (v < ROWS * TK / 4) {
+                    if constexpr (KF) {
+                        const int kk = (v % (TK / 4)) * 4, rr = v / (TK / 4);
+                        d0[(kk + 0) * STRIDE + rr] = vr[i].x; d0[(kk + 1) * STRIDE + rr] = vr[i].y;
+                        d0[(kk + 2) * STRIDE + rr] = vr[i].z; d0[(kk + 3) * STRIDE + rr] = vr[i].w;
+                        d1[(kk + 0) * STRIDE + rr] = vi[i].x; d1[(kk + 1) * STRIDE + rr] = vi[i].y;
+                        d1[(kk + 2) * STRIDE + rr] = vi[i].z; d1[(kk + 3) * STRIDE + rr] = vi[i].w;
+                    } else {
+                        const int rr = (v % (ROWS / 4)) * 4, kk = v / (ROWS / 4);
+                        float2 *q0 = reinterpret_cast<float2 *>(d0 + kk * STRIDE + rr);
+                        float2 *q1 = reinterpret_cast<float2 *>(d1 + kk * STRIDE + rr);
+                        q0[0] = make_float2(vr[i].x, vr[i].y); q0[1] = make_float2(vr[i].z, vr[i].w);
+                        q1[0] = make_float2(vi[i].x, vi[i].y); q1[1] = make_float2(vi[i].z, vi[i].w);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int e = tid + i * NT;
+                if (e < ROWS * TK) {
+                    int rr, kk;
+                    if constexpr (KF) { kk = e % TK; rr = e / TK; }
+                    else { rr = e % ROWS; kk = e / ROWS; }
+                    d0[kk * STRIDE + rr] = sr[i];
+                    d1[kk * STRIDE + rr] = si[i];
+                }
+            }
+        }
+    }
+};
+
+template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int NBUF>
+__global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmParams prm) {
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32;
+    constexpr int SA = TM + 2, SB = TN + 2;        // +2: conflict-free transposing stores
+    constexpr int ABUF = 2 * TK * SA, BBUF = 2 * TK * SB;
+    extern __shared__ float smem[];
+    float *As = smem;                 // [2 buffers][2 comps][TK][SA]
+    float *Bs = smem + NBUF * ABUF;   // [NBUF buffers][2 comps][TK][SB]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    int bid = blockIdx.x;
-    const int tn = bid % prm.tiles_n; bid /= prm.tiles_n;
-    const int tm = bid % prm.tiles_m;
-    const int bin = bid / prm.tiles_m;
+
+    // XCD-aware decomposition of the flat workgroup index (see file header).
+    const int tiles = prm.tiles_m * prm.tiles_n;
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int bins_per_xcd = prm.bins / kXcds;
+    const int bin = xcd * bins_per_xcd + slot / tiles;
+    const int tile = slot % tiles;
+    const int tm = tile / prm.tiles_n, tn = tile % prm.tiles_n;
     const int m0 = tm * TM, n0 = tn * TN;
     const int M = prm.M, N = prm.N, K = prm.K;
 
@@ -53,79 +147,39 @@ __global__ void __launch_bounds__(256) cgemm_bins_kernel(GemmParams prm) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) { acc_re[i][j][v] = 0.f; acc_im[i][j][v] = 0.f; }
 
-    float ra_re[EA], ra_im[EA], rb_re[EB], rb_im[EB];
-
-    auto load_tiles = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < EA; ++i) {
-            const int e = tid + i * 256;
-            int mm, kk;
-            if (prm.a_kfast) { kk = e % TK; mm = e / TK; } else { mm = e % TM; kk = e / TM; }
-            const int m = m0 + mm, k = k0 + kk;
-            float xr = 0.f, xi = 0.f;
-            if (m < M && k < K) {
-                const size_t idx = prm.layA.index(m * prm.a_rs + k * prm.a_cs, bin, 0);
-                xr = prm.A[idx];
-                xi = prm.A[idx + ((size_t)1 << prm.layA.tsh)];
-            }
-            ra_re[i] = xr; ra_im[i] = xi;
-        }
-#pragma unroll
-        for (int i = 0; i < EB; ++i) {
-            const int e = tid + i * 256;
-            int nn, kk;
-            if (prm.b_kfast) { kk = e % TK; nn = e / TK; } else { nn = e % TN; kk = e / TN; }
-            const int n = n0 + nn, k = k0 + kk;
-            float xr = 0.f, xi = 0.f;
-            if (n < N && k < K) {
-                const size_t idx = prm.layB.index(k * prm.b_rs + n * prm.b_cs, bin, 0);
-                xr = prm.B[idx];
-                xi = prm.B[idx + ((size_t)1 << prm.layB.tsh)];
-            }
-            rb_re[i] = xr; rb_im[i] = xi;
-        }
-    };
-    auto store_tiles = [&]() {
-#pragma unroll
-        for (int i = 0; i < EA; ++i) {
-            const int e = tid + i * 256;
-            int mm, kk;
-            if (prm.a_kfast) { kk = e % TK; mm = e / TK; } else { mm = e % TM; kk = e / TM; }
-            As[0][kk][mm] = ra_re[i];
-            As[1][kk][mm] = ra_im[i];
-        }
-#pragma unroll
-        for (int i = 0; i < EB; ++i) {
-            const int e = tid + i * 256;
-            int nn, kk;
-            if (prm.b_kfast) { kk = e % TK; nn = e / TK; } else { nn = e % TN; kk = e / TN; }
-            Bs[0][kk][nn] = rb_re[i];
-            Bs[1][kk][nn] = rb_im[i];
-        }
-    };
+    TileLoader<TM, TK, SA, AKF, VEC, NT> la;
+    TileLoader<TN, TK, SB, BKF, VEC, NT> lb;
 
     const int nkt = (K + TK - 1) / TK;
-    load_tiles(0);
-    store_tiles();
+    la.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, 0, M, K, tid);
+    // B(k, n): row index of the loader is n, so swap the strides
+    lb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, 0, N, K, tid);
+    la.store(As, tid);
+    lb.store(Bs, tid);
     __syncthreads();
+
     const int lrow = lane & 31, lk = lane >> 5;
     for (int kt = 0; kt < nkt; ++kt) {
-        if (kt + 1 < nkt) load_tiles((kt + 1) * TK);
+        const int cur = (NBUF == 2) ? (kt & 1) : 0;
+        if (kt + 1 < nkt) {
+            la.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, (kt + 1) * TK, M, K, tid);
+            lb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, (kt + 1) * TK, N, K, tid);
+        }
+        const float *a0 = As + cur * ABUF + (wm * FM * 32 + lrow);
+        const float *b0 = Bs + cur * BBUF + (wn * FN * 32 + lrow);
 #pragma unroll
         for (int ks = 0; ks < TK; ks += 2) {
             float a_re[FM], a_im[FM], a_in[FM], b_re[FN], b_im[FN];
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
-                const int mm = (wm * FM + i) * 32 + lrow;
-                a_re[i] = As[0][ks + lk][mm];
-                a_im[i] = As[1][ks + lk][mm];
+                a_re[i] = a0[(ks + lk) * SA + i * 32];
+                a_im[i] = a0[TK * SA + (ks + lk) * SA + i * 32];
                 a_in[i] = -a_im[i];
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
-                const int nn = (wn * FN + j) * 32 + lrow;
-                b_re[j] = Bs[0][ks + lk][nn];
-                b_im[j] = Bs[1][ks + lk][nn];
+                b_re[j] = b0[(ks + lk) * SB + j * 32];
+                b_im[j] = b0[TK * SB + (ks + lk) * SB + j * 32];
             }
 #pragma unroll
             for (int i = 0; i < FM; ++i)
@@ -137,10 +191,18 @@ __global__ void __launch_bounds__(256) cgemm_bins_kernel(GemmParams prm) {
                     acc_im[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im[i], b_re[j], acc_im[i][j], 0, 0, 0);
                 }
         }
-        __syncthreads();
         if (kt + 1 < nkt) {
-            store_tiles();
-            __syncthreads();
+            if constexpr (NBUF == 2) {
+                // the other buffer was last read in iteration kt-1, which every wave has left
+                la.store(As + (cur ^ 1) * ABUF, tid);
+                lb.store(Bs + (cur ^ 1) * BBUF, tid);
+                __syncthreads();
+            } else {
+                __syncthreads();
+                la.store(As, tid);
+                lb.store(Bs, tid);
+                __syncthreads();
+            }
         }
     }
 
@@ -163,32 +225,86 @@ __global__ void __launch_bounds__(256) cgemm_bins_kernel(GemmParams prm) {
         }
 }
 
-template <int WGM, int WGN, int FM, int FN>
+template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int NBUF = 2>
 static hipError_t run_gemm(GemmParams prm, hipStream_t st) {
     constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32;
     prm.tiles_m = (prm.M + TM - 1) / TM;
     prm.tiles_n = (prm.N + TN - 1) / TN;
     const long grid = (long)prm.bins * prm.tiles_m * prm.tiles_n;
-    hipLaunchKernelGGL((cgemm_bins_kernel<WGM, WGN, FM, FN>), dim3((unsigned)grid), dim3(256), 0, st, prm);
+    const size_t lds = (size_t)(NBUF * 2 * TK * (TM + 2) + NBUF * 2 * TK * (TN + 2)) * sizeof(float);
+    auto k = cgemm_bins_kernel<WGM, WGN, FM, FN, TK, AKF, BKF, VEC, MINB, NBUF>;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, st, prm);
     return hipGetLastError();
+}
+
+// Tile shapes (M x N, waves): 0 128x128/4, 1 64x128/4, 2 128x64/4, 3 64x64/4, 4 32x128/4,
+// 5 32x64/2, 6 64x32/2, 7 32x32/1, 8 64x64/4 with TK 32, 9 64x64/2, 10 64x128/8, 11 128x64/8,
+// 12 128x128/8.
+template <bool AKF, bool BKF, bool VEC>
+static hipError_t dispatch_tile(int shape, GemmParams prm, hipStream_t st) {
+    switch (shape) {
+        case 0: return run_gemm<2, 2, 2, 2, 16, AKF, BKF, VEC, 1>(prm, st);
+        case 1: return run_gemm<2, 2, 1, 2, 16, AKF, BKF, VEC, 2>(prm, st);
+        case 2: return run_gemm<2, 2, 2, 1, 16, AKF, BKF, VEC, 2>(prm, st);
+        case 3: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3>(prm, st);
+        case 4: return run_gemm<1, 4, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
+        case 5: return run_gemm<1, 2, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
+        case 6: return run_gemm<2, 1, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
+        case 7: return run_gemm<1, 1, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
+        case 8: return run_gemm<2, 2, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
+        case 9: return run_gemm<1, 2, 2, 1, 16, AKF, BKF, VEC, 3>(prm, st);
+        case 10: return run_gemm<2, 4, 1, 1, 16, AKF, BKF, VEC, 3>(prm, st);
+        case 11: return run_gemm<4, 2, 1, 1, 16, AKF, BKF, VEC, 3>(prm, st);
+        case 12: return run_gemm<2, 4, 2, 1, 16, AKF, BKF, VEC, 2>(prm, st);
+        case 13: return run_gemm<2, 2, 1, 1, 8, AKF, BKF, VEC, 3, 2>(prm, st);
+        case 14: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3, 1>(prm, st);
+        case 15: return run_gemm<2, 2, 1, 1, 32, AKF, BKF, VEC, 3, 1>(prm, st);
+        case 16: return run_gemm<2, 2, 2, 2, 16, AKF, BKF, VEC, 2, 1>(prm, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+static int pick_tile(int M, int N, int bins) {
+    if (const char *e = getenv("FFTCONV_GEMM_TILE")) return atoi(e);
+    (void)M; (void)N; (void)bins;
+    // 64x64 tiles on four waves measured fastest for every layer shape tried (more
+    // workgroups in flight beat the larger tiles' operand reuse).
+    return 3;
 }
 
 hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
                              long C_cs, int M, int N, int K, int bins, hipStream_t st) {
+    if (bins % kXcds != 0) return hipErrorInvalidValue;   // N*(N/2+1) with N >= 8 always is
     GemmParams prm;
     prm.A = A.ptr; prm.B = B.ptr; prm.C = C;
     prm.layA = A.lay; prm.layB = B.lay; prm.layC = layC;
     prm.a_rs = A.rs; prm.a_cs = A.cs; prm.b_rs = B.rs; prm.b_cs = B.cs;
     prm.c_rs = C_rs; prm.c_cs = C_cs;
     prm.M = M; prm.N = N; prm.K = K; prm.bins = bins;
-    prm.a_kfast = (A.cs == 1);
-    prm.b_kfast = (B.rs == 1);
-    auto wgs = [&](int tm, int tn) { return (long)bins * ((M + tm - 1) / tm) * ((N + tn - 1) / tn); };
-    if (M <= 32) return run_gemm<1, 4, 1, 1>(prm, st);
-    if (M > 64 && N > 64 && wgs(128, 128) >= 512) return run_gemm<2, 2, 2, 2>(prm, st);
-    if (N > 64 && wgs(64, 128) >= 512) return run_gemm<2, 2, 1, 2>(prm, st);
-    if (M > 64 && wgs(128, 64) >= 512) return run_gemm<2, 2, 2, 1>(prm, st);
-    return run_gemm<2, 2, 1, 1>(prm, st);
+    const bool akf = (A.cs == 1), bkf = (B.rs == 1);
+    // 16-byte gathers need: runs of >= 4 planes, the contiguous index a multiple of 4 at every
+    // vector start (tile origins are), its extent a multiple of 4, and the other stride too.
+    auto vec_ok = [](const FreqLayout &l, long contiguous_extent, long other_stride, const float *p) {
+        return l.tsh >= 2 && contiguous_extent % 4 == 0 && other_stride % 4 == 0 && ((size_t)p & 15) == 0;
+    };
+    const bool va = akf ? vec_ok(A.lay, K, A.rs, A.ptr) : (A.rs == 1 && vec_ok(A.lay, M, A.cs, A.ptr));
+    const bool vb = bkf ? vec_ok(B.lay, K, B.cs, B.ptr) : (B.cs == 1 && vec_ok(B.lay, N, B.rs, B.ptr));
+    const bool vec = va && vb;
+    const int shape = pick_tile(M, N, bins);
+    if (vec) {
+        if (akf && bkf) return dispatch_tile<true, true, true>(shape, prm, st);
+        if (akf && !bkf) return dispatch_tile<true, false, true>(shape, prm, st);
+        if (!akf && !bkf) return dispatch_tile<false, false, true>(shape, prm, st);
+        return dispatch_tile<false, true, true>(shape, prm, st);
+    }
+    if (akf && bkf) return dispatch_tile<true, true, false>(shape, prm, st);
+    if (akf && !bkf) return dispatch_tile<true, false, false>(shape, prm, st);
+    if (!akf && !bkf) return dispatch_tile<false, false, false>(shape, prm, st);
+    return dispatch_tile<false, true, false>(shape, prm, st);
 }
 
 }  // namespace fc

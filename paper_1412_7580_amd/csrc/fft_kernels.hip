@@ -25,6 +25,69 @@ static hipError_t allow_big_lds(const void *fn, size_t bytes) {
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+
+// Copy `total` contiguous floats from global memory into LDS at the same offsets.  Loads are
+// issued in batches of U per lane before any LDS store so that many are in flight at once;
+// 16-byte loads are used when `vec_ok` (base pointer and block start are 16-byte aligned).
+template <int BT, int U = 8>
+__device__ __forceinline__ void stage_linear(float *dst, const float *src, unsigned total, int tid,
+                                             bool vec_ok) {
+    unsigned done = 0;
+    if (vec_ok) {
+        const unsigned total4 = total >> 2;
+        const float4 *s4 = reinterpret_cast<const float4 *>(src);
+        float4 *d4 = reinterpret_cast<float4 *>(dst);
+        for (unsigned base = tid; base < total4; base += BT * U) {
+            float4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const unsigned i = base + u * BT;
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (i < total4) v[u] = s4[i];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const unsigned i = base + u * BT;
+                if (i < total4) d4[i] = v[u];
+            }
+        }
+        done = total4 << 2;
+    }
+    for (unsigned base = done + tid; base < total; base += BT * U) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned i = base + u * BT;
+            v[u] = 0.f;
+            if (i < total) v[u] = src[i];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned i = base + u * BT;
+            if (i < total) dst[i] = v[u];
+        }
+    }
+}
+
+// Copy `total` floats from LDS to contiguous global memory (optionally accumulating).
+template <int BT>
+__device__ __forceinline__ void unstage_linear(float *dst, const float *src, unsigned total, int tid,
+                                               bool vec_ok, bool accumulate) {
+    unsigned done = 0;
+    if (vec_ok && !accumulate) {
+        const unsigned total4 = total >> 2;
+        const float4 *s4 = reinterpret_cast<const float4 *>(src);
+        float4 *d4 = reinterpret_cast<float4 *>(dst);
+        for (unsigned i = tid; i < total4; i += BT) d4[i] = s4[i];
+        done = total4 << 2;
+    }
+    if (accumulate) {
+        for (unsigned i = done + tid; i < total; i += BT) dst[i] += src[i];
+    } else {
+        for (unsigned i = done + tid; i < total; i += BT) dst[i] = src[i];
+    }
+}
+
 // ------------------------------------------------------------------ 2-D forward
 struct Fwd2dParams {
     const float *in;
@@ -36,6 +99,8 @@ struct Fwd2dParams {
     MagicDiv div_hw, div_w;
     FreqLayout lay;
     float im_sign;    // -1 to store the conjugate
+    int linear;       // staged planes need no padding: LDS image == global image
+    int vec_ok;       // input base and every block start are 16-byte aligned
 };
 
 // Store helpers for the two output layouts.
@@ -75,12 +140,30 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
     {
         const float *src = prm.in + p0 * hw;
         const unsigned total = (unsigned)np * hw;
-        for (unsigned e = tid; e < total; e += BT) {
-            const unsigned pl = mdiv(e, prm.div_hw);
-            const unsigned r = e - pl * hw;
-            const unsigned row = mdiv(r, prm.div_w);
-            const unsigned col = r - row * w_in;
-            sin[pl * prm.IPS + row * prm.RS + col] = src[e];
+        if (prm.linear) {
+            stage_linear<BT>(sin, src, total, tid, prm.vec_ok != 0);
+        } else {
+            constexpr int U = 8;
+            for (unsigned base = tid; base < total; base += BT * U) {
+                float v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const unsigned e = base + u * BT;
+                    v[u] = 0.f;
+                    if (e < total) v[u] = src[e];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const unsigned e = base + u * BT;
+                    if (e < total) {
+                        const unsigned pl = mdiv(e, prm.div_hw);
+                        const unsigned r = e - pl * hw;
+                        const unsigned row = mdiv(r, prm.div_w);
+                        const unsigned col = r - row * w_in;
+                        sin[pl * prm.IPS + row * prm.RS + col] = v[u];
+                    }
+                }
+            }
         }
     }
     __syncthreads();
@@ -193,6 +276,7 @@ struct Inv2dParams {
     FreqLayout lay;
     float scale;
     int accumulate;
+    int vec_ok;       // output base and every block start are 16-byte aligned
 };
 
 template <int L, int G, int T, bool CONV>
@@ -297,11 +381,7 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
     {
         float *dst = prm.out + p0 * (long)h_out * w_out;
         const unsigned total = (unsigned)np * h_out * w_out;
-        if (prm.accumulate) {
-            for (unsigned e = tid; e < total; e += BT) dst[e] += sout[e];
-        } else {
-            for (unsigned e = tid; e < total; e += BT) dst[e] = sout[e];
-        }
+        unstage_linear<BT>(dst, sout, total, tid, prm.vec_ok != 0, prm.accumulate != 0);
     }
 }
 
@@ -312,6 +392,7 @@ struct Fwd1dParams {
     long B;
     int n_in, RS;
     MagicDiv div_n;
+    int linear, vec_ok, out_vec_ok;
 };
 
 template <int L, int G, int TB>
@@ -331,9 +412,27 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) 
     {
         const float *src = prm.in + b0 * n_in;
         const unsigned total = (unsigned)nb * n_in;
-        for (unsigned e = tid; e < total; e += BT) {
-            const unsigned s = mdiv(e, prm.div_n);
-            sin[s * prm.RS + (e - s * n_in)] = src[e];
+        if (prm.linear) {
+            stage_linear<BT>(sin, src, total, tid, prm.vec_ok != 0);
+        } else {
+            constexpr int U = 8;
+            for (unsigned base = tid; base < total; base += BT * U) {
+                float v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const unsigned e = base + u * BT;
+                    v[u] = 0.f;
+                    if (e < total) v[u] = src[e];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const unsigned e = base + u * BT;
+                    if (e < total) {
+                        const unsigned sg = mdiv(e, prm.div_n);
+                        sin[sg * prm.RS + (e - sg * n_in)] = v[u];
+                    }
+                }
+            }
         }
     }
     __syncthreads();
@@ -377,9 +476,9 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) 
     }
     __syncthreads();
     {
-        float2 *dst = reinterpret_cast<float2 *>(prm.out) + b0 * NB;
-        const unsigned total = (unsigned)nb * NB;
-        for (unsigned e = tid; e < total; e += BT) dst[e] = sout[e];
+        float *dst = prm.out + b0 * NB * 2;
+        const unsigned total = (unsigned)nb * NB * 2;
+        unstage_linear<BT>(dst, smem, total, tid, prm.out_vec_ok != 0, false);
     }
 }
 
@@ -390,6 +489,7 @@ struct Inv1dParams {
     long B;
     int n_out;
     float scale;
+    int in_vec_ok, out_vec_ok;
 };
 
 template <int L, int G, int TB>
@@ -405,9 +505,9 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_c2r_kernel(Inv1dParams prm) 
     const int nb = left < TB ? (int)left : TB;
     const int n_out = prm.n_out;
     {
-        const float2 *src = reinterpret_cast<const float2 *>(prm.in) + b0 * NB;
-        const unsigned total = (unsigned)nb * NB;
-        for (unsigned e = tid; e < total; e += BT) sin[e] = src[e];
+        const float *src = prm.in + b0 * NB * 2;
+        const unsigned total = (unsigned)nb * NB * 2;
+        stage_linear<BT>(smem, src, total, tid, prm.in_vec_ok != 0);
     }
     __syncthreads();
     const int g = tid % G, pr = tid / G;
@@ -446,7 +546,7 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_c2r_kernel(Inv1dParams prm) 
     {
         float *dst = prm.out + b0 * n_out;
         const unsigned total = (unsigned)nb * n_out;
-        for (unsigned e = tid; e < total; e += BT) dst[e] = sout[e];
+        unstage_linear<BT>(dst, sout, total, tid, prm.out_vec_ok != 0, false);
     }
 }
 
@@ -476,6 +576,8 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
     prm.lay.tsh = fft2d_tile_log2(N);
     prm.lay.bins = N * (NH + 1);
     prm.im_sign = conj ? -1.f : 1.f;
+    prm.linear = (prm.RS == w_in && prm.IPS == h_in * w_in) ? 1 : 0;
+    prm.vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * h_in * w_in) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)T * prm.IPS * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
     const size_t lds = a > b ? a : b;
     const unsigned grid = (unsigned)((planes + T - 1) / T);
@@ -515,6 +617,7 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     prm.lay.tsh = fft2d_tile_log2(N);
     prm.lay.bins = N * (NH + 1);
     prm.scale = scale; prm.accumulate = accumulate ? 1 : 0;
+    prm.vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * h_out * w_out) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)T * prm.MPS * sizeof(float2), b = (size_t)T * h_out * w_out * sizeof(float);
     const size_t lds = a > b ? a : b;
     const unsigned grid = (unsigned)((planes + T - 1) / T);
@@ -550,6 +653,9 @@ static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, hipSt
     Fwd1dParams prm;
     prm.in = in; prm.out = out; prm.B = B; prm.n_in = n_in; prm.RS = n_in | 1;
     prm.div_n = make_magic((unsigned)n_in);
+    prm.linear = (prm.RS == n_in) ? 1 : 0;
+    prm.vec_ok = (((size_t)in & 15) == 0 && ((size_t)TB * n_in) % 4 == 0) ? 1 : 0;
+    prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)TB * NB * 2) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)TB * prm.RS * sizeof(float), b = (size_t)TB * NB * sizeof(float2);
     const size_t lds = a > b ? a : b;
     auto k = fft1d_r2c_kernel<L, G, TB>;
@@ -576,6 +682,8 @@ static hipError_t run_inv1d(const float *in, float *out, long B, int n_out, hipS
     constexpr int N = L * G, NB = N / 2 + 1, BT = TB / 2 * G;
     Inv1dParams prm;
     prm.in = in; prm.out = out; prm.B = B; prm.n_out = n_out; prm.scale = 1.0f / (float)N;
+    prm.in_vec_ok = (((size_t)in & 15) == 0 && ((size_t)TB * NB * 2) % 4 == 0) ? 1 : 0;
+    prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)TB * n_out) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)TB * NB * sizeof(float2), b = (size_t)TB * n_out * sizeof(float);
     const size_t lds = a > b ? a : b;
     auto k = fft1d_c2r_kernel<L, G, TB>;
