@@ -1,15 +1,15 @@
 // In-register small FFT building blocks for gfx950 (wave64).
 //
-// A length-N line (N = L*G, G in {1,2}) is transformed by G adjacent lanes.  Lane g holds
+// A length-N line (N = L*G, G in {1,2,4}) is transformed by G adjacent lanes.  Lane g holds
 // the decimated samples x[g + G*m], m < L, in L complex registers, runs an L-point FFT on
 // them with fully static register indexing (straight-line code, twiddles are immediates),
-// and, for G = 2, finishes with one radix-2 decimation-in-time step across the lane pair
-// through DPP quad-permutes.  Afterwards lane q holds bins k + L*q in register k.
+// and, for G > 1, finishes with log2(G) radix-2 decimation-in-time steps across the lane
+// group through DPP quad-permutes.  Afterwards each lane holds a block of L consecutive bins.
 //
 // This replaces the one-element-per-lane warp-shuffle butterflies of Section 5.2 of the
 // fbfft paper: on CDNA every cross-lane permute other than DPP goes through the LDS pipe,
 // the very bottleneck Section 6 reports, so the butterflies stay inside a lane and only the
-// last stage of the two largest sizes crosses lanes.
+// last one or two stages of the two largest sizes cross lanes.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <type_traits>
@@ -109,17 +109,31 @@ __device__ __forceinline__ void fft_leaf(float (&re)[L], float (&im)[L]) {
 }
 
 // ---------------------------------------------------------------- cross-lane helpers
-// Value held by the neighbouring lane (lane ^ 1): DPP quad_perm [1,0,3,2].
-__device__ __forceinline__ float lane_xor1(float v) {
+// Value held by lane ^ 1 / ^ 2 / ^ 3 of the same quad: DPP quad_perm.
+template <int CTRL>
+__device__ __forceinline__ float quad_dpp(float v) {
     return __builtin_bit_cast(
-        float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+        float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float lane_xor1(float v) { return quad_dpp<0xB1>(v); }   // [1,0,3,2]
+__device__ __forceinline__ float lane_xor2(float v) { return quad_dpp<0x4E>(v); }   // [2,3,0,1]
+__device__ __forceinline__ float lane_xor3(float v) { return quad_dpp<0x1B>(v); }   // [3,2,1,0]
+
+// Block of output bins held by lane g after fft_group: lane g holds X[k + L*group_block(g)].
+template <int G>
+__device__ __forceinline__ int group_block(int g) {
+    if constexpr (G == 4) return ((g & 1) << 1) | (g >> 1);
+    else return g;
 }
 
-// N = L*G point FFT over G lanes.  On entry lane g holds x[g + G*m] in register m; on exit
-// lane q holds X[k + L*q] in register k.  All G lanes of a group must be active together.
+// N = L*G point FFT over G adjacent lanes (G = 1, 2 or 4).  On entry lane g holds x[g + G*m]
+// in register m; on exit lane g holds X[k + L*group_block<G>(g)] in register k.  All G lanes
+// of a group must be active together.  The cross-lane part is one (G = 2) or two (G = 4)
+// radix-2 decimation-in-time steps: the upper lane of each pair multiplies by the step's
+// twiddle, the pair swaps values through DPP and forms sum / difference.
 template <int L, int G, int DIR>
 __device__ __forceinline__ void fft_group(float (&re)[L], float (&im)[L], int g) {
-    static_assert(G == 1 || G == 2, "one lane or a lane pair per line");
+    static_assert(G == 1 || G == 2 || G == 4, "one lane, a lane pair or a lane quad per line");
     fft_leaf<L, DIR>(re, im);
     if constexpr (G == 2) {
         const float sgn = g ? -1.0f : 1.0f;
@@ -134,22 +148,61 @@ __device__ __forceinline__ void fft_group(float (&re)[L], float (&im)[L], int g)
             re[k] = qr + sgn * tr;
             im[k] = qi + sgn * ti;
         });
+    } else if constexpr (G == 4) {
+        const bool up = (g >> 1) != 0, odd = (g & 1) != 0, last = g == 3;
+        const float s1 = up ? -1.0f : 1.0f, s2 = odd ? -1.0f : 1.0f;
+        static_for<0, L>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            // step 1, lanes (0,2) and (1,3): even/odd halves of the 2L-point sub-transforms
+            constexpr cplx_d w1 = unit_root(DIR * k, 2 * L);
+            constexpr float c1 = (float)w1.re, d1 = (float)w1.im;
+            const float w1r = up ? c1 : 1.0f, w1i = up ? d1 : 0.0f;
+            const float tr = w1r * re[k] - w1i * im[k];
+            const float ti = w1r * im[k] + w1i * re[k];
+            const float ar = lane_xor2(tr) + s1 * tr;
+            const float ai = lane_xor2(ti) + s1 * ti;
+            // step 2, lanes (0,1) and (2,3): twiddle w_N^k on lane 1, w_N^(k+L) on lane 3
+            constexpr cplx_d w2 = unit_root(DIR * k, 4 * L), w3 = unit_root(DIR * (k + L), 4 * L);
+            constexpr float c2 = (float)w2.re, d2 = (float)w2.im, c3 = (float)w3.re, d3 = (float)w3.im;
+            const float w2r = odd ? (last ? c3 : c2) : 1.0f, w2i = odd ? (last ? d3 : d2) : 0.0f;
+            const float ur = w2r * ar - w2i * ai;
+            const float ui = w2r * ai + w2i * ar;
+            re[k] = lane_xor1(ur) + s2 * ur;
+            im[k] = lane_xor1(ui) + s2 * ui;
+        });
+    }
+}
+
+// Number of registers of split spectrum a lane keeps (see split_two_real).
+template <int L, int G> struct SplitRegs { static constexpr int A = (G == 1) ? L / 2 : L, B = (G == 1) ? L / 2 : 1; };
+
+// Slot (0 .. N/2-1) of the half spectrum that register k of lane g holds after
+// split_two_real for G > 1; slot 0 is the packed pair of real bins (X_0, X_{N/2}).
+template <int L, int G>
+__device__ __forceinline__ int split_slot(int g, int k) {
+    if constexpr (G == 2) return (g && k) ? L - k : k;
+    else {
+        switch (g) {
+            case 0: return k;
+            case 2: return L + k;
+            case 3: return k ? L - k : L;
+            default: return k ? 2 * L - k : 0;
+        }
     }
 }
 
 // After a forward fft_group of z = a + i b (a, b real lines), split the spectrum into the
 // spectra of a and b (the standard two-for-one trick the paper cites in Section 5.2).
-// Result, with NH = L*G/2 "slots" per line, slot 0 holding the two real bins (X_0, X_{N/2})
-// as (re, im):
+// With NH = L*G/2 slots per line, slot 0 holding the two real bins (X_0, X_{N/2}) as (re, im):
 //   G == 1: are/aim[k], bre/bim[k] for k < NH are slot k of a and of b.
-//   G == 2: lane 0 gets line a with slot k in register k; lane 1 gets line b with slot
-//           (k == 0 ? 0 : L - k) in register k.  Both are returned in are/aim.
+//   G  > 1: even lanes get line a, odd lanes line b; register k holds slot split_slot(g, k).
+//           Both are returned in are/aim.
 template <int L, int G>
 __device__ __forceinline__ void split_two_real(const float (&re)[L], const float (&im)[L], int g,
-                                               float (&are)[G == 1 ? L / 2 : L],
-                                               float (&aim)[G == 1 ? L / 2 : L],
-                                               float (&bre)[G == 1 ? L / 2 : 1],
-                                               float (&bim)[G == 1 ? L / 2 : 1]) {
+                                               float (&are)[SplitRegs<L, G>::A],
+                                               float (&aim)[SplitRegs<L, G>::A],
+                                               float (&bre)[SplitRegs<L, G>::B],
+                                               float (&bim)[SplitRegs<L, G>::B]) {
     if constexpr (G == 1) {
         constexpr int NH = L / 2;
         are[0] = re[0]; aim[0] = re[NH];
@@ -161,19 +214,31 @@ __device__ __forceinline__ void split_two_real(const float (&re)[L], const float
             bre[k] = 0.5f * (xi + yi); bim[k] = 0.5f * (yr - xr);
         }
     } else {
-        // lane 0: own = Z[k], other = Z[N-k];  lane 1: own = Z[L+k], other = Z[L-k]
-        const float o0r = lane_xor1(re[0]), o0i = lane_xor1(im[0]);
-        are[0] = g ? o0i : re[0];
-        aim[0] = g ? im[0] : o0r;
+        // Every lane pairs its own Z[j] with Z[N-j] fetched from the mirror lane.  Even lanes
+        // form A[j] = (own + conj(other)) / 2, odd lanes B[N-j] = (other - conj(own)) / (2i).
+        const bool odd = (g & 1) != 0;
+        {   // register 0: bins 0, N/2 (and N/4, 3N/4 for G = 4) pair up with the neighbour lane
+            const float o0r = lane_xor1(re[0]), o0i = lane_xor1(im[0]);
+            if constexpr (G == 2) {
+                are[0] = odd ? o0i : re[0];
+                aim[0] = odd ? im[0] : o0r;
+            } else {
+                const float a_r = 0.5f * (re[0] + o0r), a_i = 0.5f * (im[0] - o0i);
+                const float b_r = 0.5f * (o0i + im[0]), b_i = 0.5f * (re[0] - o0r);
+                const bool up = (g >> 1) != 0;
+                are[0] = up ? (odd ? b_r : a_r) : (odd ? o0i : re[0]);
+                aim[0] = up ? (odd ? b_i : a_i) : (odd ? im[0] : o0r);
+            }
+        }
         static_for<1, L>([&](auto kk) {
             constexpr int k = decltype(kk)::value;
-            const float orr = lane_xor1(re[L - k]), oi = lane_xor1(im[L - k]);
-            // lane 0: A[k]   = (own + conj(other)) / 2
-            // lane 1: B[L-k] = (other - conj(own)) / (2i)
+            float orr, oi;
+            if constexpr (G == 2) { orr = lane_xor1(re[L - k]); oi = lane_xor1(im[L - k]); }
+            else { orr = lane_xor3(re[L - k]); oi = lane_xor3(im[L - k]); }
             const float a_r = 0.5f * (re[k] + orr), a_i = 0.5f * (im[k] - oi);
             const float b_r = 0.5f * (oi + im[k]), b_i = 0.5f * (re[k] - orr);
-            are[k] = g ? b_r : a_r;
-            aim[k] = g ? b_i : a_i;
+            are[k] = odd ? b_r : a_r;
+            aim[k] = odd ? b_i : a_i;
         });
         bre[0] = 0.f; bim[0] = 0.f;
     }

@@ -9,6 +9,8 @@
 #include "fft_core.hpp"
 #include "kernels.hpp"
 
+#include <cstdlib>
+
 namespace fc {
 
 // ------------------------------------------------------------------ small helpers
@@ -101,6 +103,7 @@ struct Fwd2dParams {
     float im_sign;    // -1 to store the conjugate
     int linear;       // staged planes need no padding: LDS image == global image
     int vec_ok;       // input base and every block start are 16-byte aligned
+    int out_vec_ok;   // output base and every block start are 16-byte aligned
 };
 
 // Store helpers for the two output layouts.
@@ -121,11 +124,11 @@ struct BinStore {
     }
 };
 
-template <int L, int G, int T, bool CONV>
+template <int L, int G, int T, bool CONV, bool OSTAGE>
 __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dParams prm) {
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
-    constexpr int NA = (G == 1) ? NH : L;   // registers of split spectrum per lane
-    constexpr int NBR = (G == 1) ? NH : 1;
+    constexpr int NA = SplitRegs<L, G>::A;   // registers of split spectrum per lane
+    constexpr int NBR = SplitRegs<L, G>::B;
     extern __shared__ float smem[];
     float *sin = smem;
     float2 *mid = reinterpret_cast<float2 *>(smem);
@@ -200,13 +203,11 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
                 for (int k = 0; k < NH; ++k) mp[rb * NH + k] = make_float2(bre[k], bim[k]);
             }
         } else {
-            const int row = g ? rb : ra;
-            if (!g || hasb) {
+            const int row = (g & 1) ? rb : ra;
+            if (!(g & 1) || hasb) {
 #pragma unroll
-                for (int k = 0; k < L; ++k) {
-                    const int slot = (g && k) ? L - k : k;
-                    mp[row * NH + slot] = make_float2(are[k], aim[k]);
-                }
+                for (int k = 0; k < L; ++k)
+                    mp[row * NH + split_slot<L, G>(g, k)] = make_float2(are[k], aim[k]);
             }
         }
     }
@@ -217,10 +218,10 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
     int cg, cp, cc;
     if constexpr (CONV) { cg = tid % G; cp = (tid / G) % T; cc = tid / (G * T); }
     else { cg = tid % G; cc = (tid / G) % NH; cp = tid / (G * NH); }
-    if (cp >= np) return;
+    const bool col_active = cp < np;
 
     float re[L], im[L];
-    {
+    if (col_active) {
         const float2 *mp = mid + cp * prm.MPS + cc;
 #pragma unroll
         for (int m = 0; m < L; ++m) {
@@ -229,39 +230,66 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
             if (r < h_in) v = mp[r * NH];
             re[m] = v.x; im[m] = v.y;
         }
+        fft_group<L, G, -1>(re, im, cg);
     }
-    fft_group<L, G, -1>(re, im, cg);
 
+    // Results go either straight to global memory or, when OSTAGE, into an LDS image of the
+    // block's output (which is one contiguous range in both layouts) that is then written
+    // out with 16-byte coalesced stores.
     BinStore<N, CONV> st;
-    st.tsh = prm.lay.tsh;
     st.im_sign = prm.im_sign;
-    if constexpr (CONV) st.base = prm.out + prm.lay.index(p0, 0, 0) + cp;
-    else st.base = prm.out + (size_t)(p0 + cp) * N * NB * 2;
-
-    if (cc != 0) {
-#pragma unroll
-        for (int k = 0; k < L; ++k) st(k + L * cg, cc, re[k], im[k]);
+    if constexpr (OSTAGE) {
+        __syncthreads();   // every lane has read `mid`; the image overlays it
+        st.tsh = prm.lay.tsh;
+        if constexpr (CONV) st.base = smem + cp;
+        else st.base = smem + (size_t)cp * N * NB * 2;
     } else {
-        float ur[NA], ui[NA], vr[NBR], vi[NBR];
-        split_two_real<L, G>(re, im, cg, ur, ui, vr, vi);
-        if constexpr (G == 1) {
-            st(0, 0, ur[0], 0.f);  st(NH, 0, ui[0], 0.f);
-            st(0, NH, vr[0], 0.f); st(NH, NH, vi[0], 0.f);
+        st.tsh = prm.lay.tsh;
+        if constexpr (CONV) st.base = prm.out + prm.lay.index(p0, 0, 0) + cp;
+        else st.base = prm.out + (size_t)(p0 + cp) * N * NB * 2;
+    }
+
+    if (col_active) {
+        if (cc != 0) {
 #pragma unroll
-            for (int k = 1; k < NH; ++k) {
-                st(k, 0, ur[k], ui[k]);  st(N - k, 0, ur[k], -ui[k]);
-                st(k, NH, vr[k], vi[k]); st(N - k, NH, vr[k], -vi[k]);
-            }
+            for (int k = 0; k < L; ++k) st(k + L * group_block<G>(cg), cc, re[k], im[k]);
         } else {
-            const int k2 = cg ? NH : 0;
-            st(0, k2, ur[0], 0.f);
-            st(L, k2, ui[0], 0.f);
+            float ur[NA], ui[NA], vr[NBR], vi[NBR];
+            split_two_real<L, G>(re, im, cg, ur, ui, vr, vi);
+            if constexpr (G == 1) {
+                st(0, 0, ur[0], 0.f);  st(NH, 0, ui[0], 0.f);
+                st(0, NH, vr[0], 0.f); st(NH, NH, vi[0], 0.f);
 #pragma unroll
-            for (int k = 1; k < L; ++k) {
-                const int k1 = cg ? L - k : k;
-                st(k1, k2, ur[k], ui[k]);
-                st(N - k1, k2, ur[k], -ui[k]);
+                for (int k = 1; k < NH; ++k) {
+                    st(k, 0, ur[k], ui[k]);  st(N - k, 0, ur[k], -ui[k]);
+                    st(k, NH, vr[k], vi[k]); st(N - k, NH, vr[k], -vi[k]);
+                }
+            } else {
+                // even lanes hold the spectrum of column 0, odd lanes that of column N/2
+                const int k2 = (cg & 1) ? NH : 0;
+#pragma unroll
+                for (int k = 0; k < L; ++k) {
+                    const int k1 = split_slot<L, G>(cg, k);
+                    if (k1 == 0) {                       // packed real bins 0 and N/2
+                        st(0, k2, ur[k], 0.f);
+                        st(NH, k2, ui[k], 0.f);
+                    } else {
+                        st(k1, k2, ur[k], ui[k]);
+                        st(N - k1, k2, ur[k], -ui[k]);
+                    }
+                }
             }
+        }
+    }
+    if constexpr (OSTAGE) {
+        __syncthreads();
+        if constexpr (CONV) {
+            // whole tile, including the padding planes of a ragged last tile
+            unstage_linear<BT>(prm.out + prm.lay.index(p0, 0, 0), smem, (unsigned)T * N * NB * 2, tid,
+                               prm.out_vec_ok != 0, false);
+        } else {
+            unstage_linear<BT>(prm.out + (size_t)p0 * N * NB * 2, smem, (unsigned)np * N * NB * 2, tid,
+                               prm.out_vec_ok != 0, false);
         }
     }
 }
@@ -277,6 +305,7 @@ struct Inv2dParams {
     float scale;
     int accumulate;
     int vec_ok;       // output base and every block start are 16-byte aligned
+    int in_vec_ok;    // natural layout only: input base is 16-byte aligned
 };
 
 template <int L, int G, int T, bool CONV>
@@ -292,13 +321,20 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
     const int np = left < T ? (int)left : T;
     const int h_out = prm.h_out, w_out = prm.w_out;
 
-    // ---- column phase (inverse along k1) for column slot cc of plane cp
+    // ---- column phase (inverse along k1) for column slot cc of plane cp.  In the natural
+    //      layout the block's input is one contiguous range: bring it into LDS with wide
+    //      coalesced loads first, then pick the strided column elements out of LDS.
     {
         int cg, cp, cc;
         if constexpr (CONV) { cg = tid % G; cp = (tid / G) % T; cc = tid / (G * T); }
         else { cg = tid % G; cc = (tid / G) % NH; cp = tid / (G * NH); }
+        if constexpr (!CONV) {
+            stage_linear<BT>(smem, prm.in + (size_t)p0 * N * NB * 2, (unsigned)np * N * NB * 2, tid,
+                             prm.in_vec_ok != 0);
+            __syncthreads();
+        }
+        float cre[L], cim[L];
         if (cp < np) {
-            float re[L], im[L];
             if constexpr (CONV) {
                 const float *base = prm.in + prm.lay.index(p0, 0, 0) + cp;
                 const int tsh = prm.lay.tsh;
@@ -312,10 +348,10 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
                         const float nr = qn[0], ni = qn[(size_t)1 << tsh];
                         xr -= ni; xi += nr;
                     }
-                    re[m] = xr; im[m] = xi;
+                    cre[m] = xr; cim[m] = xi;
                 }
             } else {
-                const float2 *base = reinterpret_cast<const float2 *>(prm.in) + (size_t)(p0 + cp) * N * NB;
+                const float2 *base = reinterpret_cast<const float2 *>(smem) + cp * N * NB;
 #pragma unroll
                 for (int m = 0; m < L; ++m) {
                     const int k1 = cg + G * m;
@@ -324,15 +360,18 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
                         const float2 u = base[k1 * NB + NH];
                         v.x -= u.y; v.y += u.x;
                     }
-                    re[m] = v.x; im[m] = v.y;
+                    cre[m] = v.x; cim[m] = v.y;
                 }
             }
-            fft_group<L, G, +1>(re, im, cg);
+            fft_group<L, G, +1>(cre, cim, cg);
+        }
+        if constexpr (!CONV) __syncthreads();   // staged input fully consumed; `mid` overlays it
+        if (cp < np) {
             float2 *mp = mid + cp * prm.MPS + cc;
 #pragma unroll
             for (int k = 0; k < L; ++k) {
-                const int a = k + L * cg;
-                if (a < h_out) mp[a * NH] = make_float2(re[k], im[k]);
+                const int a = k + L * group_block<G>(cg);
+                if (a < h_out) mp[a * NH] = make_float2(cre[k], cim[k]);
             }
         }
     }
@@ -370,7 +409,7 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
         float *ob = sout + (p * h_out + rb) * w_out;
 #pragma unroll
         for (int k = 0; k < L; ++k) {
-            const int b = k + L * g;
+            const int b = k + L * group_block<G>(g);
             if (b < w_out) {
                 oa[b] = re[k] * prm.scale;
                 if (hasb) ob[b] = im[k] * prm.scale;
@@ -398,8 +437,8 @@ struct Fwd1dParams {
 template <int L, int G, int TB>
 __global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) {
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = TB / 2 * G;
-    constexpr int NA = (G == 1) ? NH : L;
-    constexpr int NBR = (G == 1) ? NH : 1;
+    constexpr int NA = SplitRegs<L, G>::A;
+    constexpr int NBR = SplitRegs<L, G>::B;
     extern __shared__ float smem[];
     float *sin = smem;
     float2 *sout = reinterpret_cast<float2 *>(smem);
@@ -466,11 +505,14 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) 
                 for (int k = 1; k < NH; ++k) ob[k] = make_float2(bre[k], bim[k]);
             }
         } else {
-            if (!g || hasb) {
-                float2 *o = sout + (g ? sb : sa) * NB;
-                o[0] = make_float2(are[0], 0.f); o[NH] = make_float2(aim[0], 0.f);
+            if (!(g & 1) || hasb) {
+                float2 *o = sout + ((g & 1) ? sb : sa) * NB;
 #pragma unroll
-                for (int k = 1; k < L; ++k) o[g ? L - k : k] = make_float2(are[k], aim[k]);
+                for (int k = 0; k < L; ++k) {
+                    const int j = split_slot<L, G>(g, k);
+                    if (j == 0) { o[0] = make_float2(are[k], 0.f); o[NH] = make_float2(aim[k], 0.f); }
+                    else o[j] = make_float2(are[k], aim[k]);
+                }
             }
         }
     }
@@ -535,7 +577,7 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_c2r_kernel(Inv1dParams prm) 
         float *oa = sout + sa * n_out, *ob = sout + sb * n_out;
 #pragma unroll
         for (int k = 0; k < L; ++k) {
-            const int b = k + L * g;
+            const int b = k + L * group_block<G>(g);
             if (b < n_out) {
                 oa[b] = re[k] * prm.scale;
                 if (hasb) ob[b] = im[k] * prm.scale;
@@ -578,20 +620,26 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
     prm.im_sign = conj ? -1.f : 1.f;
     prm.linear = (prm.RS == w_in && prm.IPS == h_in * w_in) ? 1 : 0;
     prm.vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * h_in * w_in) % 4 == 0) ? 1 : 0;
+    prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)T * prm.IPS * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
-    const size_t lds = a > b ? a : b;
+    size_t lds = a > b ? a : b;
+    // Measured: staging the output through LDS pays for the natural layout (short runs per
+    // lane otherwise) and costs for the plane-tiled layout, whose direct stores already fill
+    // whole runs of T planes.
+    const bool ostage = !conv;
+    if (ostage) {
+        const size_t c = (size_t)T * N * (NH + 1) * 2 * sizeof(float);
+        if (c > lds) lds = c;
+    }
     const unsigned grid = (unsigned)((planes + T - 1) / T);
     hipError_t e;
-    if (conv) {
-        auto k = fft2d_r2c_kernel<L, G, T, true>;
+    auto go = [&](auto k) -> hipError_t {
         if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
         hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
-    } else {
-        auto k = fft2d_r2c_kernel<L, G, T, false>;
-        if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
-        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
-    }
-    return hipGetLastError();
+        return hipGetLastError();
+    };
+    if (conv) return go(fft2d_r2c_kernel<L, G, T, true, false>);
+    return go(fft2d_r2c_kernel<L, G, T, false, true>);
 }
 
 hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
@@ -602,7 +650,7 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
         case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, conj, st);
         case 32: return run_fwd2d<32, 1, 16>(in, out, planes, h_in, w_in, conv, conj, st);
         case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, conj, st);
-        case 128: return run_fwd2d<64, 2, 1>(in, out, planes, h_in, w_in, conv, conj, st);
+        case 128: return run_fwd2d<32, 4, 1>(in, out, planes, h_in, w_in, conv, conj, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -618,8 +666,13 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     prm.lay.bins = N * (NH + 1);
     prm.scale = scale; prm.accumulate = accumulate ? 1 : 0;
     prm.vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * h_out * w_out) % 4 == 0) ? 1 : 0;
+    prm.in_vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)T * prm.MPS * sizeof(float2), b = (size_t)T * h_out * w_out * sizeof(float);
-    const size_t lds = a > b ? a : b;
+    size_t lds = a > b ? a : b;
+    if (!conv) {
+        const size_t c = (size_t)T * N * (NH + 1) * sizeof(float2);
+        if (c > lds) lds = c;
+    }
     const unsigned grid = (unsigned)((planes + T - 1) / T);
     hipError_t e;
     if (conv) {
@@ -642,7 +695,7 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
         case 16: return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
         case 32: return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
         case 64: return run_inv2d<32, 2, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
-        case 128: return run_inv2d<64, 2, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 128: return run_inv2d<32, 4, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -672,7 +725,7 @@ hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n
         case 16: return run_fwd1d<16, 1, 512>(in, out, B, n_in, st);
         case 32: return run_fwd1d<32, 1, 256>(in, out, B, n_in, st);
         case 64: return run_fwd1d<32, 2, 128>(in, out, B, n_in, st);
-        case 128: return run_fwd1d<64, 2, 64>(in, out, B, n_in, st);
+        case 128: return run_fwd1d<32, 4, 128>(in, out, B, n_in, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -700,7 +753,7 @@ hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_ou
         case 16: return run_inv1d<16, 1, 512>(in, out, B, n_out, st);
         case 32: return run_inv1d<32, 1, 256>(in, out, B, n_out, st);
         case 64: return run_inv1d<32, 2, 128>(in, out, B, n_out, st);
-        case 128: return run_inv1d<64, 2, 64>(in, out, B, n_out, st);
+        case 128: return run_inv1d<32, 4, 128>(in, out, B, n_out, st);
         default: return hipErrorInvalidValue;
     }
 }
