@@ -106,10 +106,10 @@ int fft_c2r_2d(fftconv_handle hd, const float *in, float *out, long B, int n, in
 
 /*
  * Per-stage timing of the last convolution pass, for roofline reporting.
- * With profiling enabled each pass records HIP events on the handle's stream around its
- * four stages (FFT of operand A, FFT of operand B, per-bin contraction, inverse FFT);
- * fftconv_last_stage_ms() waits for the last pass and returns the four durations in
- * milliseconds.  Off by default; enabling it adds event records to the stream.
+ * With profiling enabled each of a pass's four kernels (FFT of operand A, FFT of operand
+ * B, per-bin contraction, inverse FFT) is launched with a start/stop HIP event pair attached
+ * to that dispatch on the handle's stream; fftconv_last_stage_ms() waits for the last pass
+ * and returns the four kernel execution times in milliseconds.  Off by default.
  */
 int fftconv_set_profiling(fftconv_handle h, int enabled);
 int fftconv_last_stage_ms(fftconv_handle h, float ms_out[4]);

@@ -20,7 +20,7 @@ struct fftconv_ctx {
     void *ws;
     size_t ws_bytes;
     int profiling;
-    hipEvent_t ev[5];
+    hipEvent_t ev[8];   // start/stop pair per stage
     int ev_valid;
     char last_hip_error[256];
 };
@@ -122,21 +122,20 @@ static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB
     float *AF = reinterpret_cast<float *>(static_cast<char *>(ws) + p.offA);
     float *BF = reinterpret_cast<float *>(static_cast<char *>(ws) + p.offB);
     float *CF = reinterpret_cast<float *>(static_cast<char *>(ws) + p.offC);
-    hipStream_t st = c->stream;
     const bool prof = c->profiling != 0;
     c->ev_valid = 0;
+    auto ctx = [&](int stage) {
+        return prof ? LaunchCtx{c->stream, c->ev[2 * stage], c->ev[2 * stage + 1]}
+                    : LaunchCtx{c->stream, nullptr, nullptr};
+    };
 
-    if (prof) (void)hipEventRecord(c->ev[0], st);
-    if ((e = launch_fft2d_r2c(opA, AF, p.planesA, p.hA, p.wA, p.N, true, p.conjA, st)) != hipSuccess) return hip_fail(c, e);
-    if (prof) (void)hipEventRecord(c->ev[1], st);
-    if ((e = launch_fft2d_r2c(opB, BF, p.planesB, p.hB, p.wB, p.N, true, p.conjB, st)) != hipSuccess) return hip_fail(c, e);
-    if (prof) (void)hipEventRecord(c->ev[2], st);
+    if ((e = launch_fft2d_r2c(opA, AF, p.planesA, p.hA, p.wA, p.N, true, p.conjA, ctx(0))) != hipSuccess) return hip_fail(c, e);
+    if ((e = launch_fft2d_r2c(opB, BF, p.planesB, p.hB, p.wB, p.N, true, p.conjB, ctx(1))) != hipSuccess) return hip_fail(c, e);
     GemmOperand ga{AF, p.lay, p.a_rs, p.a_cs}, gb{BF, p.lay, p.b_rs, p.b_cs};
-    if ((e = launch_cgemm_bins(ga, gb, CF, p.lay, p.c_rs, p.c_cs, p.M, p.Nn, p.K, p.bins, st)) != hipSuccess) return hip_fail(c, e);
-    if (prof) (void)hipEventRecord(c->ev[3], st);
+    if ((e = launch_cgemm_bins(ga, gb, CF, p.lay, p.c_rs, p.c_cs, p.M, p.Nn, p.K, p.bins, ctx(2))) != hipSuccess) return hip_fail(c, e);
     const float s = scale / ((float)p.N * (float)p.N);
-    if ((e = launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, st)) != hipSuccess) return hip_fail(c, e);
-    if (prof) { (void)hipEventRecord(c->ev[4], st); c->ev_valid = 1; }
+    if ((e = launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, ctx(3))) != hipSuccess) return hip_fail(c, e);
+    if (prof) c->ev_valid = 1;
     return FFTCONV_OK;
 }
 
@@ -152,7 +151,7 @@ int fftconv_create(fftconv_handle *out, int device) {
     if (!c) return FFTCONV_HIP_ERROR;
     c->device = device; c->stream = nullptr; c->ws = nullptr; c->ws_bytes = 0;
     c->profiling = 0; c->ev_valid = 0; c->last_hip_error[0] = 0;
-    for (int i = 0; i < 5; ++i)
+    for (int i = 0; i < 8; ++i)
         if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return FFTCONV_HIP_ERROR; }
     *out = c;
     return FFTCONV_OK;
@@ -161,7 +160,7 @@ int fftconv_create(fftconv_handle *out, int device) {
 int fftconv_destroy(fftconv_handle h) {
     if (!h) return FFTCONV_INVALID_ARG;
     if (h->ws) (void)hipFree(h->ws);
-    for (int i = 0; i < 5; ++i) (void)hipEventDestroy(h->ev[i]);
+    for (int i = 0; i < 8; ++i) (void)hipEventDestroy(h->ev[i]);
     delete h;
     return FFTCONV_OK;
 }
@@ -211,7 +210,7 @@ int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in,
     if (!hd || B < 0 || n_in <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;
     if (!fft_size_ok(n)) return FFTCONV_UNSUPPORTED;
     if (n_in > n) return FFTCONV_INVALID_ARG;
-    hipError_t e = launch_fft1d_r2c(in, out, B, n_in, n, hd->stream);
+    hipError_t e = launch_fft1d_r2c(in, out, B, n_in, n, LaunchCtx{hd->stream, nullptr, nullptr});
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
@@ -219,7 +218,7 @@ int fft_c2r_1d(fftconv_handle hd, const float *in, float *out, long B, int n, in
     if (!hd || B < 0 || n_out <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;
     if (!fft_size_ok(n)) return FFTCONV_UNSUPPORTED;
     if (n_out > n) return FFTCONV_INVALID_ARG;
-    hipError_t e = launch_fft1d_c2r(in, out, B, n, n_out, hd->stream);
+    hipError_t e = launch_fft1d_c2r(in, out, B, n, n_out, LaunchCtx{hd->stream, nullptr, nullptr});
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
@@ -227,7 +226,7 @@ int fft_r2c_2d(fftconv_handle hd, const float *in, float *out, long B, int h_in,
     if (!hd || B < 0 || h_in <= 0 || w_in <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;
     if (!fft_size_ok(n)) return FFTCONV_UNSUPPORTED;
     if (h_in > n || w_in > n) return FFTCONV_INVALID_ARG;
-    hipError_t e = launch_fft2d_r2c(in, out, B, h_in, w_in, n, false, false, hd->stream);
+    hipError_t e = launch_fft2d_r2c(in, out, B, h_in, w_in, n, false, false, LaunchCtx{hd->stream, nullptr, nullptr});
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
@@ -236,7 +235,7 @@ int fft_c2r_2d(fftconv_handle hd, const float *in, float *out, long B, int n, in
     if (!fft_size_ok(n)) return FFTCONV_UNSUPPORTED;
     if (h_out > n || w_out > n) return FFTCONV_INVALID_ARG;
     const float s = 1.0f / ((float)n * (float)n);
-    hipError_t e = launch_fft2d_c2r(in, out, B, n, h_out, w_out, false, s, false, hd->stream);
+    hipError_t e = launch_fft2d_c2r(in, out, B, n, h_out, w_out, false, s, false, LaunchCtx{hd->stream, nullptr, nullptr});
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
@@ -250,10 +249,10 @@ int fftconv_set_profiling(fftconv_handle h, int enabled) {
 int fftconv_last_stage_ms(fftconv_handle h, float ms_out[4]) {
     if (!h || !ms_out) return FFTCONV_INVALID_ARG;
     if (!h->ev_valid) return FFTCONV_INVALID_ARG;
-    hipError_t e = hipEventSynchronize(h->ev[4]);
+    hipError_t e = hipEventSynchronize(h->ev[7]);
     if (e != hipSuccess) return hip_fail(h, e);
     for (int i = 0; i < 4; ++i)
-        if ((e = hipEventElapsedTime(&ms_out[i], h->ev[i], h->ev[i + 1])) != hipSuccess) return hip_fail(h, e);
+        if ((e = hipEventElapsedTime(&ms_out[i], h->ev[2 * i], h->ev[2 * i + 1])) != hipSuccess) return hip_fail(h, e);
     return FFTCONV_OK;
 }
 

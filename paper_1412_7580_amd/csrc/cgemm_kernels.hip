@@ -226,7 +226,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
 }
 
 template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int NBUF = 2>
-static hipError_t run_gemm(GemmParams prm, hipStream_t st) {
+static hipError_t run_gemm(GemmParams prm, LaunchCtx st) {
     constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32;
     prm.tiles_m = (prm.M + TM - 1) / TM;
     prm.tiles_n = (prm.N + TN - 1) / TN;
@@ -237,7 +237,7 @@ static hipError_t run_gemm(GemmParams prm, hipStream_t st) {
         hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, st, prm);
+    launch_kernel(k, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, st, prm);
     return hipGetLastError();
 }
 
@@ -245,7 +245,7 @@ static hipError_t run_gemm(GemmParams prm, hipStream_t st) {
 // 5 32x64/2, 6 64x32/2, 7 32x32/1, 8 64x64/4 with TK 32, 9 64x64/2, 10 64x128/8, 11 128x64/8,
 // 12 128x128/8.
 template <bool AKF, bool BKF, bool VEC>
-static hipError_t dispatch_tile(int shape, GemmParams prm, hipStream_t st) {
+static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
     switch (shape) {
         case 0: return run_gemm<2, 2, 2, 2, 16, AKF, BKF, VEC, 1>(prm, st);
         case 1: return run_gemm<2, 2, 1, 2, 16, AKF, BKF, VEC, 2>(prm, st);
@@ -277,7 +277,7 @@ static int pick_tile(int M, int N, int bins) {
 }
 
 hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
-                             long C_cs, int M, int N, int K, int bins, hipStream_t st) {
+                             long C_cs, int M, int N, int K, int bins, LaunchCtx st) {
     if (bins % kXcds != 0) return hipErrorInvalidValue;   // N*(N/2+1) with N >= 8 always is
     GemmParams prm;
     prm.A = A.ptr; prm.B = B.ptr; prm.C = C;

@@ -606,7 +606,7 @@ int fft2d_tile_log2(int N) {
 
 template <int L, int G, int T>
 static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, int w_in,
-                            bool conv, bool conj, hipStream_t st) {
+                            bool conv, bool conj, LaunchCtx st) {
     constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
     Fwd2dParams prm;
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_in = h_in; prm.w_in = w_in;
@@ -635,7 +635,7 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
     hipError_t e;
     auto go = [&](auto k) -> hipError_t {
         if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
-        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
+        launch_kernel(k, dim3(grid), dim3(BT), lds, st, prm);
         return hipGetLastError();
     };
     if (conv) return go(fft2d_r2c_kernel<L, G, T, true, false>);
@@ -643,7 +643,7 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
 }
 
 hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
-                            bool conv, bool conj, hipStream_t st) {
+                            bool conv, bool conj, LaunchCtx st) {
     if (planes <= 0) return hipSuccess;
     switch (N) {
         case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, conj, st);
@@ -657,7 +657,7 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
 
 template <int L, int G, int T>
 static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out, int w_out,
-                            bool conv, float scale, bool accumulate, hipStream_t st) {
+                            bool conv, float scale, bool accumulate, LaunchCtx st) {
     constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
     Inv2dParams prm;
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_out = h_out; prm.w_out = w_out;
@@ -678,17 +678,17 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     if (conv) {
         auto k = fft2d_c2r_kernel<L, G, T, true>;
         if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
-        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
+        launch_kernel(k, dim3(grid), dim3(BT), lds, st, prm);
     } else {
         auto k = fft2d_c2r_kernel<L, G, T, false>;
         if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
-        hipLaunchKernelGGL(k, dim3(grid), dim3(BT), lds, st, prm);
+        launch_kernel(k, dim3(grid), dim3(BT), lds, st, prm);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int h_out, int w_out,
-                            bool conv, float scale, bool accumulate, hipStream_t st) {
+                            bool conv, float scale, bool accumulate, LaunchCtx st) {
     if (planes <= 0) return hipSuccess;
     switch (N) {
         case 8: return run_inv2d<8, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
@@ -701,7 +701,7 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
 }
 
 template <int L, int G, int TB>
-static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, hipStream_t st) {
+static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, LaunchCtx st) {
     constexpr int N = L * G, NB = N / 2 + 1, BT = TB / 2 * G;
     Fwd1dParams prm;
     prm.in = in; prm.out = out; prm.B = B; prm.n_in = n_in; prm.RS = n_in | 1;
@@ -714,11 +714,11 @@ static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, hipSt
     auto k = fft1d_r2c_kernel<L, G, TB>;
     hipError_t e;
     if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
-    hipLaunchKernelGGL(k, dim3((unsigned)((B + TB - 1) / TB)), dim3(BT), lds, st, prm);
+    launch_kernel(k, dim3((unsigned)((B + TB - 1) / TB)), dim3(BT), lds, st, prm);
     return hipGetLastError();
 }
 
-hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, hipStream_t st) {
+hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st) {
     if (B <= 0) return hipSuccess;
     switch (n) {
         case 8: return run_fwd1d<8, 1, 512>(in, out, B, n_in, st);
@@ -731,7 +731,7 @@ hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n
 }
 
 template <int L, int G, int TB>
-static hipError_t run_inv1d(const float *in, float *out, long B, int n_out, hipStream_t st) {
+static hipError_t run_inv1d(const float *in, float *out, long B, int n_out, LaunchCtx st) {
     constexpr int N = L * G, NB = N / 2 + 1, BT = TB / 2 * G;
     Inv1dParams prm;
     prm.in = in; prm.out = out; prm.B = B; prm.n_out = n_out; prm.scale = 1.0f / (float)N;
@@ -742,11 +742,11 @@ static hipError_t run_inv1d(const float *in, float *out, long B, int n_out, hipS
     auto k = fft1d_c2r_kernel<L, G, TB>;
     hipError_t e;
     if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
-    hipLaunchKernelGGL(k, dim3((unsigned)((B + TB - 1) / TB)), dim3(BT), lds, st, prm);
+    launch_kernel(k, dim3((unsigned)((B + TB - 1) / TB)), dim3(BT), lds, st, prm);
     return hipGetLastError();
 }
 
-hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, hipStream_t st) {
+hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st) {
     if (B <= 0) return hipSuccess;
     switch (n) {
         case 8: return run_inv1d<8, 1, 512>(in, out, B, n_out, st);

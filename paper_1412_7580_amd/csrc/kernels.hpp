@@ -1,9 +1,24 @@
 // Internal launch interface between the C ABI (api.hip) and the kernel files.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 
 namespace fc {
+
+// Where a kernel is launched and, optionally, a pair of events that the runtime attaches to
+// that one dispatch (their elapsed time is the kernel's own execution time, without the gaps
+// that events recorded between launches would include).
+struct LaunchCtx {
+    hipStream_t stream;
+    hipEvent_t start, stop;
+};
+
+template <class K, class P>
+inline void launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const LaunchCtx &lc, const P &prm) {
+    if (lc.start) hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, lc.stream, lc.start, lc.stop, 0, prm);
+    else hipLaunchKernelGGL(kernel, grid, block, lds, lc.stream, prm);
+}
 
 // Private frequency-domain layout used between the FFT stages and the contraction
 // ("plane-tiled, bin-major, planar"):
@@ -34,15 +49,15 @@ int fft2d_tile_log2(int N);
 //                imaginary parts on store (used where a pass needs the conjugate operand).
 //   natural layout: out = [planes][N][N/2+1][2].
 hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
-                            bool conv_layout, bool conj_out, hipStream_t st);
+                            bool conv_layout, bool conj_out, LaunchCtx st);
 
 // 2-D C2R + crop.  out[planes][h_out][w_out] = scale * real inverse (the caller folds 1/N^2
 // into `scale`), added to the previous contents when accumulate is set.
 hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int h_out, int w_out,
-                            bool conv_layout, float scale, bool accumulate, hipStream_t st);
+                            bool conv_layout, float scale, bool accumulate, LaunchCtx st);
 
-hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, hipStream_t st);
-hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, hipStream_t st);
+hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
+hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);
 
 // Per-bin complex contraction  C[b](m,n) = sum_k A[b](m,k) * B[b](k,n)  over all bins.
 // Operand element (row r, col c) of X lives at plane  r * X_rs + c * X_cs  of its layout.
@@ -52,6 +67,6 @@ struct GemmOperand {
     long rs, cs;       // plane strides of the (row, col) indices
 };
 hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
-                             long C_cs, int M, int N, int K, int bins, hipStream_t st);
+                             long C_cs, int M, int N, int K, int bins, LaunchCtx st);
 
 }  // namespace fc
