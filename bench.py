@@ -26,6 +26,17 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 
 STAGES = ("fft_a", "fft_b", "contraction", "ifft")
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
+# scaled by what the same counters read for a plain 256 MiB copy: x2.00 and x1.00); the runs
+# and the table are in profiles/c2_hbm_traffic.md.  Keyed by workload, then "pass.stage".
+MEASURED_TRAFFIC_BYTES = {
+    "C2": {
+        "fprop.contraction": (2.616e4 * 2.0 + 3.482e4) * 1024,
+        "bprop.contraction": (2.617e4 * 2.0 + 3.482e4) * 1024,
+        "accgrad.contraction": (3.487e4 * 2.0 + 1.741e4) * 1024,
+    },
+}
+
 
 def stage_model(cfg, pass_name):
     """Algorithmic bytes (FFT stages) and executed flops (contraction) of one pass."""
@@ -246,6 +257,9 @@ def main():
         kn = "fft2d_c2r_kernel" if ds == "ifft" else "fft2d_r2c_kernel"
         roof = {"kernel": f"{dom} ({kn})", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+    tr = MEASURED_TRAFFIC_BYTES.get(name, {}).get(dom)
+    roof["traffic"] = None if tr is None else round(tr)
+    roof["algorithmic_bytes"] = model["bytes"]
     roof["avg_launch_ms"] = dms
     roof["launches_averaged"] = prof_steps
 
