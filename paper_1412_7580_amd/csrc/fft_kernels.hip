@@ -308,7 +308,7 @@ struct Inv2dParams {
     int in_vec_ok;    // natural layout only: input base is 16-byte aligned
 };
 
-template <int L, int G, int T, bool CONV>
+template <int L, int G, int T, bool CONV, bool ISTAGE>
 __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dParams prm) {
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
     extern __shared__ float smem[];
@@ -328,15 +328,19 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
         int cg, cp, cc;
         if constexpr (CONV) { cg = tid % G; cp = (tid / G) % T; cc = tid / (G * T); }
         else { cg = tid % G; cc = (tid / G) % NH; cp = tid / (G * NH); }
-        if constexpr (!CONV) {
-            stage_linear<BT>(smem, prm.in + (size_t)p0 * N * NB * 2, (unsigned)np * N * NB * 2, tid,
-                             prm.in_vec_ok != 0);
+        if constexpr (ISTAGE) {
+            if constexpr (CONV)   // whole tile (its padding planes are simply not used)
+                stage_linear<BT>(smem, prm.in + prm.lay.index(p0, 0, 0), (unsigned)T * N * NB * 2, tid,
+                                 prm.in_vec_ok != 0);
+            else
+                stage_linear<BT>(smem, prm.in + (size_t)p0 * N * NB * 2, (unsigned)np * N * NB * 2, tid,
+                                 prm.in_vec_ok != 0);
             __syncthreads();
         }
         float cre[L], cim[L];
         if (cp < np) {
             if constexpr (CONV) {
-                const float *base = prm.in + prm.lay.index(p0, 0, 0) + cp;
+                const float *base = (ISTAGE ? smem : prm.in + prm.lay.index(p0, 0, 0)) + cp;
                 const int tsh = prm.lay.tsh;
 #pragma unroll
                 for (int m = 0; m < L; ++m) {
@@ -365,7 +369,7 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
             }
             fft_group<L, G, +1>(cre, cim, cg);
         }
-        if constexpr (!CONV) __syncthreads();   // staged input fully consumed; `mid` overlays it
+        if constexpr (ISTAGE) __syncthreads();   // staged input fully consumed; `mid` overlays it
         if (cp < np) {
             float2 *mp = mid + cp * prm.MPS + cc;
 #pragma unroll
@@ -669,22 +673,23 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     prm.in_vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)T * prm.MPS * sizeof(float2), b = (size_t)T * h_out * w_out * sizeof(float);
     size_t lds = a > b ? a : b;
-    if (!conv) {
+    // Stage the block's (contiguous) input through LDS with 16-byte loads: always for the
+    // natural layout; for the plane-tiled layout it measured faster except for the small
+    // bases when most of the output is kept.
+    const bool istage = !conv || N >= 32 || 2 * h_out <= N;
+    if (istage) {
         const size_t c = (size_t)T * N * (NH + 1) * sizeof(float2);
         if (c > lds) lds = c;
     }
     const unsigned grid = (unsigned)((planes + T - 1) / T);
     hipError_t e;
-    if (conv) {
-        auto k = fft2d_c2r_kernel<L, G, T, true>;
+    auto go = [&](auto k) -> hipError_t {
         if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
         launch_kernel(k, dim3(grid), dim3(BT), lds, st, prm);
-    } else {
-        auto k = fft2d_c2r_kernel<L, G, T, false>;
-        if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
-        launch_kernel(k, dim3(grid), dim3(BT), lds, st, prm);
-    }
-    return hipGetLastError();
+        return hipGetLastError();
+    };
+    if (conv) return istage ? go(fft2d_c2r_kernel<L, G, T, true, true>) : go(fft2d_c2r_kernel<L, G, T, true, false>);
+    return go(fft2d_c2r_kernel<L, G, T, false, true>);
 }
 
 hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int h_out, int w_out,
