@@ -15,23 +15,14 @@
 // on XCD i % 8), so that the tiles of one bin, and neighbouring bins that share cache
 // lines in the plane-tiled layout, meet in the same L2.
 #include "kernels.hpp"
+#include "gemm_params.hpp"
 
 #include <cstdlib>
 
 namespace fc {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-struct GemmParams {
-    const float *A, *B;
-    float *C;
-    FreqLayout layA, layB, layC;
-    long a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;
-    int M, N, K, bins;
-    int tiles_m, tiles_n;
-};
 
-constexpr int kXcds = 8;
 
 // Loader of one operand tile (ROWS x TK) with the "row" index being m (or n) and the
 // reduction index k.  KF: k is the contiguous plane index (else the row index is).
@@ -241,9 +232,9 @@ static hipError_t run_gemm(GemmParams prm, LaunchCtx st) {
     return hipGetLastError();
 }
 
-// Tile shapes (M x N, waves): 0 128x128/4, 1 64x128/4, 2 128x64/4, 3 64x64/4, 4 32x128/4,
-// 5 32x64/2, 6 64x32/2, 7 32x32/1, 8 64x64/4 with TK 32, 9 64x64/2, 10 64x128/8, 11 128x64/8,
-// 12 128x128/8.
+// Tile shapes (M x N on four waves): 0 128x128, 1 64x128, 2 128x64, 3 64x64, 4 64x64 with a
+// single LDS buffer.  1-, 2- and 8-wave workgroups and TK = 8 / 32 were also measured; none
+// beat shape 3.
 template <bool AKF, bool BKF, bool VEC>
 static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
     switch (shape) {
@@ -251,22 +242,12 @@ static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
         case 1: return run_gemm<2, 2, 1, 2, 16, AKF, BKF, VEC, 2>(prm, st);
         case 2: return run_gemm<2, 2, 2, 1, 16, AKF, BKF, VEC, 2>(prm, st);
         case 3: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3>(prm, st);
-        case 4: return run_gemm<1, 4, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
-        case 5: return run_gemm<1, 2, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
-        case 6: return run_gemm<2, 1, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
-        case 7: return run_gemm<1, 1, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
-        case 8: return run_gemm<2, 2, 1, 1, 32, AKF, BKF, VEC, 3>(prm, st);
-        case 9: return run_gemm<1, 2, 2, 1, 16, AKF, BKF, VEC, 3>(prm, st);
-        case 10: return run_gemm<2, 4, 1, 1, 16, AKF, BKF, VEC, 3>(prm, st);
-        case 11: return run_gemm<4, 2, 1, 1, 16, AKF, BKF, VEC, 3>(prm, st);
-        case 12: return run_gemm<2, 4, 2, 1, 16, AKF, BKF, VEC, 2>(prm, st);
-        case 13: return run_gemm<2, 2, 1, 1, 8, AKF, BKF, VEC, 3, 2>(prm, st);
-        case 14: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3, 1>(prm, st);
-        case 15: return run_gemm<2, 2, 1, 1, 32, AKF, BKF, VEC, 3, 1>(prm, st);
-        case 16: return run_gemm<2, 2, 2, 2, 16, AKF, BKF, VEC, 2, 1>(prm, st);
+        case 4: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3, 1>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
+
+hipError_t launch_cgemm_bingroup(const GemmParams &prm, bool akf, bool bkf, LaunchCtx st);
 
 static int pick_tile(int M, int N, int bins) {
     if (const char *e = getenv("FFTCONV_GEMM_TILE")) return atoi(e);
@@ -295,6 +276,14 @@ hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout 
     const bool vb = bkf ? vec_ok(B.lay, K, B.cs, B.ptr) : (B.cs == 1 && vec_ok(B.lay, N, B.rs, B.ptr));
     const bool vec = va && vb;
     const int shape = pick_tile(M, N, bins);
+    // Layouts with runs of 4 planes (basis 64) put four bins in every 128-byte line: the
+    // bin-group kernel loads whole lines and multiplies the four bins side by side.
+    const char *no_bg_env = getenv("FFTCONV_GEMM_NO_BINGROUP");
+    const bool no_bg = no_bg_env && atoi(no_bg_env);
+    if (vec && !no_bg && A.lay.tsh == 2 && B.lay.tsh == 2 && layC.tsh == 2 && bins % (4 * kXcds) == 0 &&
+        (akf || A.rs == 1) && (bkf || B.cs == 1) && C_cs == 1 && C_rs % 4 == 0 && N % 4 == 0 &&
+        ((size_t)C & 15) == 0)
+        return launch_cgemm_bingroup(prm, akf, bkf, st);
     if (vec) {
         if (akf && bkf) return dispatch_tile<true, true, true>(shape, prm, st);
         if (akf && !bkf) return dispatch_tile<true, false, true>(shape, prm, st);
