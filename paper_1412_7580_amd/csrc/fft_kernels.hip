@@ -106,20 +106,22 @@ struct Fwd2dParams {
     int out_vec_ok;   // output base and every block start are 16-byte aligned
 };
 
-// Store helpers for the two output layouts.
-template <int N, bool CONV>
+// Store helpers for the two output layouts.  `base` is uniform over the workgroup (block
+// or LDS image start) and the lane's part of the address is a 32-bit element offset, so that a
+// store costs one 32-bit add instead of 64-bit pointer arithmetic.
+template <int N, int T, bool CONV>
 struct BinStore {
-    float *base;        // CONV: tile base + lane's plane offset; natural: plane base
-    int tsh;
+    float *base;
+    unsigned lane_off;  // CONV: plane within the tile; natural: plane * N * (N/2+1) (in float2)
     float im_sign;
     __device__ __forceinline__ void operator()(int k1, int k2, float re, float im) const {
         constexpr int NB = N / 2 + 1;
         if constexpr (CONV) {
-            float *q = base + ((size_t)((k1 * NB + k2) * 2) << tsh);
-            q[0] = re;
-            q[(size_t)1 << tsh] = im_sign * im;
+            const unsigned idx = lane_off + (unsigned)((k1 * NB + k2) * 2) * T;
+            base[idx] = re;
+            base[idx + T] = im_sign * im;
         } else {
-            reinterpret_cast<float2 *>(base)[k1 * NB + k2] = make_float2(re, im);
+            reinterpret_cast<float2 *>(base)[lane_off + (unsigned)(k1 * NB + k2)] = make_float2(re, im);
         }
     }
 };
@@ -180,6 +182,9 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
     float are[NA], aim[NA], bre[NBR], bim[NBR];
     if (row_active) {
         float re[L], im[L];
+        // (Conditional reads: the compiler turns them into uniform branches that skip the
+        // loads of the zero padding; measured faster than unconditional reads plus selects,
+        // which cost registers and occupancy on the two-lane kernels.)
         const float *pa = sin + p * prm.IPS + ra * prm.RS;
         const float *pb = sin + p * prm.IPS + rb * prm.RS;
 #pragma unroll
@@ -236,17 +241,15 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
     // Results go either straight to global memory or, when OSTAGE, into an LDS image of the
     // block's output (which is one contiguous range in both layouts) that is then written
     // out with 16-byte coalesced stores.
-    BinStore<N, CONV> st;
+    BinStore<N, T, CONV> st;
     st.im_sign = prm.im_sign;
+    st.lane_off = CONV ? (unsigned)cp : (unsigned)cp * N * NB;
     if constexpr (OSTAGE) {
         __syncthreads();   // every lane has read `mid`; the image overlays it
-        st.tsh = prm.lay.tsh;
-        if constexpr (CONV) st.base = smem + cp;
-        else st.base = smem + (size_t)cp * N * NB * 2;
+        st.base = smem;
     } else {
-        st.tsh = prm.lay.tsh;
-        if constexpr (CONV) st.base = prm.out + prm.lay.index(p0, 0, 0) + cp;
-        else st.base = prm.out + (size_t)(p0 + cp) * N * NB * 2;
+        if constexpr (CONV) st.base = prm.out + prm.lay.index(p0, 0, 0);
+        else st.base = prm.out + (size_t)p0 * N * NB * 2;
     }
 
     if (col_active) {
@@ -390,14 +393,14 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
     float re[L], im[L];
     if (active) {
         const float2 *A = mid + p * prm.MPS + ra * NH;
-        const float2 *B = mid + p * prm.MPS + rb * NH;
+        const float2 *B = mid + p * prm.MPS + (hasb ? rb : ra) * NH;
 #pragma unroll
         for (int m = 0; m < L; ++m) {
             const int k2 = g + G * m;
             const int slot = (k2 == NH) ? 0 : (k2 < NH ? k2 : N - k2);
             const float2 a = A[slot];
-            float2 b = make_float2(0.f, 0.f);
-            if (hasb) b = B[slot];
+            float2 b = B[slot];
+            if (!hasb) b = make_float2(0.f, 0.f);
             float xr, xi;
             if (k2 == 0) { xr = a.x; xi = b.x; }
             else if (k2 == NH) { xr = a.y; xi = b.y; }
@@ -485,13 +488,14 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) 
     float are[NA], aim[NA], bre[NBR], bim[NBR];
     if (active) {
         float re[L], im[L];
-        const float *pa = sin + sa * prm.RS, *pb = sin + sb * prm.RS;
+        const float *pa = sin + sa * prm.RS, *pb = sin + (hasb ? sb : sa) * prm.RS;
 #pragma unroll
         for (int m = 0; m < L; ++m) {
             const int j = g + G * m;
+            const float va = pa[j], vb = pb[j];     // unconditional; LDS has N floats of slack
             const bool in = j < n_in;
-            re[m] = in ? pa[j] : 0.f;
-            im[m] = (in && hasb) ? pb[j] : 0.f;
+            re[m] = in ? va : 0.f;
+            im[m] = (in && hasb) ? vb : 0.f;
         }
         fft_group<L, G, -1>(re, im, g);
         split_two_real<L, G>(re, im, g, are, aim, bre, bim);
@@ -561,14 +565,14 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_c2r_kernel(Inv1dParams prm) 
     const bool active = sa < nb, hasb = sb < nb;
     float re[L], im[L];
     if (active) {
-        const float2 *A = sin + sa * NB, *Bp = sin + sb * NB;
+        const float2 *A = sin + sa * NB, *Bp = sin + (hasb ? sb : sa) * NB;
 #pragma unroll
         for (int m = 0; m < L; ++m) {
             const int k2 = g + G * m;
             const int slot = k2 <= NH ? k2 : N - k2;
             float2 a = A[slot];
-            float2 b = make_float2(0.f, 0.f);
-            if (hasb) b = Bp[slot];
+            float2 b = Bp[slot];
+            if (!hasb) b = make_float2(0.f, 0.f);
             if (k2 == 0 || k2 == NH) { a.y = 0.f; b.y = 0.f; }
             else if (k2 > NH) { a.y = -a.y; b.y = -b.y; }
             re[m] = a.x - b.y;
@@ -625,7 +629,7 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
     prm.linear = (prm.RS == w_in && prm.IPS == h_in * w_in) ? 1 : 0;
     prm.vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * h_in * w_in) % 4 == 0) ? 1 : 0;
     prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
-    const size_t a = (size_t)T * prm.IPS * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
+    const size_t a = ((size_t)T * prm.IPS + N) * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
     size_t lds = a > b ? a : b;
     // Measured: staging the output through LDS pays for the natural layout (short runs per
     // lane otherwise) and costs for the plane-tiled layout, whose direct stores already fill
@@ -714,7 +718,7 @@ static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, Launc
     prm.linear = (prm.RS == n_in) ? 1 : 0;
     prm.vec_ok = (((size_t)in & 15) == 0 && ((size_t)TB * n_in) % 4 == 0) ? 1 : 0;
     prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)TB * NB * 2) % 4 == 0) ? 1 : 0;
-    const size_t a = (size_t)TB * prm.RS * sizeof(float), b = (size_t)TB * NB * sizeof(float2);
+    const size_t a = ((size_t)TB * prm.RS + N) * sizeof(float), b = (size_t)TB * NB * sizeof(float2);
     const size_t lds = a > b ? a : b;
     auto k = fft1d_r2c_kernel<L, G, TB>;
     hipError_t e;
