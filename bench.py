@@ -54,7 +54,9 @@ def stage_model(cfg, pass_name):
     return {
         "fft_a": {"bytes": fwd(A)},
         "fft_b": {"bytes": fwd(B)},
-        "contraction": {"flops": 8 * M * Nn * K * bins,
+        # executed real flops: three real multiply-adds per complex one (Gauss's 3-multiplication
+        # product), i.e. 6 M N K per bin; a plain 4-multiplication product would execute 8 M N K
+        "contraction": {"flops": 6 * M * Nn * K * bins,
                         "bytes": 8 * bins * (A[0] + B[0] + C[0])},
         "ifft": {"bytes": C[0] * (8 * bins + 4 * C[1] * C[2])},
     }

@@ -62,7 +62,7 @@ struct GroupLoader {
 };
 
 template <int FM, int FN, int TK, bool AKF, bool BKF>
-__global__ void __launch_bounds__(256) cgemm_bingroup_kernel(GemmParams prm) {
+__global__ void __launch_bounds__(256, (FM * FN == 1 && AKF == BKF ? 4 : 1)) cgemm_bingroup_kernel(GemmParams prm) {
     constexpr int TM = 32 * FM, TN = 32 * FN;
     constexpr int SA = TM + 2, SB = TN + 2;
     // region strides: odd (scalar transposing stores spread over banks) or even (float2 stores)
@@ -80,13 +80,15 @@ __global__ void __launch_bounds__(256) cgemm_bingroup_kernel(GemmParams prm) {
     const int m0 = (tile / prm.tiles_n) * TM, n0 = (tile % prm.tiles_n) * TN;
     const int M = prm.M, N = prm.N, K = prm.K, bins = prm.bins;
 
-    floatx16 acc_re[FM][FN], acc_im[FM][FN];
+    // Three real products per complex product (Gauss): P1 = Ar Br, P2 = Ai Bi,
+    // P3 = (Ar + Ai)(Br + Bi);  Cr = P1 - P2,  Ci = P3 - P1 - P2.
+    floatx16 acc_p1[FM][FN], acc_p2[FM][FN], acc_p3[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { acc_re[i][j][v] = 0.f; acc_im[i][j][v] = 0.f; }
+            for (int v = 0; v < 16; ++v) { acc_p1[i][j][v] = 0.f; acc_p2[i][j][v] = 0.f; acc_p3[i][j][v] = 0.f; }
 
     GroupLoader<TM, TK, SA, RA, AKF> la;
     GroupLoader<TN, TK, SB, RB, BKF> lb;
@@ -108,26 +110,26 @@ __global__ void __launch_bounds__(256) cgemm_bingroup_kernel(GemmParams prm) {
         }
 #pragma unroll
         for (int ks = 0; ks < TK; ks += 2) {
-            float a_re[FM], a_im[FM], a_in[FM], b_re[FN], b_im[FN];
+            float a_re[FM], a_im[FM], a_sm[FM], b_re[FN], b_im[FN], b_sm[FN];
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 a_re[i] = a0[(ks + lk) * SA + i * 32];
                 a_im[i] = a0[RA + (ks + lk) * SA + i * 32];
-                a_in[i] = -a_im[i];
+                a_sm[i] = a_re[i] + a_im[i];
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 b_re[j] = b0p[(ks + lk) * SB + j * 32];
                 b_im[j] = b0p[RB + (ks + lk) * SB + j * 32];
+                b_sm[j] = b_re[j] + b_im[j];
             }
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
-                    acc_re[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re[i], b_re[j], acc_re[i][j], 0, 0, 0);
-                    acc_im[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re[i], b_im[j], acc_im[i][j], 0, 0, 0);
-                    acc_re[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_in[i], b_im[j], acc_re[i][j], 0, 0, 0);
-                    acc_im[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im[i], b_re[j], acc_im[i][j], 0, 0, 0);
+                    acc_p1[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re[i], b_re[j], acc_p1[i][j], 0, 0, 0);
+                    acc_p2[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im[i], b_im[j], acc_p2[i][j], 0, 0, 0);
+                    acc_p3[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_sm[i], b_sm[j], acc_p3[i][j], 0, 0, 0);
                 }
         }
         if (more) {
@@ -155,8 +157,9 @@ __global__ void __launch_bounds__(256) cgemm_bingroup_kernel(GemmParams prm) {
             for (int v = 0; v < 16; ++v) {
                 const int mm = i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
                 float *q = img + (mm * NQ + (nn >> 2)) * LSTR + wave * 8 + (nn & 3);
-                q[0] = acc_re[i][j][v];
-                q[4] = acc_im[i][j][v];
+                const float p1 = acc_p1[i][j][v], p2 = acc_p2[i][j][v];
+                q[0] = p1 - p2;
+                q[4] = acc_p3[i][j][v] - p1 - p2;
             }
         }
     __syncthreads();

@@ -3,8 +3,9 @@
 // This is the Cgemm step of Table 1 of the fbfft paper (one small complex matrix product
 // per frequency bin, reducing over f for fprop, f' for bprop and S for accGrad), done as one
 // launch over all bins instead of a batched library call on transposed tensors.  A complex
-// product is four real MFMA products on planar operands:
-//     Cr += Ar*Br + (-Ai)*Bi ,   Ci += Ar*Bi + Ai*Br
+// product is three real MFMA products on planar operands (Gauss's trick; the operand sums
+// are one VALU add per value read from LDS):
+//     P1 += Ar*Br,  P2 += Ai*Bi,  P3 += (Ar+Ai)*(Br+Bi);   Cr = P1 - P2,  Ci = P3 - P1 - P2
 // Operands are gathered straight from the FFT kernels' plane-tiled layout (kernels.hpp), so
 // the three explicit transposes of the paper's pipeline never exist.
 //
@@ -18,8 +19,17 @@
 #include "gemm_params.hpp"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace fc {
+
+template <int I, int E, class F>
+__device__ __forceinline__ void static_for_gemm(F &&f) {
+    if constexpr (I < E) {
+        f(std::integral_constant<int, I>{});
+        static_for_gemm<I + 1, E>(f);
+    }
+}
 
 
 
@@ -107,7 +117,7 @@ struct TileLoader {
     }
 };
 
-template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int NBUF>
+template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int PD>
 __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmParams prm) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32;
@@ -115,7 +125,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
     constexpr int ABUF = 2 * TK * SA, BBUF = 2 * TK * SB;
     extern __shared__ float smem[];
     float *As = smem;                 // [2 buffers][2 comps][TK][SA]
-    float *Bs = smem + NBUF * ABUF;   // [NBUF buffers][2 comps][TK][SB]
+    float *Bs = smem + 2 * ABUF;      // [2 buffers][2 comps][TK][SB]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -130,71 +140,82 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
     const int m0 = tm * TM, n0 = tn * TN;
     const int M = prm.M, N = prm.N, K = prm.K;
 
-    floatx16 acc_re[FM][FN], acc_im[FM][FN];
+    // Three real products per complex product (Gauss): P1 = Ar Br, P2 = Ai Bi,
+    // P3 = (Ar + Ai)(Br + Bi);  Cr = P1 - P2,  Ci = P3 - P1 - P2.
+    floatx16 acc_p1[FM][FN], acc_p2[FM][FN], acc_p3[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { acc_re[i][j][v] = 0.f; acc_im[i][j][v] = 0.f; }
+            for (int v = 0; v < 16; ++v) { acc_p1[i][j][v] = 0.f; acc_p2[i][j][v] = 0.f; acc_p3[i][j][v] = 0.f; }
 
-    TileLoader<TM, TK, SA, AKF, VEC, NT> la;
-    TileLoader<TN, TK, SB, BKF, VEC, NT> lb;
-
+    // Register staging for PD tiles ahead: tile t travels global -> la/lb[t % PD] -> LDS buffer
+    // t % 2.  With a short reduction (K of a few tiles) every gather is in flight before the
+    // first MFMA; with a long one a single tile ahead is enough.
+    TileLoader<TM, TK, SA, AKF, VEC, NT> la[PD];
+    TileLoader<TN, TK, SB, BKF, VEC, NT> lb[PD];
     const int nkt = (K + TK - 1) / TK;
-    la.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, 0, M, K, tid);
-    // B(k, n): row index of the loader is n, so swap the strides
-    lb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, 0, N, K, tid);
-    la.store(As, tid);
-    lb.store(Bs, tid);
+    auto issue = [&](auto &xa, auto &xb, int kt) {
+        xa.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, kt * TK, M, K, tid);
+        // B(k, n): row index of the loader is n, so swap the strides
+        xb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, kt * TK, N, K, tid);
+    };
+    static_for_gemm<0, PD>([&](auto dd) {
+        constexpr int d = decltype(dd)::value;
+        if (d < nkt) issue(la[d], lb[d], d);
+    });
+    la[0].store(As, tid);
+    lb[0].store(Bs, tid);
+    if (PD < nkt) issue(la[0], lb[0], PD);
     __syncthreads();
 
     const int lrow = lane & 31, lk = lane >> 5;
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int cur = (NBUF == 2) ? (kt & 1) : 0;
-        if (kt + 1 < nkt) {
-            la.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, (kt + 1) * TK, M, K, tid);
-            lb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, (kt + 1) * TK, N, K, tid);
-        }
+    auto compute = [&](int cur) {
         const float *a0 = As + cur * ABUF + (wm * FM * 32 + lrow);
         const float *b0 = Bs + cur * BBUF + (wn * FN * 32 + lrow);
 #pragma unroll
         for (int ks = 0; ks < TK; ks += 2) {
-            float a_re[FM], a_im[FM], a_in[FM], b_re[FN], b_im[FN];
+            float a_re[FM], a_im[FM], a_sm[FM], b_re[FN], b_im[FN], b_sm[FN];
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 a_re[i] = a0[(ks + lk) * SA + i * 32];
                 a_im[i] = a0[TK * SA + (ks + lk) * SA + i * 32];
-                a_in[i] = -a_im[i];
+                a_sm[i] = a_re[i] + a_im[i];
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 b_re[j] = b0[(ks + lk) * SB + j * 32];
                 b_im[j] = b0[TK * SB + (ks + lk) * SB + j * 32];
+                b_sm[j] = b_re[j] + b_im[j];
             }
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
-                    acc_re[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re[i], b_re[j], acc_re[i][j], 0, 0, 0);
-                    acc_im[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re[i], b_im[j], acc_im[i][j], 0, 0, 0);
-                    acc_re[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_in[i], b_im[j], acc_re[i][j], 0, 0, 0);
-                    acc_im[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im[i], b_re[j], acc_im[i][j], 0, 0, 0);
+                    acc_p1[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re[i], b_re[j], acc_p1[i][j], 0, 0, 0);
+                    acc_p2[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im[i], b_im[j], acc_p2[i][j], 0, 0, 0);
+                    acc_p3[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_sm[i], b_sm[j], acc_p3[i][j], 0, 0, 0);
                 }
         }
-        if (kt + 1 < nkt) {
-            if constexpr (NBUF == 2) {
-                // the other buffer was last read in iteration kt-1, which every wave has left
-                la.store(As + (cur ^ 1) * ABUF, tid);
-                lb.store(Bs + (cur ^ 1) * BBUF, tid);
-                __syncthreads();
-            } else {
-                __syncthreads();
-                la.store(As, tid);
-                lb.store(Bs, tid);
-                __syncthreads();
+    };
+    for (int kt0 = 0; kt0 < nkt; kt0 += PD) {
+        static_for_gemm<0, PD>([&](auto dd) {
+            constexpr int d = decltype(dd)::value;
+            constexpr int dn = (d + 1) % PD;
+            const int kt = kt0 + d;
+            if (kt < nkt) {
+                const int cur = kt & 1;
+                compute(cur);
+                if (kt + 1 < nkt) {
+                    // buffer cur^1 was last read in iteration kt-1, which every wave has left
+                    la[dn].store(As + (cur ^ 1) * ABUF, tid);
+                    lb[dn].store(Bs + (cur ^ 1) * BBUF, tid);
+                    if (kt + 1 + PD < nkt) issue(la[dn], lb[dn], kt + 1 + PD);
+                    __syncthreads();
+                }
             }
-        }
+        });
     }
 
     // D layout of the 32x32x2 MFMA: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32.
@@ -209,21 +230,22 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
                 const int m = m0 + (wm * FM + i) * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
                 if (m < M && n < N) {
                     const size_t idx = prm.layC.index(m * prm.c_rs + n * prm.c_cs, bin, 0);
-                    prm.C[idx] = acc_re[i][j][v];
-                    prm.C[idx + cim] = acc_im[i][j][v];
+                    const float p1 = acc_p1[i][j][v], p2 = acc_p2[i][j][v];
+                    prm.C[idx] = p1 - p2;
+                    prm.C[idx + cim] = acc_p3[i][j][v] - p1 - p2;
                 }
             }
         }
 }
 
-template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int NBUF = 2>
+template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int PD = 1>
 static hipError_t run_gemm(GemmParams prm, LaunchCtx st) {
     constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32;
     prm.tiles_m = (prm.M + TM - 1) / TM;
     prm.tiles_n = (prm.N + TN - 1) / TN;
     const long grid = (long)prm.bins * prm.tiles_m * prm.tiles_n;
-    const size_t lds = (size_t)(NBUF * 2 * TK * (TM + 2) + NBUF * 2 * TK * (TN + 2)) * sizeof(float);
-    auto k = cgemm_bins_kernel<WGM, WGN, FM, FN, TK, AKF, BKF, VEC, MINB, NBUF>;
+    const size_t lds = (size_t)(2 * 2 * TK * (TM + 2) + 2 * 2 * TK * (TN + 2)) * sizeof(float);
+    auto k = cgemm_bins_kernel<WGM, WGN, FM, FN, TK, AKF, BKF, VEC, MINB, PD>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
@@ -232,8 +254,8 @@ static hipError_t run_gemm(GemmParams prm, LaunchCtx st) {
     return hipGetLastError();
 }
 
-// Tile shapes (M x N on four waves): 0 128x128, 1 64x128, 2 128x64, 3 64x64, 4 64x64 with a
-// single LDS buffer.  1-, 2- and 8-wave workgroups and TK = 8 / 32 were also measured; none
+// Tile shapes (M x N on four waves): 0 128x128, 1 64x128, 2 128x64, 3 64x64; 4 and 5 are 64x64
+// with 2 and 4 tiles of register staging ahead.  1-, 2- and 8-wave workgroups and TK = 8 / 32 were also measured; none
 // beat shape 3.
 template <bool AKF, bool BKF, bool VEC>
 static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
@@ -242,19 +264,21 @@ static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
         case 1: return run_gemm<2, 2, 1, 2, 16, AKF, BKF, VEC, 2>(prm, st);
         case 2: return run_gemm<2, 2, 2, 1, 16, AKF, BKF, VEC, 2>(prm, st);
         case 3: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3>(prm, st);
-        case 4: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3, 1>(prm, st);
+        case 4: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3, 2>(prm, st);
+        case 5: return run_gemm<2, 2, 1, 1, 16, AKF, BKF, VEC, 3, 4>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_cgemm_bingroup(const GemmParams &prm, bool akf, bool bkf, LaunchCtx st);
 
-static int pick_tile(int M, int N, int bins) {
+static int pick_tile(int M, int N, int K, int bins) {
     if (const char *e = getenv("FFTCONV_GEMM_TILE")) return atoi(e);
     (void)M; (void)N; (void)bins;
     // 64x64 tiles on four waves measured fastest for every layer shape tried (more
-    // workgroups in flight beat the larger tiles' operand reuse).
-    return 3;
+    // workgroups in flight beat the larger tiles' operand reuse); two tiles of register
+    // staging ahead pay off once the reduction is long.
+    return K >= 8 * 16 ? 4 : 3;
 }
 
 hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
@@ -275,7 +299,7 @@ hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout 
     const bool va = akf ? vec_ok(A.lay, K, A.rs, A.ptr) : (A.rs == 1 && vec_ok(A.lay, M, A.cs, A.ptr));
     const bool vb = bkf ? vec_ok(B.lay, K, B.cs, B.ptr) : (B.cs == 1 && vec_ok(B.lay, N, B.rs, B.ptr));
     const bool vec = va && vb;
-    const int shape = pick_tile(M, N, bins);
+    const int shape = pick_tile(M, N, K, bins);
     // Layouts with runs of 4 planes (basis 64) put four bins in every 128-byte line: the
     // bin-group kernel loads whole lines and multiplies the four bins side by side.
     const char *no_bg_env = getenv("FFTCONV_GEMM_NO_BINGROUP");
