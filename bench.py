@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix, published
 
-STAGES = ("fft_a", "fft_b", "contraction", "ifft")
+STAGES = ("fft", "contraction", "ifft")   # kernels of one pass, in launch order
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
 # scaled by what the same counters read for a plain 256 MiB copy: x2.00 and x1.00); the runs
@@ -52,6 +52,7 @@ def stage_model(cfg, pass_name):
         A, B, C, (M, Nn, K) = gy, x, wt, (fo, f, S)
     fwd = lambda t: t[0] * (4 * t[1] * t[2] + 8 * bins)
     return {
+        "fft": {"bytes": fwd(A) + fwd(B)},
         "fft_a": {"bytes": fwd(A)},
         "fft_b": {"bytes": fwd(B)},
         # executed real flops: three real multiply-adds per complex one (Gauss's 3-multiplication
@@ -67,7 +68,14 @@ def direct_flops(cfg):
     return 2 * S * f * fo * kh * kw * (h - kh + 1) * (w - kw + 1)
 
 
-def run_step(hd, t, cfg, passes):
+def run_step(hd, t, cfg, passes, reuse=False):
+    """One step.  reuse=True: fft_conv_fprop_save + fft_conv_backward (x and w are transformed
+    once, gy once); reuse=False: the three independent passes."""
+    if reuse and len(passes) == 3:
+        hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
+        hd.fft_conv_backward(t["gy"], t["saved"], cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"],
+                             gx=t["gx"], gw=t["gw"])
+        return
     if "fprop" in passes:
         hd.fft_conv_fprop(t["x"], t["w"], y=t["y"])
     if "bprop" in passes:
@@ -85,33 +93,62 @@ def device_tensors(cfg, seed):
     return t, (x, w, gy)
 
 
-def time_steps(hd, t, cfg, passes, steps, warmup):
+def add_saved(hd, t, cfg):
+    import torch
+    n = hd.saved_bytes(cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    t["saved"] = torch.empty(n // 4, device="cuda", dtype=torch.float32)
+
+
+def time_steps(hd, t, cfg, passes, steps, warmup, reuse=False):
     import torch
     for _ in range(warmup):
-        run_step(hd, t, cfg, passes)
+        run_step(hd, t, cfg, passes, reuse)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        run_step(hd, t, cfg, passes)
+        run_step(hd, t, cfg, passes, reuse)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps
 
 
 def profile_stages(hd, t, cfg, passes, steps):
-    """Average duration (ms) of each stage of each pass over `steps` repetitions of the timed
-    region, from the HIP events the library records on its stream around every launch."""
+    """Average execution time (ms) of each kernel of each pass over `steps` repetitions, from the
+    start/stop events the library attaches to every dispatch on its stream.
+    Returns {pass: [fft, contraction, ifft]}."""
     import torch
     hd.set_profiling(True)
-    acc = {p: [0.0] * 4 for p in passes}
+    acc = {p: [0.0] * 3 for p in passes}
     for _ in range(steps):
         for p in passes:
             run_step(hd, t, cfg, (p,))
-            ms = hd.last_stage_ms()
-            for i in range(4):
+            ms = hd.last_kernel_ms()
+            for i in range(3):
                 acc[p][i] += ms[i]
     hd.set_profiling(False)
     torch.cuda.synchronize()
     return {p: [v / steps for v in acc[p]] for p in passes}
+
+
+REUSE_KERNELS = ("fprop.fft", "fprop.contraction", "fprop.ifft", "backward.fft",
+                 "bprop.contraction", "bprop.ifft", "accgrad.contraction", "accgrad.ifft")
+
+
+def profile_reuse_step(hd, t, cfg, steps):
+    """Same for the two-call step with transform reuse: eight kernels, {name: ms}."""
+    import torch
+    hd.set_profiling(True)
+    acc = [0.0] * 8
+    for _ in range(steps):
+        hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
+        a = hd.last_kernel_ms()
+        hd.fft_conv_backward(t["gy"], t["saved"], cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"],
+                             gx=t["gx"], gw=t["gw"])
+        b = hd.last_kernel_ms()
+        for i, v in enumerate(a + b):
+            acc[i] += v
+    hd.set_profiling(False)
+    torch.cuda.synchronize()
+    return {k: v / steps for k, v in zip(REUSE_KERNELS, acc)}
 
 
 def cpu_baseline(cfg, host_inputs, budget_s=12.0):
@@ -196,6 +233,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-passes", action="store_true",
+                    help="time the three independent pass calls instead of fprop_save + backward")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the FFT sweep")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy a few times (reference for scaling the "
@@ -226,34 +265,55 @@ def main():
     passes = synth.CONV_CONFIGS[name]["passes"]
     t, host = device_tensors(cfg, synth.CONV_SEEDS[name])
 
-    sec = time_steps(hd, t, cfg, passes, args.steps, args.warmup)
+    reuse = (len(passes) == 3) and not args.separate_passes
+    if reuse:
+        add_saved(hd, t, cfg)
+    sec = time_steps(hd, t, cfg, passes, args.steps, args.warmup, reuse)
     flops = direct_flops(cfg) * len(passes)
     value = flops / sec / 1e12
 
-    # Per-kernel durations over a second run of the same region, with the library's events on.
+    # Per-kernel durations over a second run of the same region, with per-dispatch events on.
     prof_steps = max(1, min(args.steps, 50))
-    stage_ms = profile_stages(hd, t, cfg, passes, prof_steps)
     kernels = {}
-    for p in passes:
-        model = stage_model(cfg, p)
-        for i, s in enumerate(STAGES):
-            ms = stage_ms[p][i]
-            ent = {"ms": round(ms, 5)}
-            if s == "contraction":
-                ent["TFLOPs"] = round(model[s]["flops"] / ms / 1e9, 2)
-                ent["GBps"] = round(model[s]["bytes"] / ms / 1e6, 1)
+    models = {p: stage_model(cfg, p) for p in passes}
+
+    def entry(ms, model):
+        ent = {"ms": round(ms, 5), "GBps": round(model["bytes"] / ms / 1e6, 1)}
+        if "flops" in model:
+            ent["TFLOPs"] = round(model["flops"] / ms / 1e9, 2)
+        return ent
+
+    if reuse:
+        km = profile_reuse_step(hd, t, cfg, prof_steps)
+        for k, ms in km.items():
+            p, s_ = k.split(".")
+            if k == "fprop.fft":
+                model = models["fprop"]["fft"]
+            elif k == "backward.fft":
+                model = models["bprop"]["fft_a"]
             else:
-                ent["GBps"] = round(model[s]["bytes"] / ms / 1e6, 1)
-            kernels[f"{p}.{s}"] = ent
+                model = models[p][s_]
+            kernels[k] = entry(ms, model)
+            kernels[k]["_model"] = model
+    else:
+        stage_ms = profile_stages(hd, t, cfg, passes, prof_steps)
+        for p in passes:
+            for i, s_ in enumerate(STAGES):
+                kernels[f"{p}.{s_}"] = entry(stage_ms[p][i], models[p][s_])
+                kernels[f"{p}.{s_}"]["_model"] = models[p][s_]
     dom = max(kernels, key=lambda k: kernels[k]["ms"])
-    dp, ds = dom.split(".")
-    model = stage_model(cfg, dp)[ds]
+    ds = dom.split(".")[1]
+    model = kernels[dom]["_model"]
+    for k in kernels:
+        del kernels[k]["_model"]
     dms = kernels[dom]["ms"]
     if ds == "contraction":
         ach = model["flops"] / dms / 1e9
         roof = {"kernel": dom + " (cgemm_bins_kernel)", "bound": "mfma", "achieved": round(ach, 2),
                 "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
-                "traffic": None}
+                "traffic": None,
+                "note": "executed flops: 6 M N K per bin (3-multiplication complex product); "
+                        "the 4-multiplication equivalent rate is 4/3 of `achieved`"}
     else:
         ach = model["bytes"] / dms / 1e6
         kn = "fft2d_c2r_kernel" if ds == "ifft" else "fft2d_r2c_kernel"
@@ -272,7 +332,9 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{name}: S={cfg['S']} f={cfg['f']} f'={cfg['fo']} input {cfg['h']}x{cfg['w']} "
                                f"kernel {cfg['kh']}x{cfg['kw']} FFT {cfg['N']}x{cfg['N']}, passes " + "+".join(passes),
-                   "seed": synth.CONV_SEEDS[name]},
+                   "seed": synth.CONV_SEEDS[name],
+                   "calls": "fft_conv_fprop_save + fft_conv_backward (x, w, gy transformed once each)" if reuse
+                            else "fft_conv_fprop, fft_conv_bprop, fft_conv_accgrad (independent passes)"},
         "roofline": roof,
         "kernels": kernels,
     }
@@ -280,6 +342,10 @@ def main():
         out["cpu_baseline"] = cpu_baseline(cfg, host)
     if not args.no_extra:
         extra = {}
+        if reuse:
+            s3 = time_steps(hd, t, cfg, passes, max(10, args.steps // 4), 5, False)
+            extra[name + "_separate_passes"] = {"ms_per_step": round(s3 * 1e3, 5),
+                                                "effective_TFLOPs": round(flops / s3 / 1e12, 2)}
         for other in ("C1", "C3", "C4"):
             if other == name:
                 continue
@@ -289,11 +355,17 @@ def main():
             opasses = synth.CONV_CONFIGS[other]["passes"]
             t, _ = device_tensors(ocfg, synth.CONV_SEEDS[other])
             n = 20 if other == "C4" else 50
-            s = time_steps(hd, t, ocfg, opasses, n, 5)
+            s3 = time_steps(hd, t, ocfg, opasses, n, 5)
             sm = profile_stages(hd, t, ocfg, opasses, 5)
-            extra[other] = {"ms_per_step": round(s * 1e3, 4),
-                            "effective_TFLOPs": round(direct_flops(ocfg) * len(opasses) / s / 1e12, 2),
-                            "stage_ms": {p: [round(v, 4) for v in sm[p]] for p in opasses}}
+            ent = {"ms_per_step_separate_passes": round(s3 * 1e3, 4),
+                   "effective_TFLOPs_separate_passes": round(direct_flops(ocfg) * len(opasses) / s3 / 1e12, 2),
+                   "kernel_ms[fft,contraction,ifft]": {p: [round(v, 4) for v in sm[p]] for p in opasses}}
+            if len(opasses) == 3:
+                add_saved(hd, t, ocfg)
+                s2 = time_steps(hd, t, ocfg, opasses, n, 5, True)
+                ent["ms_per_step"] = round(s2 * 1e3, 4)
+                ent["effective_TFLOPs"] = round(direct_flops(ocfg) * 3 / s2 / 1e12, 2)
+            extra[other] = ent
         del t
         torch.cuda.empty_cache()
         extra["fft_sweep_256MiB"] = fft_sweep(hd)

@@ -105,14 +105,42 @@ int fft_r2c_2d(fftconv_handle hd, const float *in, float *out, long B, int h_in,
 int fft_c2r_2d(fftconv_handle hd, const float *in, float *out, long B, int n, int h_out, int w_out);
 
 /*
- * Per-stage timing of the last convolution pass, for roofline reporting.
- * With profiling enabled each of a pass's four kernels (FFT of operand A, FFT of operand
- * B, per-bin contraction, inverse FFT) is launched with a start/stop HIP event pair attached
- * to that dispatch on the handle's stream; fftconv_last_stage_ms() waits for the last pass
- * and returns the four kernel execution times in milliseconds.  Off by default.
+ * Reuse of transforms between the passes of one layer (the first of the two opportunities
+ * Section 6 of the paper lists and forgoes for lack of memory: "reuse 2 FFT results in each
+ * hidden layer").  fft_conv_fprop_save computes the same y as fft_conv_fprop and leaves the
+ * transforms of x and wt in the caller's `saved` buffer (device memory, at least
+ * fftconv_saved_bytes(), contents private).  fft_conv_backward then computes gx (as
+ * fft_conv_bprop) and gw (as fft_conv_accgrad, with scale / accumulate) from gy and that
+ * buffer, transforming gy once: three forward transforms per layer and step instead of six.
+ * Either of gx, gw may be NULL to skip that half.  `saved` must come from
+ * fft_conv_fprop_save with the same shape arguments and x, wt unchanged since.
+ * `ws` as for the passes; sizes: fftconv_workspace_bytes(FFTCONV_FPROP, ...) is enough for
+ * fft_conv_fprop_save, fftconv_backward_workspace_bytes() for fft_conv_backward.
+ */
+size_t fftconv_saved_bytes(int S, int f, int fo, int h, int w, int kh, int kw);
+size_t fftconv_backward_workspace_bytes(int S, int f, int fo, int h, int w, int kh, int kw);
+int fft_conv_fprop_save(fftconv_handle hd, const float *x, const float *wt, float *y,
+                        int S, int f, int fo, int h, int w, int kh, int kw,
+                        void *saved, size_t saved_bytes, void *ws, size_t ws_bytes);
+int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                      int S, int f, int fo, int h, int w, int kh, int kw,
+                      float scale, int accumulate, const void *saved, size_t saved_bytes,
+                      void *ws, size_t ws_bytes);
+
+/*
+ * Per-kernel timing of the last convolution call, for roofline reporting.
+ * With profiling enabled every kernel of a convolution call is launched with a start/stop
+ * HIP event pair attached to that dispatch on the handle's stream.
+ * fftconv_last_kernel_ms() waits for the last call and writes the execution times in
+ * milliseconds, in launch order, to ms_out[0 .. *count):
+ *   fft_conv_fprop / bprop / accgrad / fprop_save: forward FFT of both operands (one launch),
+ *     per-bin contraction, inverse FFT                                             (3 kernels)
+ *   fft_conv_backward: forward FFT of gy, then contraction + inverse FFT for gx and again
+ *     for gw (those requested)                                                 (3 or 5 kernels)
+ * Off by default.
  */
 int fftconv_set_profiling(fftconv_handle h, int enabled);
-int fftconv_last_stage_ms(fftconv_handle h, float ms_out[4]);
+int fftconv_last_kernel_ms(fftconv_handle h, float *ms_out, int capacity, int *count);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,8 @@ SYMBOLS = [
     "fftconv_create", "fftconv_destroy", "fftconv_set_stream", "fftconv_status_string",
     "fftconv_workspace_bytes", "fft_conv_fprop", "fft_conv_bprop", "fft_conv_accgrad",
     "fft_r2c_1d", "fft_c2r_1d", "fft_r2c_2d", "fft_c2r_2d",
-    "fftconv_set_profiling", "fftconv_last_stage_ms",
+    "fftconv_set_profiling", "fftconv_last_kernel_ms",
+    "fftconv_saved_bytes", "fftconv_backward_workspace_bytes", "fft_conv_fprop_save", "fft_conv_backward",
 ]
 
 
@@ -53,7 +54,13 @@ def load_library():
     lib.fft_r2c_2d.argtypes = [vp, vp, vp, l, i, i, i]
     lib.fft_c2r_2d.argtypes = [vp, vp, vp, l, i, i, i]
     lib.fftconv_set_profiling.argtypes = [vp, i]
-    lib.fftconv_last_stage_ms.argtypes = [vp, ctypes.POINTER(f * 4)]
+    lib.fftconv_last_kernel_ms.argtypes = [vp, ctypes.POINTER(f), i, ctypes.POINTER(i)]
+    lib.fftconv_saved_bytes.argtypes = [i] * 7
+    lib.fftconv_saved_bytes.restype = sz
+    lib.fftconv_backward_workspace_bytes.argtypes = [i] * 7
+    lib.fftconv_backward_workspace_bytes.restype = sz
+    lib.fft_conv_fprop_save.argtypes = [vp, vp, vp, vp] + [i] * 7 + [vp, sz, vp, sz]
+    lib.fft_conv_backward.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i, vp, sz, vp, sz]
     _lib = lib
     return lib
 
@@ -108,10 +115,17 @@ class Handle:
     def set_profiling(self, on: bool):
         _check(self._lib.fftconv_set_profiling(self._h, 1 if on else 0), "fftconv_set_profiling")
 
-    def last_stage_ms(self):
-        buf = (ctypes.c_float * 4)()
-        _check(self._lib.fftconv_last_stage_ms(self._h, ctypes.byref(buf)), "fftconv_last_stage_ms")
-        return [float(v) for v in buf]
+    def last_kernel_ms(self):
+        buf = (ctypes.c_float * 8)()
+        n = ctypes.c_int(0)
+        _check(self._lib.fftconv_last_kernel_ms(self._h, buf, 8, ctypes.byref(n)), "fftconv_last_kernel_ms")
+        return [float(buf[k]) for k in range(n.value)]
+
+    def saved_bytes(self, S, f, fo, h, w, kh, kw) -> int:
+        return int(self._lib.fftconv_saved_bytes(S, f, fo, h, w, kh, kw))
+
+    def backward_workspace_bytes(self, S, f, fo, h, w, kh, kw) -> int:
+        return int(self._lib.fftconv_backward_workspace_bytes(S, f, fo, h, w, kh, kw))
 
     # ---- convolution passes -------------------------------------------------------------
     def fft_conv_fprop(self, x, wt, y=None, ws=None):
@@ -126,6 +140,43 @@ class Handle:
         _check(self._lib.fft_conv_fprop(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
                                         S, f, fo, h, w, kh, kw, *self._ws(ws)), "fft_conv_fprop")
         return y
+
+    def fft_conv_fprop_save(self, x, wt, saved, y=None, ws=None):
+        """fprop that also leaves the transforms of x and wt in `saved` (a float32 device tensor
+        of at least saved_bytes() bytes) for fft_conv_backward."""
+        import torch
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f:
+            raise FFTConvError("x and wt disagree on the number of input planes")
+        if y is None:
+            y = torch.empty((S, fo, h - kh + 1, w - kw + 1), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop_save(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
+                                             S, f, fo, h, w, kh, kw, *self._ws(saved), *self._ws(ws)),
+               "fft_conv_fprop_save")
+        return y
+
+    def fft_conv_backward(self, gy, saved, f, h, w, kh, kw, gx=None, gw=None, want_gx=True, want_gw=True,
+                          scale=1.0, accumulate=False, ws=None):
+        """bprop and accGrad of one layer from gy and the transforms saved by fft_conv_fprop_save."""
+        import torch
+        S, fo, oh, ow = gy.shape
+        if oh != h - kh + 1 or ow != w - kw + 1:
+            raise FFTConvError("gy and (h, w, kh, kw) disagree")
+        if want_gx and gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        if want_gw and gw is None:
+            if accumulate:
+                raise FFTConvError("accumulate needs an existing gw")
+            gw = torch.empty((fo, f, kh, kw), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_backward(self._h, _dev_f32(gy, "gy"),
+                                           _dev_f32(gx, "gx") if want_gx else None,
+                                           _dev_f32(gw, "gw") if want_gw else None,
+                                           S, f, fo, h, w, kh, kw, float(scale), 1 if accumulate else 0,
+                                           *self._ws(saved), *self._ws(ws)), "fft_conv_backward")
+        return gx, gw
 
     def fft_conv_bprop(self, gy, wt, h, w, gx=None, ws=None):
         import torch

@@ -14,14 +14,16 @@
 
 using namespace fc;
 
+constexpr int kMaxKernels = 8;
+
 struct fftconv_ctx {
     int device;
     hipStream_t stream;
     void *ws;
     size_t ws_bytes;
     int profiling;
-    hipEvent_t ev[8];   // start/stop pair per stage
-    int ev_valid;
+    hipEvent_t ev[2 * 8];   // start/stop pair per kernel of the last call
+    int nk;                 // kernels of the last call that carry events
     char last_hip_error[256];
 };
 
@@ -97,6 +99,61 @@ static int hip_fail(fftconv_ctx *c, hipError_t e) {
     return FFTCONV_HIP_ERROR;
 }
 
+static int get_workspace(fftconv_ctx *c, size_t need, void **ws, size_t ws_bytes) {
+    if (*ws) return ws_bytes < need ? FFTCONV_WORKSPACE_TOO_SMALL : FFTCONV_OK;
+    hipError_t e;
+    if (c->ws_bytes < need) {
+        if (c->ws) {
+            if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e);
+            (void)hipFree(c->ws);
+            c->ws = nullptr; c->ws_bytes = 0;
+        }
+        if ((e = hipMalloc(&c->ws, need)) != hipSuccess) return hip_fail(c, e);
+        c->ws_bytes = need;
+    }
+    *ws = c->ws;
+    return FFTCONV_OK;
+}
+
+// Launch context for the next kernel of the current call: with profiling on, each kernel gets
+// its own start/stop event pair (kMaxKernels per call).
+static LaunchCtx next_ctx(fftconv_ctx *c) {
+    if (!c->profiling || c->nk >= kMaxKernels) return LaunchCtx{c->stream, nullptr, nullptr};
+    const int k = c->nk++;
+    return LaunchCtx{c->stream, c->ev[2 * k], c->ev[2 * k + 1]};
+}
+
+static float *at(void *base, size_t off) { return reinterpret_cast<float *>(static_cast<char *>(base) + off); }
+
+// Forward transforms of both operands of a pass.  For the bases up to 32 they share one launch
+// (two short kernels would queue behind each other's ramp-up and tail; measured 14 us of 204
+// per step on the 32-basis layer).  For basis 64 and up the transform is ALU-bound and a shared
+// launch would give every block the larger operand's LDS footprint, costing occupancy
+// (measured slower), so the operands are launched one after the other.  Profiling then reports
+// the pair as one entry only in the shared case, so that case also pairs the events.
+static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a, float *AF,
+                               const float *b, float *BF) {
+    if (p.N <= 32) {
+        FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA}, {b, BF, p.planesB, p.hB, p.wB}};
+        return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c));
+    }
+    // one event pair around both launches: start from the first, stop from the second
+    LaunchCtx lc = next_ctx(c);
+    hipError_t e = launch_fft2d_r2c(a, AF, p.planesA, p.hA, p.wA, p.N, true, LaunchCtx{lc.stream, lc.start, nullptr});
+    if (e != hipSuccess) return e;
+    return launch_fft2d_r2c(b, BF, p.planesB, p.hB, p.wB, p.N, true, LaunchCtx{lc.stream, nullptr, lc.stop});
+}
+
+// Contraction + inverse transform of one pass, operands already in the frequency domain.
+static hipError_t contract_and_invert(fftconv_ctx *c, const PassPlan &p, const float *AF, const float *BF,
+                                      float *CF, float *out, float scale, int accumulate) {
+    hipError_t e;
+    GemmOperand ga{AF, p.lay, p.a_rs, p.a_cs, p.conjA}, gb{BF, p.lay, p.b_rs, p.b_cs, p.conjB};
+    if ((e = launch_cgemm_bins(ga, gb, CF, p.lay, p.c_rs, p.c_cs, p.M, p.Nn, p.K, p.bins, next_ctx(c))) != hipSuccess) return e;
+    const float s = scale / ((float)p.N * (float)p.N);
+    return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c));
+}
+
 static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB, float *out,
                     int S, int f, int fo, int h, int w, int kh, int kw, float scale, int accumulate,
                     void *ws, size_t ws_bytes) {
@@ -104,39 +161,26 @@ static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB
     PassPlan p;
     int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p);
     if (rc != FFTCONV_OK) return rc;
+    if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
+    float *AF = at(ws, p.offA), *BF = at(ws, p.offB), *CF = at(ws, p.offC);
+    c->nk = 0;
     hipError_t e;
-    if (ws) {
-        if (ws_bytes < p.total) return FFTCONV_WORKSPACE_TOO_SMALL;
-    } else {
-        if (c->ws_bytes < p.total) {
-            if (c->ws) {
-                if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e);
-                (void)hipFree(c->ws);
-                c->ws = nullptr; c->ws_bytes = 0;
-            }
-            if ((e = hipMalloc(&c->ws, p.total)) != hipSuccess) return hip_fail(c, e);
-            c->ws_bytes = p.total;
-        }
-        ws = c->ws;
-    }
-    float *AF = reinterpret_cast<float *>(static_cast<char *>(ws) + p.offA);
-    float *BF = reinterpret_cast<float *>(static_cast<char *>(ws) + p.offB);
-    float *CF = reinterpret_cast<float *>(static_cast<char *>(ws) + p.offC);
-    const bool prof = c->profiling != 0;
-    c->ev_valid = 0;
-    auto ctx = [&](int stage) {
-        return prof ? LaunchCtx{c->stream, c->ev[2 * stage], c->ev[2 * stage + 1]}
-                    : LaunchCtx{c->stream, nullptr, nullptr};
-    };
-
-    if ((e = launch_fft2d_r2c(opA, AF, p.planesA, p.hA, p.wA, p.N, true, p.conjA, ctx(0))) != hipSuccess) return hip_fail(c, e);
-    if ((e = launch_fft2d_r2c(opB, BF, p.planesB, p.hB, p.wB, p.N, true, p.conjB, ctx(1))) != hipSuccess) return hip_fail(c, e);
-    GemmOperand ga{AF, p.lay, p.a_rs, p.a_cs}, gb{BF, p.lay, p.b_rs, p.b_cs};
-    if ((e = launch_cgemm_bins(ga, gb, CF, p.lay, p.c_rs, p.c_cs, p.M, p.Nn, p.K, p.bins, ctx(2))) != hipSuccess) return hip_fail(c, e);
-    const float s = scale / ((float)p.N * (float)p.N);
-    if ((e = launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, ctx(3))) != hipSuccess) return hip_fail(c, e);
-    if (prof) c->ev_valid = 1;
+    if ((e = forward_pair(c, p, opA, AF, opB, BF)) != hipSuccess) return hip_fail(c, e);
+    if ((e = contract_and_invert(c, p, AF, BF, CF, out, scale, accumulate)) != hipSuccess) return hip_fail(c, e);
     return FFTCONV_OK;
+}
+
+// Layout of the buffer that carries the input and weight transforms from fprop to the
+// backward call: [XF | WF], each in the plane-tiled layout of the layer's basis.
+struct SavedPlan {
+    size_t offX, offW, total;
+};
+static SavedPlan saved_plan(const PassPlan &fp) {
+    SavedPlan s;
+    s.offX = 0;
+    s.offW = align_up(fp.lay.floats(fp.planesA) * sizeof(float), 256);
+    s.total = align_up(s.offW + fp.lay.floats(fp.planesB) * sizeof(float), 256);
+    return s;
 }
 
 extern "C" {
@@ -150,8 +194,8 @@ int fftconv_create(fftconv_handle *out, int device) {
     fftconv_ctx *c = new (std::nothrow) fftconv_ctx();
     if (!c) return FFTCONV_HIP_ERROR;
     c->device = device; c->stream = nullptr; c->ws = nullptr; c->ws_bytes = 0;
-    c->profiling = 0; c->ev_valid = 0; c->last_hip_error[0] = 0;
-    for (int i = 0; i < 8; ++i)
+    c->profiling = 0; c->nk = 0; c->last_hip_error[0] = 0;
+    for (int i = 0; i < 2 * kMaxKernels; ++i)
         if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return FFTCONV_HIP_ERROR; }
     *out = c;
     return FFTCONV_OK;
@@ -160,7 +204,7 @@ int fftconv_create(fftconv_handle *out, int device) {
 int fftconv_destroy(fftconv_handle h) {
     if (!h) return FFTCONV_INVALID_ARG;
     if (h->ws) (void)hipFree(h->ws);
-    for (int i = 0; i < 8; ++i) (void)hipEventDestroy(h->ev[i]);
+    for (int i = 0; i < 2 * kMaxKernels; ++i) (void)hipEventDestroy(h->ev[i]);
     delete h;
     return FFTCONV_OK;
 }
@@ -226,7 +270,7 @@ int fft_r2c_2d(fftconv_handle hd, const float *in, float *out, long B, int h_in,
     if (!hd || B < 0 || h_in <= 0 || w_in <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;
     if (!fft_size_ok(n)) return FFTCONV_UNSUPPORTED;
     if (h_in > n || w_in > n) return FFTCONV_INVALID_ARG;
-    hipError_t e = launch_fft2d_r2c(in, out, B, h_in, w_in, n, false, false, LaunchCtx{hd->stream, nullptr, nullptr});
+    hipError_t e = launch_fft2d_r2c(in, out, B, h_in, w_in, n, false, LaunchCtx{hd->stream, nullptr, nullptr});
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
@@ -242,17 +286,80 @@ int fft_c2r_2d(fftconv_handle hd, const float *in, float *out, long B, int n, in
 int fftconv_set_profiling(fftconv_handle h, int enabled) {
     if (!h) return FFTCONV_INVALID_ARG;
     h->profiling = enabled ? 1 : 0;
-    h->ev_valid = 0;
+    h->nk = 0;
     return FFTCONV_OK;
 }
 
-int fftconv_last_stage_ms(fftconv_handle h, float ms_out[4]) {
-    if (!h || !ms_out) return FFTCONV_INVALID_ARG;
-    if (!h->ev_valid) return FFTCONV_INVALID_ARG;
-    hipError_t e = hipEventSynchronize(h->ev[7]);
+int fftconv_last_kernel_ms(fftconv_handle h, float *ms_out, int capacity, int *count) {
+    if (!h || !ms_out || !count || capacity < 0) return FFTCONV_INVALID_ARG;
+    *count = 0;
+    if (!h->profiling || h->nk == 0) return FFTCONV_INVALID_ARG;
+    hipError_t e = hipEventSynchronize(h->ev[2 * (h->nk - 1) + 1]);
     if (e != hipSuccess) return hip_fail(h, e);
-    for (int i = 0; i < 4; ++i)
+    const int n = h->nk < capacity ? h->nk : capacity;
+    for (int i = 0; i < n; ++i)
         if ((e = hipEventElapsedTime(&ms_out[i], h->ev[2 * i], h->ev[2 * i + 1])) != hipSuccess) return hip_fail(h, e);
+    *count = n;
+    return FFTCONV_OK;
+}
+
+size_t fftconv_saved_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
+    PassPlan p;
+    if (make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p) != FFTCONV_OK) return 0;
+    return saved_plan(p).total;
+}
+
+size_t fftconv_backward_workspace_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
+    PassPlan pb, pa;
+    if (make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb) != FFTCONV_OK) return 0;
+    if (make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa) != FFTCONV_OK) return 0;
+    const size_t gyf = align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256);
+    const size_t cb = pb.lay.floats(pb.planesC) * sizeof(float), ca = pa.lay.floats(pa.planesC) * sizeof(float);
+    return gyf + align_up(cb > ca ? cb : ca, 256);
+}
+
+int fft_conv_fprop_save(fftconv_handle hd, const float *x, const float *wt, float *y,
+                        int S, int f, int fo, int h, int w, int kh, int kw,
+                        void *saved, size_t saved_bytes, void *ws, size_t ws_bytes) {
+    if (!hd || !x || !wt || !y || !saved) return FFTCONV_INVALID_ARG;
+    PassPlan p;
+    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
+    if (rc != FFTCONV_OK) return rc;
+    const SavedPlan sp = saved_plan(p);
+    if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
+    const size_t need = align_up(p.lay.floats(p.planesC) * sizeof(float), 256);
+    if ((rc = get_workspace(hd, need, &ws, ws_bytes)) != FFTCONV_OK) return rc;
+    float *XF = at(saved, sp.offX), *WF = at(saved, sp.offW), *YF = at(ws, 0);
+    hd->nk = 0;
+    hipError_t e;
+    if ((e = forward_pair(hd, p, x, XF, wt, WF)) != hipSuccess) return hip_fail(hd, e);
+    if ((e = contract_and_invert(hd, p, XF, WF, YF, y, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
+    return FFTCONV_OK;
+}
+
+int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                      int S, int f, int fo, int h, int w, int kh, int kw,
+                      float scale, int accumulate, const void *saved, size_t saved_bytes,
+                      void *ws, size_t ws_bytes) {
+    if (!hd || !gy || !saved || (!gx && !gw)) return FFTCONV_INVALID_ARG;
+    PassPlan pf, pb, pa;
+    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &pf);
+    if (rc != FFTCONV_OK) return rc;
+    (void)make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb);
+    (void)make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa);
+    const SavedPlan sp = saved_plan(pf);
+    if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
+    const size_t need = fftconv_backward_workspace_bytes(S, f, fo, h, w, kh, kw);
+    if ((rc = get_workspace(hd, need, &ws, ws_bytes)) != FFTCONV_OK) return rc;
+    const float *XF = at(const_cast<void *>(saved), sp.offX), *WF = at(const_cast<void *>(saved), sp.offW);
+    float *GYF = at(ws, 0);
+    float *CF = at(ws, align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256));
+    hd->nk = 0;
+    hipError_t e;
+    if ((e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+    // bprop: GX = GY . W ; accGrad: GW = conj(GY) . X  (operand A of both plans is GYF)
+    if (gx && (e = contract_and_invert(hd, pb, GYF, WF, CF, gx, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
+    if (gw && (e = contract_and_invert(hd, pa, GYF, XF, CF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
     return FFTCONV_OK;
 }
 

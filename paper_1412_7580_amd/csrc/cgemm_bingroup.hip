@@ -114,13 +114,13 @@ __global__ void __launch_bounds__(256, (FM * FN == 1 && AKF == BKF ? 4 : 1)) cge
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 a_re[i] = a0[(ks + lk) * SA + i * 32];
-                a_im[i] = a0[RA + (ks + lk) * SA + i * 32];
+                a_im[i] = flip(a0[RA + (ks + lk) * SA + i * 32], prm.a_sign);
                 a_sm[i] = a_re[i] + a_im[i];
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 b_re[j] = b0p[(ks + lk) * SB + j * 32];
-                b_im[j] = b0p[RB + (ks + lk) * SB + j * 32];
+                b_im[j] = flip(b0p[RB + (ks + lk) * SB + j * 32], prm.b_sign);
                 b_sm[j] = b_re[j] + b_im[j];
             }
 #pragma unroll

@@ -180,13 +180,13 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 a_re[i] = a0[(ks + lk) * SA + i * 32];
-                a_im[i] = a0[TK * SA + (ks + lk) * SA + i * 32];
+                a_im[i] = flip(a0[TK * SA + (ks + lk) * SA + i * 32], prm.a_sign);
                 a_sm[i] = a_re[i] + a_im[i];
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 b_re[j] = b0[(ks + lk) * SB + j * 32];
-                b_im[j] = b0[TK * SB + (ks + lk) * SB + j * 32];
+                b_im[j] = flip(b0[TK * SB + (ks + lk) * SB + j * 32], prm.b_sign);
                 b_sm[j] = b_re[j] + b_im[j];
             }
 #pragma unroll
@@ -290,6 +290,8 @@ hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout 
     prm.a_rs = A.rs; prm.a_cs = A.cs; prm.b_rs = B.rs; prm.b_cs = B.cs;
     prm.c_rs = C_rs; prm.c_cs = C_cs;
     prm.M = M; prm.N = N; prm.K = K; prm.bins = bins;
+    prm.a_sign = A.conj ? 0x80000000u : 0u;
+    prm.b_sign = B.conj ? 0x80000000u : 0u;
     const bool akf = (A.cs == 1), bkf = (B.rs == 1);
     // 16-byte gathers need: runs of >= 4 planes, the contiguous index a multiple of 4 at every
     // vector start (tile origins are), its extent a multiple of 4, and the other stride too.

@@ -100,7 +100,6 @@ struct Fwd2dParams {
     int MPS;          // LDS plane stride of the row-transformed data (float2, odd)
     MagicDiv div_hw, div_w;
     FreqLayout lay;
-    float im_sign;    // -1 to store the conjugate
     int linear;       // staged planes need no padding: LDS image == global image
     int vec_ok;       // input base and every block start are 16-byte aligned
     int out_vec_ok;   // output base and every block start are 16-byte aligned
@@ -113,13 +112,12 @@ template <int N, int T, bool CONV>
 struct BinStore {
     float *base;
     unsigned lane_off;  // CONV: plane within the tile; natural: plane * N * (N/2+1) (in float2)
-    float im_sign;
     __device__ __forceinline__ void operator()(int k1, int k2, float re, float im) const {
         constexpr int NB = N / 2 + 1;
         if constexpr (CONV) {
             const unsigned idx = lane_off + (unsigned)((k1 * NB + k2) * 2) * T;
             base[idx] = re;
-            base[idx + T] = im_sign * im;
+            base[idx + T] = im;
         } else {
             reinterpret_cast<float2 *>(base)[lane_off + (unsigned)(k1 * NB + k2)] = make_float2(re, im);
         }
@@ -127,7 +125,7 @@ struct BinStore {
 };
 
 template <int L, int G, int T, bool CONV, bool OSTAGE>
-__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dParams prm) {
+__device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned block) {
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
     constexpr int NA = SplitRegs<L, G>::A;   // registers of split spectrum per lane
     constexpr int NBR = SplitRegs<L, G>::B;
@@ -136,7 +134,7 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
     float2 *mid = reinterpret_cast<float2 *>(smem);
 
     const int tid = threadIdx.x;
-    const long p0 = (long)blockIdx.x * T;
+    const long p0 = (long)block * T;
     const int h_in = prm.h_in, w_in = prm.w_in, hw = h_in * w_in;
     const long left = prm.planes - p0;
     const int np = left < T ? (int)left : T;
@@ -242,7 +240,6 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
     // block's output (which is one contiguous range in both layouts) that is then written
     // out with 16-byte coalesced stores.
     BinStore<N, T, CONV> st;
-    st.im_sign = prm.im_sign;
     st.lane_off = CONV ? (unsigned)cp : (unsigned)cp * N * NB;
     if constexpr (OSTAGE) {
         __syncthreads();   // every lane has read `mid`; the image overlays it
@@ -295,6 +292,26 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dPara
                                prm.out_vec_ok != 0, false);
         }
     }
+}
+
+template <int L, int G, int T, bool CONV, bool OSTAGE>
+__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_kernel(Fwd2dParams prm) {
+    fft2d_r2c_body<L, G, T, CONV, OSTAGE>(prm, blockIdx.x);
+}
+
+// Up to three operand tensors transformed by one launch (plane-tiled layout only): the blocks
+// of operand o are [first[o], first[o+1]).  Short transforms of several operands fill the chip
+// together instead of queueing behind each other's ramp-up and tail.
+struct FwdMultiParams {
+    Fwd2dParams op[3];
+    unsigned first[4];
+};
+
+template <int L, int G, int T>
+__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_r2c_multi_kernel(FwdMultiParams m) {
+    const unsigned b = blockIdx.x;
+    const int o = (b >= m.first[1]) + (b >= m.first[2]);
+    fft2d_r2c_body<L, G, T, true, false>(m.op[o], b - m.first[o]);
 }
 
 // ------------------------------------------------------------------ 2-D inverse + crop
@@ -613,9 +630,8 @@ int fft2d_tile_log2(int N) {
 }
 
 template <int L, int G, int T>
-static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, int w_in,
-                            bool conv, bool conj, LaunchCtx st) {
-    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in, int w_in, size_t *lds) {
+    constexpr int N = L * G, NH = N / 2;
     Fwd2dParams prm;
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_in = h_in; prm.w_in = w_in;
     prm.RS = w_in | 1;
@@ -625,12 +641,20 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
     prm.div_w = make_magic((unsigned)w_in);
     prm.lay.tsh = fft2d_tile_log2(N);
     prm.lay.bins = N * (NH + 1);
-    prm.im_sign = conj ? -1.f : 1.f;
     prm.linear = (prm.RS == w_in && prm.IPS == h_in * w_in) ? 1 : 0;
     prm.vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * h_in * w_in) % 4 == 0) ? 1 : 0;
     prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
     const size_t a = ((size_t)T * prm.IPS + N) * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
-    size_t lds = a > b ? a : b;
+    *lds = a > b ? a : b;
+    return prm;
+}
+
+template <int L, int G, int T>
+static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, int w_in,
+                            bool conv, LaunchCtx st) {
+    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+    size_t lds;
+    const Fwd2dParams prm = make_fwd2d<L, G, T>(in, out, planes, h_in, w_in, &lds);
     // Measured: staging the output through LDS pays for the natural layout (short runs per
     // lane otherwise) and costs for the plane-tiled layout, whose direct stores already fill
     // whole runs of T planes.
@@ -650,15 +674,55 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
     return go(fft2d_r2c_kernel<L, G, T, false, true>);
 }
 
+template <int L, int G, int T>
+static hipError_t run_fwd2d_multi(const FwdOperand *ops, int nops, LaunchCtx st) {
+    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+    FwdMultiParams m;
+    size_t lds = 0;
+    unsigned blocks = 0;
+    for (int o = 0; o < 3; ++o) {
+        m.first[o] = blocks;
+        if (o < nops) {
+            size_t l;
+            m.op[o] = make_fwd2d<L, G, T>(ops[o].in, ops[o].out, ops[o].planes, ops[o].h_in, ops[o].w_in, &l);
+            if (l > lds) lds = l;
+            blocks += (unsigned)((ops[o].planes + T - 1) / T);
+        } else {
+            m.op[o] = m.op[0];
+        }
+    }
+    m.first[3] = blocks;
+    for (int o = nops; o < 3; ++o) m.first[o] = blocks;   // unused operands own no blocks
+    auto k = fft2d_r2c_multi_kernel<L, G, T>;
+    hipError_t e;
+    if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
+    launch_kernel(k, dim3(blocks), dim3(BT), lds, st, m);
+    return hipGetLastError();
+}
+
+hipError_t launch_fft2d_r2c_multi(const FwdOperand *ops, int nops, int N, LaunchCtx st) {
+    if (nops < 1 || nops > 3) return hipErrorInvalidValue;
+    for (int o = 0; o < nops; ++o)
+        if (ops[o].planes <= 0) return hipErrorInvalidValue;
+    switch (N) {
+        case 8: return run_fwd2d_multi<8, 1, 64>(ops, nops, st);
+        case 16: return run_fwd2d_multi<16, 1, 32>(ops, nops, st);
+        case 32: return run_fwd2d_multi<32, 1, 16>(ops, nops, st);
+        case 64: return run_fwd2d_multi<32, 2, 4>(ops, nops, st);
+        case 128: return run_fwd2d_multi<32, 4, 1>(ops, nops, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
-                            bool conv, bool conj, LaunchCtx st) {
+                            bool conv, LaunchCtx st) {
     if (planes <= 0) return hipSuccess;
     switch (N) {
-        case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, conj, st);
-        case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, conj, st);
-        case 32: return run_fwd2d<32, 1, 16>(in, out, planes, h_in, w_in, conv, conj, st);
-        case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, conj, st);
-        case 128: return run_fwd2d<32, 4, 1>(in, out, planes, h_in, w_in, conv, conj, st);
+        case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, st);
+        case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st);
+        case 32: return run_fwd2d<32, 1, 16>(in, out, planes, h_in, w_in, conv, st);
+        case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st);
+        case 128: return run_fwd2d<32, 4, 1>(in, out, planes, h_in, w_in, conv, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -13,7 +13,12 @@ struct GemmParams {
     long a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;
     int M, N, K, bins;
     int tiles_m, tiles_n;
+    unsigned a_sign, b_sign;   // 0x80000000 to conjugate the operand (flips Im on the way to the MFMA)
 };
+
+__device__ __forceinline__ float flip(float v, unsigned sign) {
+    return __builtin_bit_cast(float, __builtin_bit_cast(unsigned, v) ^ sign);
+}
 
 constexpr int kXcds = 8;   // workgroup i is placed on XCD i % kXcds
 

@@ -16,7 +16,7 @@ struct LaunchCtx {
 
 template <class K, class P>
 inline void launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const LaunchCtx &lc, const P &prm) {
-    if (lc.start) hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, lc.stream, lc.start, lc.stop, 0, prm);
+    if (lc.start || lc.stop) hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, lc.stream, lc.start, lc.stop, 0, prm);
     else hipLaunchKernelGGL(kernel, grid, block, lds, lc.stream, prm);
 }
 
@@ -45,11 +45,19 @@ struct FreqLayout {
 int fft2d_tile_log2(int N);
 
 // 2-D R2C of `planes` planes [h_in x w_in] zero-padded to N x N.
-//   conv layout: out = FreqLayout buffer (tile = fft2d_tile_log2(N)); conj_out negates the
-//                imaginary parts on store (used where a pass needs the conjugate operand).
+//   conv layout: out = FreqLayout buffer (tile = fft2d_tile_log2(N)).
 //   natural layout: out = [planes][N][N/2+1][2].
 hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
-                            bool conv_layout, bool conj_out, LaunchCtx st);
+                            bool conv_layout, LaunchCtx st);
+
+// The same transform of up to three operand tensors (plane-tiled layout) in ONE launch.
+struct FwdOperand {
+    const float *in;
+    float *out;
+    long planes;
+    int h_in, w_in;
+};
+hipError_t launch_fft2d_r2c_multi(const FwdOperand *ops, int nops, int N, LaunchCtx st);
 
 // 2-D C2R + crop.  out[planes][h_out][w_out] = scale * real inverse (the caller folds 1/N^2
 // into `scale`), added to the previous contents when accumulate is set.
@@ -59,12 +67,14 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
 hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);
 
-// Per-bin complex contraction  C[b](m,n) = sum_k A[b](m,k) * B[b](k,n)  over all bins.
-// Operand element (row r, col c) of X lives at plane  r * X_rs + c * X_cs  of its layout.
+// Per-bin complex contraction  C[b](m,n) = sum_k A'[b](m,k) * B'[b](k,n)  over all bins, where
+// X' is X or its complex conjugate.  Operand element (row r, col c) of X lives at plane
+// r * X_rs + c * X_cs  of its layout.
 struct GemmOperand {
     const float *ptr;
     FreqLayout lay;
     long rs, cs;       // plane strides of the (row, col) indices
+    bool conj;         // use the complex conjugate of the stored values
 };
 hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
                              long C_cs, int M, int N, int K, int bins, LaunchCtx st);

@@ -17,7 +17,7 @@ def test_header_symbols_exported():
     import paper_1412_7580_amd as pkg
     lib = pkg.load_library()
     decl = _declared()
-    assert len(decl) >= 14
+    assert len(decl) >= 18
     for name in decl:
         assert hasattr(lib, name), f"{name} declared in fftconv.h but not exported"
     assert sorted(pkg.SYMBOLS) == decl
@@ -32,6 +32,7 @@ def test_host_only_calls():
     # fprop of the smallest configuration: three frequency tensors of 256 planes, 144 bins
     need = lib.fftconv_workspace_bytes(0, 16, 16, 16, 13, 13, 3, 3)
     assert need == 3 * 256 * 144 * 2 * 4
+    assert lib.fftconv_saved_bytes(16, 16, 16, 13, 13, 3, 3) == 2 * 256 * 144 * 2 * 4
     # invalid (kernel larger than input) and unsupported (basis 256) shapes
     assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 4, 4, 5, 5) == 0
     assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 200, 200, 3, 3) == 0

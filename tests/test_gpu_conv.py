@@ -146,3 +146,50 @@ def test_repeat_calls_are_deterministic(hd):
     a = hd.fft_conv_fprop(dx, dw).clone()
     b = hd.fft_conv_fprop(dx, dw)
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("cfg", [SMALL[3], SMALL[6], SMALL[9], dict(S=9, f=20, fo=12, h=16, w=16, kh=3, kw=3)],
+                         ids=lambda c: "S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c))
+def test_fprop_save_and_backward(hd, cfg):
+    """Transform reuse: fprop_save + backward must give what the three independent passes give
+    (each checked against the oracle), including the gx-only / gw-only forms."""
+    import torch
+    x, w, gy = synth.conv_inputs(seed=104, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
+    y = hd.fft_conv_fprop_save(dx, dw, saved)
+    assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
+    args = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    gx, gw = hd.fft_conv_backward(dgy, saved, *args)
+    ref_gx, ref_gw = oracle.conv_bprop(gy, w, cfg["h"], cfg["w"]), oracle.conv_accgrad(x, gy)
+    assert _relerr(_np(gx), ref_gx) <= TOL
+    assert _relerr(_np(gw), ref_gw) <= TOL
+    gx2, none = hd.fft_conv_backward(dgy, saved, *args, want_gw=False)
+    assert none is None and torch.equal(gx2, gx)
+    none, gw2 = hd.fft_conv_backward(dgy, saved, *args, want_gx=False, scale=0.5)
+    assert none is None and _relerr(_np(gw2), 0.5 * ref_gw) <= TOL
+
+
+def test_reuse_at_c2(hd):
+    import torch
+    cfg = {k: v for k, v in synth.CONV_CONFIGS["C2"].items() if k not in ("passes", "N")}
+    x, w, gy = synth.conv_inputs(seed=synth.CONV_SEEDS["C2"], **cfg)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
+    y = hd.fft_conv_fprop_save(_dev(x), _dev(w), saved)
+    gx, gw = hd.fft_conv_backward(_dev(gy), saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
+    assert _relerr(_np(gx), oracle.conv_bprop(gy, w, cfg["h"], cfg["w"])) <= TOL
+    assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
+
+
+def test_saved_buffer_too_small(hd, lib):
+    import torch
+    cfg = dict(S=2, f=3, fo=4, h=9, w=9, kh=3, kw=3)
+    x, w, gy = synth.conv_inputs(seed=105, **cfg)
+    need = hd.saved_bytes(2, 3, 4, 9, 9, 3, 3)
+    assert need > 0
+    small = torch.empty(need // 8, device="cuda", dtype=torch.float32)
+    with pytest.raises(lib.FFTConvError, match="workspace too small"):
+        hd.fft_conv_fprop_save(_dev(x), _dev(w), small)
