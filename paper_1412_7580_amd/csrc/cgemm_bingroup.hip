@@ -189,10 +189,7 @@ static hipError_t run_bg(GemmParams prm, LaunchCtx st) {
     const size_t img = (size_t)TM * (TN / 4) * 36 * sizeof(float);
     if (img > lds) lds = img;
     auto k = cgemm_bingroup_kernel<FM, FN, TK, AKF, BKF>;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
     launch_kernel(k, dim3((unsigned)grid), dim3(256), lds, st, prm);
     return hipGetLastError();
 }

@@ -246,10 +246,7 @@ static hipError_t run_gemm(GemmParams prm, LaunchCtx st) {
     const long grid = (long)prm.bins * prm.tiles_m * prm.tiles_n;
     const size_t lds = (size_t)(2 * 2 * TK * (TM + 2) + 2 * 2 * TK * (TN + 2)) * sizeof(float);
     auto k = cgemm_bins_kernel<WGM, WGN, FM, FN, TK, AKF, BKF, VEC, MINB, PD>;
-    if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
     launch_kernel(k, dim3((unsigned)grid), dim3(64 * WGM * WGN), lds, st, prm);
     return hipGetLastError();
 }

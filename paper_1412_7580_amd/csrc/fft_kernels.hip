@@ -10,6 +10,8 @@
 #include "kernels.hpp"
 
 #include <cstdlib>
+#include <mutex>
+#include <unordered_map>
 
 namespace fc {
 
@@ -22,9 +24,17 @@ __device__ __forceinline__ unsigned mdiv(unsigned x, MagicDiv md) {
     return (unsigned)(((unsigned long long)x * md.m) >> 32);
 }
 
-static hipError_t allow_big_lds(const void *fn, size_t bytes) {
+hipError_t allow_big_lds(const void *fn, size_t bytes) {
     if (bytes <= 64 * 1024) return hipSuccess;
-    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    static std::mutex mu;
+    static std::unordered_map<const void *, size_t> granted;
+    std::lock_guard<std::mutex> lock(mu);
+    size_t &have = granted[fn];
+    if (have >= bytes) return hipSuccess;
+    const size_t ask = 160 * 1024;   // the whole LDS of a gfx950 compute unit
+    const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ask);
+    if (e == hipSuccess) have = ask;
+    return e;
 }
 
 
@@ -766,7 +776,9 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
     switch (N) {
         case 8: return run_inv2d<8, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
         case 16: return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
-        case 32: return run_inv2d<16, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 32:
+            if (conv && 2 * h_out > 32) return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+            return run_inv2d<16, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
         // the inverse gains from more lanes per line (fewer registers, shorter serial chains):
         // (16,4) measured 15..25 % faster than (32,2) here, (16,2) 20 % faster than (32,1) at 32
         case 64: return run_inv2d<16, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);

@@ -20,6 +20,11 @@ inline void launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, const Lau
     else hipLaunchKernelGGL(kernel, grid, block, lds, lc.stream, prm);
 }
 
+// Raise a kernel's dynamic-LDS limit when it needs more than the default 64 KB.  The runtime
+// call is made once per kernel function and size class (the largest request so far is kept),
+// not on every launch.
+hipError_t allow_big_lds(const void *fn, size_t bytes);
+
 // Private frequency-domain layout used between the FFT stages and the contraction
 // ("plane-tiled, bin-major, planar"):
 //     F[plane / T][bin][c][plane % T],   bin = k1 * (N/2+1) + k2,  c = 0 real, 1 imaginary

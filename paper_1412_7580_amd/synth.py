@@ -38,8 +38,9 @@ def uniform_pm1(seed: int, stream: int, shape, start: int = 0) -> np.ndarray:
 def normal01(seed: int, stream: int, shape, start: int = 0) -> np.ndarray:
     """fp32 N(0,1) by Box-Muller on two counter-based uniforms per sample."""
     count = int(np.prod(shape))
-    u1 = (_bits(seed, stream, 2 * start, 2 * count)[0::2] >> np.uint64(11)).astype(np.float64)
-    u2 = (_bits(seed, stream, 2 * start, 2 * count)[1::2] >> np.uint64(11)).astype(np.float64)
+    b = _bits(seed, stream, 2 * start, 2 * count) >> np.uint64(11)
+    u1 = b[0::2].astype(np.float64)
+    u2 = b[1::2].astype(np.float64)
     u1 = (u1 + 1.0) * 2.0 ** -53
     u2 = u2 * 2.0 ** -53
     z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)

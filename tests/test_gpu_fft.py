@@ -124,3 +124,29 @@ def test_argument_errors(hd, lib):
     # an empty batch is a no-op, not an error
     out = hd.fft_r2c_1d(torch.zeros((0, 5), device="cuda"), 8)
     assert out.shape == (0, 5, 2)
+
+
+@pytest.mark.parametrize("dim", [1, 2])
+@pytest.mark.parametrize("n", SIZES)
+def test_sweep_full_size(hd, dim, n):
+    """The FFT-sweep workload at its full size (256 MiB of input, the launch configuration the
+    benchmark times): R2C checked against the oracle on the first, the last and a seeded sample
+    of transforms; the C2R round trip checked against the input over the whole batch."""
+    import torch
+    B = synth.fft_sweep_batch(dim, n)
+    x = synth.fft_sweep_input(dim, n, 0, B)
+    dx = _dev(x)
+    rng = np.random.default_rng(n * 10 + dim)
+    sel = np.unique(np.concatenate([[0, B - 1], rng.integers(0, B, 510 if dim == 1 else 62)]))
+    if dim == 1:
+        X = hd.fft_r2c_1d(dx, n)
+        back = hd.fft_c2r_1d(X, n, n - 3)
+        ref = oracle.dft_r2c_1d(x[sel], n)
+    else:
+        X = hd.fft_r2c_2d(dx, n)
+        back = hd.fft_c2r_2d(X, n, n - 3, n - 3)
+        ref = oracle.dft_r2c_2d(x[sel], n)
+    got = _c(X[torch.from_numpy(sel).cuda()])
+    assert _relerr(got, ref) <= TOL
+    err = float((back - dx).abs().max()) / float(dx.abs().max())
+    assert err <= TOL
