@@ -100,6 +100,41 @@ __device__ __forceinline__ void unstage_linear(float *dst, const float *src, uns
     }
 }
 
+
+// Copy a contiguous block of `rows` rows of w floats (consecutive planes of h rows each) into
+// an LDS image with padded strides (row stride rs, plane stride ps), V floats per load
+// (V divides w; the block start is V*4-byte aligned).  Batched like stage_linear.
+template <int BT, int V>
+__device__ __forceinline__ void stage_padded(float *dst, const float *src, unsigned rows, unsigned w,
+                                             unsigned h, unsigned rs, unsigned ps, MagicDiv div_wv,
+                                             MagicDiv div_h, int tid) {
+    constexpr int U = (V == 1) ? 8 : 6;
+    typedef float vec_t __attribute__((ext_vector_type(V)));
+    const unsigned wv = w / V, total = rows * wv;
+    const vec_t *sv = reinterpret_cast<const vec_t *>(src);
+    for (unsigned base = tid; base < total; base += BT * U) {
+        vec_t v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned e = base + u * BT;
+            v[u] = vec_t(0.f);
+            if (e < total) v[u] = sv[e];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned e = base + u * BT;
+            if (e < total) {
+                const unsigned row = mdiv(e, div_wv);
+                const unsigned c = (e - row * wv) * V;
+                const unsigned pl = mdiv(row, div_h);
+                float *d = dst + pl * ps + (row - pl * h) * rs + c;
+#pragma unroll
+                for (int q = 0; q < V; ++q) d[q] = v[u][q];
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------ 2-D forward
 struct Fwd2dParams {
     const float *in;
@@ -108,7 +143,8 @@ struct Fwd2dParams {
     int h_in, w_in;
     int RS, IPS;      // LDS row / plane stride of the staged input (floats, odd)
     int MPS;          // LDS plane stride of the row-transformed data (float2, odd)
-    MagicDiv div_hw, div_w;
+    MagicDiv div_wv, div_h;   // row length in load vectors, rows per plane
+    int vecw;                 // floats per staging load when the image is padded: 4, 2 or 1
     FreqLayout lay;
     int linear;       // staged planes need no padding: LDS image == global image
     int vec_ok;       // input base and every block start are 16-byte aligned
@@ -152,31 +188,16 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
     // ---- stage the contiguous block of np planes into LDS (coalesced reads)
     {
         const float *src = prm.in + p0 * hw;
-        const unsigned total = (unsigned)np * hw;
         if (prm.linear) {
-            stage_linear<BT>(sin, src, total, tid, prm.vec_ok != 0);
+            stage_linear<BT>(sin, src, (unsigned)np * hw, tid, prm.vec_ok != 0);
         } else {
-            constexpr int U = 8;
-            for (unsigned base = tid; base < total; base += BT * U) {
-                float v[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const unsigned e = base + u * BT;
-                    v[u] = 0.f;
-                    if (e < total) v[u] = src[e];
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const unsigned e = base + u * BT;
-                    if (e < total) {
-                        const unsigned pl = mdiv(e, prm.div_hw);
-                        const unsigned r = e - pl * hw;
-                        const unsigned row = mdiv(r, prm.div_w);
-                        const unsigned col = r - row * w_in;
-                        sin[pl * prm.IPS + row * prm.RS + col] = v[u];
-                    }
-                }
-            }
+            const unsigned rows = (unsigned)np * h_in;
+            if (prm.vecw == 4)
+                stage_padded<BT, 4>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+            else if (prm.vecw == 2)
+                stage_padded<BT, 2>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+            else
+                stage_padded<BT, 1>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
         }
     }
     __syncthreads();
@@ -644,11 +665,24 @@ static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in
     constexpr int N = L * G, NH = N / 2;
     Fwd2dParams prm;
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_in = h_in; prm.w_in = w_in;
+    // LDS strides of the staged planes.  Odd strides by default: when w_in and h_in*w_in are
+    // already odd the block is copied as it lies in memory, with 16-byte loads (that plain copy
+    // measured worth more than any bank layout).  When padding is needed anyway and lanes work
+    // in groups, pick the strides that spread a half-wave over all 32 banks: row-phase lanes are
+    // ordered (lane-in-group g, plane p, row pair rp) and read element g + G*m of their rows,
+    // bank = g + rp*RS + p*IPS (mod 32), so RS = G and IPS = G * (row pairs per 32 lanes) mod 32.
     prm.RS = w_in | 1;
     prm.IPS = (h_in * prm.RS) | 1;
+    if (G > 1 && !(prm.RS == w_in && prm.IPS == h_in * w_in)) {
+        auto up_to_residue = [](int v, int r) { return v + ((r - v) % 32 + 32) % 32; };
+        const int rows32 = 32 / (G * T) > 0 ? 32 / (G * T) : 1;
+        prm.RS = up_to_residue(w_in, G);
+        prm.IPS = up_to_residue(h_in * prm.RS, (G * rows32) % 32);
+    }
     prm.MPS = (h_in * NH) | 1;
-    prm.div_hw = make_magic((unsigned)(h_in * w_in));
-    prm.div_w = make_magic((unsigned)w_in);
+    prm.vecw = (((size_t)in & 15) == 0 && w_in % 4 == 0) ? 4 : ((((size_t)in & 7) == 0 && w_in % 2 == 0) ? 2 : 1);
+    prm.div_wv = make_magic((unsigned)(w_in / prm.vecw));
+    prm.div_h = make_magic((unsigned)h_in);
     prm.lay.tsh = fft2d_tile_log2(N);
     prm.lay.bins = N * (NH + 1);
     prm.linear = (prm.RS == w_in && prm.IPS == h_in * w_in) ? 1 : 0;
