@@ -30,10 +30,15 @@ STAGES = ("fft", "contraction", "ifft")   # kernels of one pass, in launch order
 # scaled by what the same counters read for a plain 256 MiB copy: x2.00 and x1.00); the runs
 # and the table are in profiles/c2_hbm_traffic.md.  Keyed by workload, then "pass.stage".
 MEASURED_TRAFFIC_BYTES = {
-    "C2": {
-        "fprop.contraction": (2.616e4 * 2.0 + 3.482e4) * 1024,
+    "C2": {   # keys: the eight launches of the fprop_save + backward step
+        "fprop.fft": (1.200e4 * 2.0 + 5.222e4) * 1024,
+        "fprop.contraction": (2.617e4 * 2.0 + 3.482e4) * 1024,
+        "fprop.ifft": (1.753e4 * 2.0 + 1.693e4) * 1024,
+        "backward.fft": (8.595e3 * 2.0 + 3.482e4) * 1024,
         "bprop.contraction": (2.617e4 * 2.0 + 3.482e4) * 1024,
-        "accgrad.contraction": (3.487e4 * 2.0 + 1.741e4) * 1024,
+        "bprop.ifft": (1.753e4 * 2.0 + 2.333e4) * 1024,
+        "accgrad.contraction": (3.489e4 * 2.0 + 1.741e4) * 1024,
+        "accgrad.ifft": (8.794e3 * 2.0 + 4.00e2) * 1024,
     },
 }
 
@@ -319,7 +324,7 @@ def main():
         kn = "fft2d_c2r_kernel" if ds == "ifft" else "fft2d_r2c_kernel"
         roof = {"kernel": f"{dom} ({kn})", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
-    tr = MEASURED_TRAFFIC_BYTES.get(name, {}).get(dom)
+    tr = MEASURED_TRAFFIC_BYTES.get(name, {}).get(dom) if (reuse or ds == "contraction") else None
     roof["traffic"] = None if tr is None else round(tr)
     roof["algorithmic_bytes"] = model["bytes"]
     roof["avg_launch_ms"] = dms
