@@ -7,6 +7,7 @@
 //   bprop   GX = sum_j  GY_sj . W_ji
 //   accGrad GW = sum_s  conj(GY_sj) . X_si
 // each followed by the inverse transform and a crop at the origin.
+#include <cstdlib>
 #include "../../include/fftconv.h"
 #include "kernels.hpp"
 
@@ -144,14 +145,28 @@ static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a
     return launch_fft2d_r2c(b, BF, p.planesB, p.hB, p.wB, p.N, true, LaunchCtx{lc.stream, nullptr, lc.stop});
 }
 
+// The contraction of one pass as the kernels see it.
+static GemmProblem gemm_problem(const PassPlan &p, const float *AF, const float *BF, float *CF) {
+    GemmProblem g;
+    g.A = GemmOperand{AF, p.lay, p.a_rs, p.a_cs, p.conjA};
+    g.B = GemmOperand{BF, p.lay, p.b_rs, p.b_cs, p.conjB};
+    g.C = CF; g.layC = p.lay; g.C_rs = p.c_rs; g.C_cs = p.c_cs;
+    g.M = p.M; g.N = p.Nn; g.K = p.K; g.bins = p.bins;
+    return g;
+}
+
+// Inverse transform + crop of one pass's product (1/N^2 folded into the output scale).
+static hipError_t invert(fftconv_ctx *c, const PassPlan &p, const float *CF, float *out, float scale, int accumulate) {
+    const float s = scale / ((float)p.N * (float)p.N);
+    return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c));
+}
+
 // Contraction + inverse transform of one pass, operands already in the frequency domain.
 static hipError_t contract_and_invert(fftconv_ctx *c, const PassPlan &p, const float *AF, const float *BF,
                                       float *CF, float *out, float scale, int accumulate) {
-    hipError_t e;
-    GemmOperand ga{AF, p.lay, p.a_rs, p.a_cs, p.conjA}, gb{BF, p.lay, p.b_rs, p.b_cs, p.conjB};
-    if ((e = launch_cgemm_bins(ga, gb, CF, p.lay, p.c_rs, p.c_cs, p.M, p.Nn, p.K, p.bins, next_ctx(c))) != hipSuccess) return e;
-    const float s = scale / ((float)p.N * (float)p.N);
-    return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c));
+    const GemmProblem g = gemm_problem(p, AF, BF, CF);
+    if (hipError_t e = launch_cgemm_bins(g.A, g.B, g.C, g.layC, g.C_rs, g.C_cs, g.M, g.N, g.K, g.bins, next_ctx(c)); e != hipSuccess) return e;
+    return invert(c, p, CF, out, scale, accumulate);
 }
 
 static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB, float *out,
@@ -314,8 +329,9 @@ size_t fftconv_backward_workspace_bytes(int S, int f, int fo, int h, int w, int 
     if (make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb) != FFTCONV_OK) return 0;
     if (make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa) != FFTCONV_OK) return 0;
     const size_t gyf = align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256);
+    // one product buffer per pass: the two contractions may run in one launch
     const size_t cb = pb.lay.floats(pb.planesC) * sizeof(float), ca = pa.lay.floats(pa.planesC) * sizeof(float);
-    return gyf + align_up(cb > ca ? cb : ca, 256);
+    return gyf + align_up(cb, 256) + align_up(ca, 256);
 }
 
 int fft_conv_fprop_save(fftconv_handle hd, const float *x, const float *wt, float *y,
@@ -353,13 +369,27 @@ int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
     if ((rc = get_workspace(hd, need, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     const float *XF = at(const_cast<void *>(saved), sp.offX), *WF = at(const_cast<void *>(saved), sp.offW);
     float *GYF = at(ws, 0);
-    float *CF = at(ws, align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256));
+    const size_t off_gxf = align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256);
+    float *GXF = at(ws, off_gxf);
+    float *GWF = at(ws, off_gxf + align_up(pb.lay.floats(pb.planesC) * sizeof(float), 256));
     hd->nk = 0;
     hipError_t e;
     if ((e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
     // bprop: GX = GY . W ; accGrad: GW = conj(GY) . X  (operand A of both plans is GYF)
-    if (gx && (e = contract_and_invert(hd, pb, GYF, WF, CF, gx, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
-    if (gw && (e = contract_and_invert(hd, pa, GYF, XF, CF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
+    if (gx && gw) {
+        const GemmProblem qb = gemm_problem(pb, GYF, WF, GXF), qa = gemm_problem(pa, GYF, XF, GWF);
+        if (cgemm_pair_supported(qb, qa)) {
+            // both contractions in one launch, then the two inverse transforms
+            // (the one with the longer reduction first: its workgroups run longest)
+            const bool a_first = pa.K >= pb.K;
+            if ((e = launch_cgemm_pair(a_first ? qa : qb, a_first ? qb : qa, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+            if ((e = invert(hd, pb, GXF, gx, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
+            if ((e = invert(hd, pa, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
+            return FFTCONV_OK;
+        }
+    }
+    if (gx && (e = contract_and_invert(hd, pb, GYF, WF, GXF, gx, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
+    if (gw && (e = contract_and_invert(hd, pa, GYF, XF, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
     return FFTCONV_OK;
 }
 

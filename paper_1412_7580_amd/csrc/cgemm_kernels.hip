@@ -117,8 +117,9 @@ struct TileLoader {
     }
 };
 
-template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int PD>
-__global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmParams prm) {
+// One workgroup's share of the contraction: workgroup number wg of prm's grid.
+template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int PD>
+__device__ __forceinline__ void cgemm_bins_body(const GemmParams &prm, const unsigned wg) {
     constexpr int NT = 64 * WGM * WGN;
     constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32;
     constexpr int SA = TM + 2, SB = TN + 2;        // +2: conflict-free transposing stores
@@ -132,7 +133,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
 
     // XCD-aware decomposition of the flat workgroup index (see file header).
     const int tiles = prm.tiles_m * prm.tiles_n;
-    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int xcd = wg % kXcds, slot = wg / kXcds;
     const int bins_per_xcd = prm.bins / kXcds;
     const int bin = xcd * bins_per_xcd + slot / tiles;
     const int tile = slot % tiles;
@@ -171,34 +172,55 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
     __syncthreads();
 
     const int lrow = lane & 31, lk = lane >> 5;
-    auto compute = [&](int cur) {
-        const float *a0 = As + cur * ABUF + (wm * FM * 32 + lrow);
-        const float *b0 = Bs + cur * BBUF + (wn * FN * 32 + lrow);
+    // The k-steps of the tile in LDS buffer cur, software-pipelined: the LDS reads of step
+    // s + 1 are issued before the MFMAs of step s, so a wave on its own keeps the matrix
+    // pipe fed.  mid() runs half way through the tile.
+    struct Frag { float a_re[FM], a_im[FM], b_re[FN], b_im[FN]; };
+    auto read_frag = [&](Frag &f, const float *a0, const float *b0, int ks) {
 #pragma unroll
-        for (int ks = 0; ks < TK; ks += 2) {
-            float a_re[FM], a_im[FM], a_sm[FM], b_re[FN], b_im[FN], b_sm[FN];
+        for (int i = 0; i < FM; ++i) {
+            f.a_re[i] = a0[(ks + lk) * SA + i * 32];
+            f.a_im[i] = a0[TK * SA + (ks + lk) * SA + i * 32];
+        }
 #pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                a_re[i] = a0[(ks + lk) * SA + i * 32];
-                a_im[i] = flip(a0[TK * SA + (ks + lk) * SA + i * 32], prm.a_sign);
-                a_sm[i] = a_re[i] + a_im[i];
-            }
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                b_re[j] = b0[(ks + lk) * SB + j * 32];
-                b_im[j] = flip(b0[TK * SB + (ks + lk) * SB + j * 32], prm.b_sign);
-                b_sm[j] = b_re[j] + b_im[j];
-            }
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    acc_p1[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re[i], b_re[j], acc_p1[i][j], 0, 0, 0);
-                    acc_p2[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im[i], b_im[j], acc_p2[i][j], 0, 0, 0);
-                    acc_p3[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_sm[i], b_sm[j], acc_p3[i][j], 0, 0, 0);
-                }
+        for (int j = 0; j < FN; ++j) {
+            f.b_re[j] = b0[(ks + lk) * SB + j * 32];
+            f.b_im[j] = b0[TK * SB + (ks + lk) * SB + j * 32];
         }
     };
+    auto mma = [&](const Frag &f) {
+        float a_im[FM], a_sm[FM], b_im[FN], b_sm[FN];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) { a_im[i] = flip(f.a_im[i], prm.a_sign); a_sm[i] = f.a_re[i] + a_im[i]; }
+#pragma unroll
+        for (int j = 0; j < FN; ++j) { b_im[j] = flip(f.b_im[j], prm.b_sign); b_sm[j] = f.b_re[j] + b_im[j]; }
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                acc_p1[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a_re[i], f.b_re[j], acc_p1[i][j], 0, 0, 0);
+                acc_p2[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im[i], b_im[j], acc_p2[i][j], 0, 0, 0);
+                acc_p3[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_sm[i], b_sm[j], acc_p3[i][j], 0, 0, 0);
+            }
+    };
+    auto compute = [&](int cur, auto &&mid) {
+        const float *a0 = As + cur * ABUF + (wm * FM * 32 + lrow);
+        const float *b0 = Bs + cur * BBUF + (wn * FN * 32 + lrow);
+        Frag f[2];
+        read_frag(f[0], a0, b0, 0);
+        static_for_gemm<0, TK / 2>([&](auto ss) {
+            constexpr int st = decltype(ss)::value;
+            if constexpr (st + 1 < TK / 2) read_frag(f[(st + 1) & 1], a0, b0, 2 * (st + 1));
+            __builtin_amdgcn_sched_barrier(0);
+            mma(f[st & 1]);
+            if constexpr (st == TK / 4 - 1) mid();
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // Iteration kt multiplies tile kt out of LDS buffer kt & 1.  Half way through, tile kt + 1
+    // moves from its registers into the other buffer (which every wave left at the barrier
+    // that ended iteration kt - 1) and the freed registers take the gathers of tile
+    // kt + 1 + PD, so that between two tiles a wave only passes a barrier.
     for (int kt0 = 0; kt0 < nkt; kt0 += PD) {
         static_for_gemm<0, PD>([&](auto dd) {
             constexpr int d = decltype(dd)::value;
@@ -206,14 +228,14 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
             const int kt = kt0 + d;
             if (kt < nkt) {
                 const int cur = kt & 1;
-                compute(cur);
-                if (kt + 1 < nkt) {
-                    // buffer cur^1 was last read in iteration kt-1, which every wave has left
-                    la[dn].store(As + (cur ^ 1) * ABUF, tid);
-                    lb[dn].store(Bs + (cur ^ 1) * BBUF, tid);
-                    if (kt + 1 + PD < nkt) issue(la[dn], lb[dn], kt + 1 + PD);
-                    __syncthreads();
-                }
+                compute(cur, [&]() {
+                    if (kt + 1 < nkt) {
+                        la[dn].store(As + (cur ^ 1) * ABUF, tid);
+                        lb[dn].store(Bs + (cur ^ 1) * BBUF, tid);
+                        if (kt + 1 + PD < nkt) issue(la[dn], lb[dn], kt + 1 + PD);
+                    }
+                });
+                if (kt + 1 < nkt) __syncthreads();
             }
         });
     }
@@ -238,6 +260,25 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
         }
 }
 
+template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int PD>
+__global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmParams prm) {
+    cgemm_bins_body<WGM, WGN, FM, FN, TK, AKF, BKF, VEC, PD>(prm, blockIdx.x);
+}
+
+// Two independent contractions in one launch (the two backward passes of a layer share
+// their first operand and neither waits for the other): workgroups [0, n1) work on p1, the
+// rest on p2.  One grid means one ramp-up and one tail instead of two, and the second
+// problem's workgroups fill the slots that the first one's stragglers leave idle.
+struct GemmPairParams {
+    GemmParams p1, p2;
+    unsigned n1;
+};
+template <bool AKF1, bool BKF1, bool AKF2, bool BKF2>
+__global__ void __launch_bounds__(256, 3) cgemm_pair_kernel(GemmPairParams pp) {
+    if (blockIdx.x < pp.n1) cgemm_bins_body<2, 2, 1, 1, 16, AKF1, BKF1, true, 1>(pp.p1, blockIdx.x);
+    else cgemm_bins_body<2, 2, 1, 1, 16, AKF2, BKF2, true, 1>(pp.p2, blockIdx.x - pp.n1);
+}
+
 template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int PD = 1>
 static hipError_t run_gemm(GemmParams prm, LaunchCtx st) {
     constexpr int TM = WGM * FM * 32, TN = WGN * FN * 32;
@@ -252,8 +293,8 @@ static hipError_t run_gemm(GemmParams prm, LaunchCtx st) {
 }
 
 // Tile shapes (M x N on four waves): 0 128x128, 1 64x128, 2 128x64, 3 64x64; 4 and 5 are 64x64
-// with 2 and 4 tiles of register staging ahead.  1-, 2- and 8-wave workgroups and TK = 8 / 32 were also measured; none
-// beat shape 3.
+// with 2 and 4 tiles of register staging ahead.  3 is the default, the others are kept for
+// A/B runs.  1-, 2- and 8-wave workgroups and TK = 8 / 32 were also measured; none beat 3.
 template <bool AKF, bool BKF, bool VEC>
 static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
     switch (shape) {
@@ -269,24 +310,32 @@ static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
 
 hipError_t launch_cgemm_bingroup(const GemmParams &prm, bool akf, bool bkf, LaunchCtx st);
 
-static int pick_tile(int M, int N, int K, int bins) {
+static int pick_tile() {
     if (const char *e = getenv("FFTCONV_GEMM_TILE")) return atoi(e);
-    (void)M; (void)N; (void)bins;
-    // 64x64 tiles on four waves measured fastest for every layer shape tried (more
-    // workgroups in flight beat the larger tiles' operand reuse); two tiles of register
-    // staging ahead pay off once the reduction is long.
-    return K >= 8 * 16 ? 4 : 3;
+    // 64x64 tiles on four waves with one tile of register staging ahead measured fastest for
+    // every layer shape tried (more workgroups in flight beat the larger tiles' operand
+    // reuse and the deeper staging's registers).
+    return 3;
 }
 
-hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
-                             long C_cs, int M, int N, int K, int bins, LaunchCtx st) {
-    if (bins % kXcds != 0) return hipErrorInvalidValue;   // N*(N/2+1) with N >= 8 always is
+// Kernel parameters of one contraction and the kernel variant it can use.
+struct Prepared {
     GemmParams prm;
+    bool akf, bkf;     // the reduction index is the contiguous plane index of A / B
+    bool vec;          // 16-byte gathers are possible
+    bool bingroup;     // the four-bins-per-line kernel applies
+};
+
+static hipError_t prepare(const GemmOperand &A, const GemmOperand &B, float *C, FreqLayout layC, long C_rs,
+                          long C_cs, int M, int N, int K, int bins, Prepared *out) {
+    if (bins % kXcds != 0) return hipErrorInvalidValue;   // N*(N/2+1) with N >= 8 always is
+    GemmParams &prm = out->prm;
     prm.A = A.ptr; prm.B = B.ptr; prm.C = C;
     prm.layA = A.lay; prm.layB = B.lay; prm.layC = layC;
     prm.a_rs = A.rs; prm.a_cs = A.cs; prm.b_rs = B.rs; prm.b_cs = B.cs;
     prm.c_rs = C_rs; prm.c_cs = C_cs;
     prm.M = M; prm.N = N; prm.K = K; prm.bins = bins;
+    prm.tiles_m = prm.tiles_n = 0;
     prm.a_sign = A.conj ? 0x80000000u : 0u;
     prm.b_sign = B.conj ? 0x80000000u : 0u;
     const bool akf = (A.cs == 1), bkf = (B.rs == 1);
@@ -297,26 +346,85 @@ hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout 
     };
     const bool va = akf ? vec_ok(A.lay, K, A.rs, A.ptr) : (A.rs == 1 && vec_ok(A.lay, M, A.cs, A.ptr));
     const bool vb = bkf ? vec_ok(B.lay, K, B.cs, B.ptr) : (B.cs == 1 && vec_ok(B.lay, N, B.rs, B.ptr));
-    const bool vec = va && vb;
-    const int shape = pick_tile(M, N, K, bins);
+    out->akf = akf; out->bkf = bkf; out->vec = va && vb;
     // Layouts with runs of 4 planes (basis 64) put four bins in every 128-byte line: the
     // bin-group kernel loads whole lines and multiplies the four bins side by side.
     const char *no_bg_env = getenv("FFTCONV_GEMM_NO_BINGROUP");
     const bool no_bg = no_bg_env && atoi(no_bg_env);
-    if (vec && !no_bg && A.lay.tsh == 2 && B.lay.tsh == 2 && layC.tsh == 2 && bins % (4 * kXcds) == 0 &&
-        (akf || A.rs == 1) && (bkf || B.cs == 1) && C_cs == 1 && C_rs % 4 == 0 && N % 4 == 0 &&
-        ((size_t)C & 15) == 0)
-        return launch_cgemm_bingroup(prm, akf, bkf, st);
-    if (vec) {
-        if (akf && bkf) return dispatch_tile<true, true, true>(shape, prm, st);
-        if (akf && !bkf) return dispatch_tile<true, false, true>(shape, prm, st);
-        if (!akf && !bkf) return dispatch_tile<false, false, true>(shape, prm, st);
+    out->bingroup = out->vec && !no_bg && A.lay.tsh == 2 && B.lay.tsh == 2 && layC.tsh == 2 &&
+                    bins % (4 * kXcds) == 0 && (akf || A.rs == 1) && (bkf || B.cs == 1) && C_cs == 1 &&
+                    C_rs % 4 == 0 && N % 4 == 0 && ((size_t)C & 15) == 0;
+    return hipSuccess;
+}
+
+static hipError_t launch_prepared(const Prepared &q, LaunchCtx st) {
+    const GemmParams &prm = q.prm;
+    if (q.bingroup) return launch_cgemm_bingroup(prm, q.akf, q.bkf, st);
+    const int shape = pick_tile();
+    if (q.vec) {
+        if (q.akf && q.bkf) return dispatch_tile<true, true, true>(shape, prm, st);
+        if (q.akf && !q.bkf) return dispatch_tile<true, false, true>(shape, prm, st);
+        if (!q.akf && !q.bkf) return dispatch_tile<false, false, true>(shape, prm, st);
         return dispatch_tile<false, true, true>(shape, prm, st);
     }
-    if (akf && bkf) return dispatch_tile<true, true, false>(shape, prm, st);
-    if (akf && !bkf) return dispatch_tile<true, false, false>(shape, prm, st);
-    if (!akf && !bkf) return dispatch_tile<false, false, false>(shape, prm, st);
+    if (q.akf && q.bkf) return dispatch_tile<true, true, false>(shape, prm, st);
+    if (q.akf && !q.bkf) return dispatch_tile<true, false, false>(shape, prm, st);
+    if (!q.akf && !q.bkf) return dispatch_tile<false, false, false>(shape, prm, st);
     return dispatch_tile<false, true, false>(shape, prm, st);
+}
+
+hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
+                             long C_cs, int M, int N, int K, int bins, LaunchCtx st) {
+    Prepared q;
+    if (hipError_t e = prepare(A, B, C, layC, C_rs, C_cs, M, N, K, bins, &q); e != hipSuccess) return e;
+    return launch_prepared(q, st);
+}
+
+template <bool AKF1, bool BKF1, bool AKF2, bool BKF2>
+static hipError_t run_pair(GemmPairParams &pp, LaunchCtx st) {
+    constexpr int TM = 64, TN = 64, TK = 16;
+    for (GemmParams *g : {&pp.p1, &pp.p2}) {
+        g->tiles_m = (g->M + TM - 1) / TM;
+        g->tiles_n = (g->N + TN - 1) / TN;
+    }
+    const long n1 = (long)pp.p1.bins * pp.p1.tiles_m * pp.p1.tiles_n;
+    const long n2 = (long)pp.p2.bins * pp.p2.tiles_m * pp.p2.tiles_n;
+    pp.n1 = (unsigned)n1;     // a multiple of the XCD count, as bins is
+    const size_t lds = (size_t)(2 * 2 * TK * (TM + 2) + 2 * 2 * TK * (TN + 2)) * sizeof(float);
+    auto k = cgemm_pair_kernel<AKF1, BKF1, AKF2, BKF2>;
+    if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
+    launch_kernel(k, dim3((unsigned)(n1 + n2)), dim3(256), lds, st, pp);
+    return hipGetLastError();
+}
+
+template <bool AKF1, bool BKF1>
+static hipError_t pair_second(const Prepared &q2, GemmPairParams &pp, LaunchCtx st) {
+    if (q2.akf && q2.bkf) return run_pair<AKF1, BKF1, true, true>(pp, st);
+    if (q2.akf && !q2.bkf) return run_pair<AKF1, BKF1, true, false>(pp, st);
+    if (!q2.akf && !q2.bkf) return run_pair<AKF1, BKF1, false, false>(pp, st);
+    return run_pair<AKF1, BKF1, false, true>(pp, st);
+}
+
+bool cgemm_pair_supported(const GemmProblem &g1, const GemmProblem &g2) {
+    if (getenv("FFTCONV_GEMM_TILE")) return false;       // A/B runs of single-kernel shapes
+    if (const char *e = getenv("FFTCONV_GEMM_NO_PAIR")) if (atoi(e)) return false;
+    Prepared q1, q2;
+    if (prepare(g1.A, g1.B, g1.C, g1.layC, g1.C_rs, g1.C_cs, g1.M, g1.N, g1.K, g1.bins, &q1) != hipSuccess) return false;
+    if (prepare(g2.A, g2.B, g2.C, g2.layC, g2.C_rs, g2.C_cs, g2.M, g2.N, g2.K, g2.bins, &q2) != hipSuccess) return false;
+    return q1.vec && q2.vec && !q1.bingroup && !q2.bingroup;
+}
+
+hipError_t launch_cgemm_pair(const GemmProblem &g1, const GemmProblem &g2, LaunchCtx st) {
+    Prepared q1, q2;
+    if (hipError_t e = prepare(g1.A, g1.B, g1.C, g1.layC, g1.C_rs, g1.C_cs, g1.M, g1.N, g1.K, g1.bins, &q1); e != hipSuccess) return e;
+    if (hipError_t e = prepare(g2.A, g2.B, g2.C, g2.layC, g2.C_rs, g2.C_cs, g2.M, g2.N, g2.K, g2.bins, &q2); e != hipSuccess) return e;
+    if (!(q1.vec && q2.vec) || q1.bingroup || q2.bingroup) return hipErrorInvalidValue;
+    GemmPairParams pp;
+    pp.p1 = q1.prm; pp.p2 = q2.prm; pp.n1 = 0;
+    if (q1.akf && q1.bkf) return pair_second<true, true>(q2, pp, st);
+    if (q1.akf && !q1.bkf) return pair_second<true, false>(q2, pp, st);
+    if (!q1.akf && !q1.bkf) return pair_second<false, false>(q2, pp, st);
+    return pair_second<false, true>(q2, pp, st);
 }
 
 }  // namespace fc

@@ -84,4 +84,16 @@ struct GemmOperand {
 hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
                              long C_cs, int M, int N, int K, int bins, LaunchCtx st);
 
+// Two independent contractions in one launch (see cgemm_pair_kernel).  Possible when both
+// can use 16-byte gathers and neither is a case for the four-bins-per-line kernel.
+struct GemmProblem {
+    GemmOperand A, B;
+    float *C;
+    FreqLayout layC;
+    long C_rs, C_cs;
+    int M, N, K, bins;
+};
+bool cgemm_pair_supported(const GemmProblem &g1, const GemmProblem &g2);
+hipError_t launch_cgemm_pair(const GemmProblem &g1, const GemmProblem &g2, LaunchCtx st);
+
 }  // namespace fc
