@@ -20,6 +20,8 @@
  *    is launched, so on an error other than FFTCONV_HIP_ERROR no device work was issued.
  *  - The Fourier basis is square with N = the smallest power of two >= max(h, w),
  *    at least 8 and at most 128 (the range of the paper's 2-D kernels, Section 5.3).
+ *    Layers that would need a larger basis are tiled (Section 6): the passes then run on
+ *    windows of the images with a small basis, with identical results.
  */
 #ifndef FFTCONV_H
 #define FFTCONV_H
@@ -35,7 +37,7 @@ typedef struct fftconv_ctx *fftconv_handle;
 typedef enum {
     FFTCONV_OK = 0,
     FFTCONV_INVALID_ARG = 1,         /* null pointer, non-positive size, kernel larger than input, n_in > n ... */
-    FFTCONV_UNSUPPORTED = 2,         /* Fourier basis outside {8,16,32,64,128} */
+    FFTCONV_UNSUPPORTED = 2,         /* Fourier basis outside {8,16,32,64,128}; kernel larger than 128 */
     FFTCONV_WORKSPACE_TOO_SMALL = 3, /* caller-supplied workspace smaller than fftconv_workspace_bytes() */
     FFTCONV_HIP_ERROR = 4            /* allocation or launch failure reported by the HIP runtime */
 } fftconv_status;
@@ -85,6 +87,30 @@ int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *
                      float scale, int accumulate, void *ws, size_t ws_bytes);
 
 /*
+ * Tiled passes (the tiling strategy of Section 6).  An output tile of d rows needs d + kh - 1
+ * input rows, so a large convolution splits into many small ones on a basis of
+ * tile_n = d + kh - 1 (columns alike): fprop and bprop by overlapping input windows, accGrad
+ * by summing the per-tile correlations, the tile index joining the minibatch index in the
+ * reduction.  Results equal those of the untiled calls up to rounding.  tile_n is a power of
+ * two in 8..128, at least max(kh, kw); 0 lets the library choose (the basis with the fewest
+ * frequency bins overall).  The untiled entry points above tile by themselves, with that
+ * choice, exactly when max(h, w) > 128.  Arguments, layouts and errors as for the untiled
+ * calls; tile_n < 0, not a power of two or smaller than the kernel gives FFTCONV_INVALID_ARG.
+ */
+size_t fftconv_tiled_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw, int tile_n);
+/* The basis a tiled call with this tile_n uses (host only; 0 for invalid arguments). */
+int fftconv_tile_basis(int h, int w, int kh, int kw, int tile_n);
+int fft_conv_fprop_tiled(fftconv_handle hd, const float *x, const float *wt, float *y,
+                         int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                         void *ws, size_t ws_bytes);
+int fft_conv_bprop_tiled(fftconv_handle hd, const float *gy, const float *wt, float *gx,
+                         int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                         void *ws, size_t ws_bytes);
+int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, float *gw,
+                           int S, int f, int fo, int h, int w, int kh, int kw,
+                           float scale, int accumulate, int tile_n, void *ws, size_t ws_bytes);
+
+/*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
  * (Supplement, DFT definition); n in {8,16,32,64,128}.  Inputs shorter than n are
  * zero-padded implicitly while loading (the clipping of Section 5.1), no padded copy is
@@ -106,8 +132,8 @@ int fft_c2r_2d(fftconv_handle hd, const float *in, float *out, long B, int n, in
 
 /*
  * Reuse of transforms between the passes of one layer (the first of the two opportunities
- * Section 6 of the paper lists and forgoes for lack of memory: "reuse 2 FFT results in each
- * hidden layer").  fft_conv_fprop_save computes the same y as fft_conv_fprop and leaves the
+ * Section 6 of the paper lists and forgoes for lack of memory: keeping transforms that a
+ * layer's passes share).  fft_conv_fprop_save computes the same y as fft_conv_fprop and leaves the
  * transforms of x and wt in the caller's `saved` buffer (device memory, at least
  * fftconv_saved_bytes(), contents private).  fft_conv_backward then computes gx (as
  * fft_conv_bprop) and gw (as fft_conv_accgrad, with scale / accumulate) from gy and that

@@ -19,6 +19,8 @@ SYMBOLS = [
     "fft_r2c_1d", "fft_c2r_1d", "fft_r2c_2d", "fft_c2r_2d",
     "fftconv_set_profiling", "fftconv_last_kernel_ms",
     "fftconv_saved_bytes", "fftconv_backward_workspace_bytes", "fft_conv_fprop_save", "fft_conv_backward",
+    "fftconv_tiled_workspace_bytes", "fftconv_tile_basis",
+    "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled",
 ]
 
 
@@ -61,6 +63,12 @@ def load_library():
     lib.fftconv_backward_workspace_bytes.restype = sz
     lib.fft_conv_fprop_save.argtypes = [vp, vp, vp, vp] + [i] * 7 + [vp, sz, vp, sz]
     lib.fft_conv_backward.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i, vp, sz, vp, sz]
+    lib.fftconv_tiled_workspace_bytes.argtypes = [i] * 9
+    lib.fftconv_tiled_workspace_bytes.restype = sz
+    lib.fftconv_tile_basis.argtypes = [i] * 5
+    lib.fft_conv_fprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
+    lib.fft_conv_bprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
+    lib.fft_conv_accgrad_tiled.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i, i, vp, sz]
     _lib = lib
     return lib
 
@@ -206,6 +214,58 @@ class Handle:
         _check(self._lib.fft_conv_accgrad(self._h, _dev_f32(x, "x"), _dev_f32(gy, "gy"), _dev_f32(gw, "gw"),
                                           S, f, fo, h, w, kh, kw, float(scale), 1 if accumulate else 0,
                                           *self._ws(ws)), "fft_conv_accgrad")
+        return gw
+
+    # ---- tiled passes ---------------------------------------------------------------------
+    def tiled_workspace_bytes(self, pass_, S, f, fo, h, w, kh, kw, tile_n) -> int:
+        return int(self._lib.fftconv_tiled_workspace_bytes(pass_, S, f, fo, h, w, kh, kw, tile_n))
+
+    def tile_basis(self, h, w, kh, kw, tile_n) -> int:
+        return int(self._lib.fftconv_tile_basis(h, w, kh, kw, tile_n))
+
+    def fft_conv_fprop_tiled(self, x, wt, tile_n, y=None, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f:
+            raise FFTConvError("x and wt disagree on the number of input planes")
+        if y is None:
+            y = torch.empty((S, fo, h - kh + 1, w - kw + 1), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop_tiled(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
+                                              S, f, fo, h, w, kh, kw, int(tile_n), *self._ws(ws)),
+               "fft_conv_fprop_tiled")
+        return y
+
+    def fft_conv_bprop_tiled(self, gy, wt, h, w, tile_n, gx=None, ws=None):
+        import torch
+        S, fo, oh, ow = gy.shape
+        fo2, f, kh, kw = wt.shape
+        if fo2 != fo or oh != h - kh + 1 or ow != w - kw + 1:
+            raise FFTConvError("gy, wt and (h, w) disagree")
+        if gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_bprop_tiled(self._h, _dev_f32(gy, "gy"), _dev_f32(wt, "wt"), _dev_f32(gx, "gx"),
+                                              S, f, fo, h, w, kh, kw, int(tile_n), *self._ws(ws)),
+               "fft_conv_bprop_tiled")
+        return gx
+
+    def fft_conv_accgrad_tiled(self, x, gy, tile_n, gw=None, scale=1.0, accumulate=False, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        S2, fo, oh, ow = gy.shape
+        if S2 != S:
+            raise FFTConvError("x and gy disagree on the minibatch size")
+        kh, kw = h - oh + 1, w - ow + 1
+        if gw is None:
+            if accumulate:
+                raise FFTConvError("accumulate needs an existing gw")
+            gw = torch.empty((fo, f, kh, kw), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_accgrad_tiled(self._h, _dev_f32(x, "x"), _dev_f32(gy, "gy"), _dev_f32(gw, "gw"),
+                                                S, f, fo, h, w, kh, kw, float(scale), 1 if accumulate else 0,
+                                                int(tile_n), *self._ws(ws)), "fft_conv_accgrad_tiled")
         return gw
 
     @staticmethod

@@ -45,49 +45,122 @@ struct PassPlan {
     long a_rs, a_cs, b_rs, b_cs, c_rs, c_cs;
     FreqLayout lay;
     size_t offA, offB, offC, total;
+    // Tiling (Section 6 of the paper): which operands are windows of larger images, and how.
+    bool tiled;
+    bool viewA, viewB, viewC;
+    PlaneView vA, vB, vC;
 };
 
-static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int kw, PassPlan *p) {
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static bool pow2_basis(int n) { return n == 8 || n == 16 || n == 32 || n == 64 || n == 128; }
+
+// Tile basis used when the caller leaves the choice to the library: the power of two that
+// minimises (number of tiles) x (bins per tile), a proxy for both the contraction's work and
+// the frequency tensors' size.  Output tiles are (n - kh + 1) x (n - kw + 1).
+static int pick_tile_basis(int h, int w, int kh, int kw) {
+    const int oh = h - kh + 1, ow = w - kw + 1;
+    int best = 0;
+    double best_cost = 0;
+    for (int n = 8; n <= 128; n <<= 1) {
+        if (n < kh || n < kw) continue;
+        const double cost = (double)ceil_div(oh, n - kh + 1) * ceil_div(ow, n - kw + 1) * n * (n / 2 + 1);
+        if (!best || cost < best_cost) { best = n; best_cost = cost; }
+    }
+    return best;
+}
+
+// tile_n: -1 = no tiling unless the layer needs it (basis above 128), 0 = tile with the
+// library's choice of basis, else tile with basis tile_n.
+static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int kw, PassPlan *p, int tile_n = -1) {
     if (S <= 0 || f <= 0 || fo <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0) return FFTCONV_INVALID_ARG;
     if (kh > h || kw > w) return FFTCONV_INVALID_ARG;
     if (pass < 0 || pass > 2) return FFTCONV_INVALID_ARG;
-    const int N = basis_size(h, w);
-    if (N > 128) return FFTCONV_UNSUPPORTED;
+    if (tile_n > 0 && (!pow2_basis(tile_n) || tile_n < kh || tile_n < kw)) return FFTCONV_INVALID_ARG;
+    int N = basis_size(h, w);
+    bool tiled = tile_n >= 0;
+    if (N > 128) { tiled = true; if (tile_n < 0) tile_n = 0; }
+    if (tiled && tile_n == 0) tile_n = pick_tile_basis(h, w, kh, kw);
+    if (tiled && tile_n == 0) return FFTCONV_UNSUPPORTED;   // kernel larger than every basis
+    if (tiled) N = tile_n;
     const int oh = h - kh + 1, ow = w - kw + 1;
+    const int dy = N - kh + 1, dx = N - kw + 1;             // output tile (tiled plans only)
     p->N = N;
     p->bins = N * (N / 2 + 1);
     p->lay.tsh = fft2d_tile_log2(N);
     p->lay.bins = p->bins;
     p->conjA = p->conjB = false;
+    p->tiled = tiled;
+    p->viewA = p->viewB = p->viewC = false;
+    p->vA = p->vB = p->vC = PlaneView{};
+    auto imin = [](int a, int b) { return a < b ? a : b; };
     switch (pass) {
-        case FFTCONV_FPROP:
-            p->planesA = (long)S * f;  p->hA = h;  p->wA = w;
+        case FFTCONV_FPROP: {
+            long Sm = S;
+            p->hA = h;  p->wA = w;  p->hC = oh; p->wC = ow;
+            if (tiled) {
+                // y[a0 + r] needs x[a0 + r + u]: windows of N rows starting at the tile origin
+                const int nty = ceil_div(oh, dy), ntx = ceil_div(ow, dx);
+                Sm = (long)S * nty * ntx;
+                p->viewA = true; p->vA = PlaneView{f, nty, ntx, dy, dx, 0, 0, h, w};
+                p->hA = imin(N, h); p->wA = imin(N, w);
+                p->viewC = true; p->vC = PlaneView{fo, nty, ntx, dy, dx, 0, 0, oh, ow};
+                p->hC = imin(dy, oh); p->wC = imin(dx, ow);
+            }
+            p->planesA = Sm * f;
             p->planesB = (long)fo * f; p->hB = kh; p->wB = kw; p->conjB = true;
-            p->planesC = (long)S * fo; p->hC = oh; p->wC = ow;
-            p->M = S; p->Nn = fo; p->K = f;
+            p->planesC = Sm * fo;
+            p->M = (int)Sm; p->Nn = fo; p->K = f;
             p->a_rs = f;  p->a_cs = 1;     // A(s,i) = XF[s][i]
             p->b_rs = 1;  p->b_cs = f;     // B(i,j) = conj WF[j][i]
             p->c_rs = fo; p->c_cs = 1;     // C(s,j) = YF[s][j]
             break;
-        case FFTCONV_BPROP:
-            p->planesA = (long)S * fo; p->hA = oh; p->wA = ow;
+        }
+        case FFTCONV_BPROP: {
+            long Sm = S;
+            p->hA = oh; p->wA = ow; p->hC = h;  p->wC = w;
+            if (tiled) {
+                // gx[p0 + t] = sum_u gy[p0 + t - u] w[u]: windows of N rows starting kh - 1 rows
+                // before the tile origin; the cyclic result is valid from row kh - 1 on
+                const int nty = ceil_div(h, dy), ntx = ceil_div(w, dx);
+                Sm = (long)S * nty * ntx;
+                p->viewA = true; p->vA = PlaneView{fo, nty, ntx, dy, dx, -(kh - 1), -(kw - 1), oh, ow};
+                p->hA = N; p->wA = N;
+                p->viewC = true; p->vC = PlaneView{f, nty, ntx, dy, dx, kh - 1, kw - 1, h, w};
+                p->hC = imin(dy, h); p->wC = imin(dx, w);
+            }
+            p->planesA = Sm * fo;
             p->planesB = (long)fo * f; p->hB = kh; p->wB = kw;
-            p->planesC = (long)S * f;  p->hC = h;  p->wC = w;
-            p->M = S; p->Nn = f; p->K = fo;
+            p->planesC = Sm * f;
+            p->M = (int)Sm; p->Nn = f; p->K = fo;
             p->a_rs = fo; p->a_cs = 1;     // A(s,j) = GYF[s][j]
             p->b_rs = f;  p->b_cs = 1;     // B(j,i) = WF[j][i]
             p->c_rs = f;  p->c_cs = 1;     // C(s,i) = GXF[s][i]
             break;
-        default:
-            p->planesA = (long)S * fo; p->hA = oh; p->wA = ow; p->conjA = true;
-            p->planesB = (long)S * f;  p->hB = h;  p->wB = w;
+        }
+        default: {
+            long Sm = S;
+            p->hA = oh; p->wA = ow; p->hB = h;  p->wB = w;
+            if (tiled) {
+                // gw[u] = sum over samples and tiles of (gy tile) correlated with (x window):
+                // the tile index joins the sample index in the reduction
+                const int nty = ceil_div(oh, dy), ntx = ceil_div(ow, dx);
+                Sm = (long)S * nty * ntx;
+                p->viewA = true; p->vA = PlaneView{fo, nty, ntx, dy, dx, 0, 0, oh, ow};
+                p->hA = imin(dy, oh); p->wA = imin(dx, ow);
+                p->viewB = true; p->vB = PlaneView{f, nty, ntx, dy, dx, 0, 0, h, w};
+                p->hB = imin(N, h); p->wB = imin(N, w);
+            }
+            p->planesA = Sm * fo; p->conjA = true;
+            p->planesB = Sm * f;
             p->planesC = (long)fo * f; p->hC = kh; p->wC = kw;
-            p->M = fo; p->Nn = f; p->K = S;
+            p->M = fo; p->Nn = f; p->K = (int)Sm;
             p->a_rs = 1;  p->a_cs = fo;    // A(j,s) = conj GYF[s][j]
             p->b_rs = f;  p->b_cs = 1;     // B(s,i) = XF[s][i]
             p->c_rs = f;  p->c_cs = 1;     // C(j,i) = GWF[j][i]
             break;
+        }
     }
+    if (p->planesA > 0x7fffffffL || p->planesB > 0x7fffffffL || p->planesC > 0x7fffffffL) return FFTCONV_UNSUPPORTED;
     p->offA = 0;
     p->offB = align_up(p->offA + p->lay.floats(p->planesA) * sizeof(float), 256);
     p->offC = align_up(p->offB + p->lay.floats(p->planesB) * sizeof(float), 256);
@@ -134,15 +207,16 @@ static float *at(void *base, size_t off) { return reinterpret_cast<float *>(stat
 // the pair as one entry only in the shared case, so that case also pairs the events.
 static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a, float *AF,
                                const float *b, float *BF) {
+    const PlaneView *va = p.viewA ? &p.vA : nullptr, *vb = p.viewB ? &p.vB : nullptr;
     if (p.N <= 32) {
-        FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA}, {b, BF, p.planesB, p.hB, p.wB}};
+        FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, va}, {b, BF, p.planesB, p.hB, p.wB, vb}};
         return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c));
     }
     // one event pair around both launches: start from the first, stop from the second
     LaunchCtx lc = next_ctx(c);
-    hipError_t e = launch_fft2d_r2c(a, AF, p.planesA, p.hA, p.wA, p.N, true, LaunchCtx{lc.stream, lc.start, nullptr});
+    hipError_t e = launch_fft2d_r2c(a, AF, p.planesA, p.hA, p.wA, p.N, true, LaunchCtx{lc.stream, lc.start, nullptr}, va);
     if (e != hipSuccess) return e;
-    return launch_fft2d_r2c(b, BF, p.planesB, p.hB, p.wB, p.N, true, LaunchCtx{lc.stream, nullptr, lc.stop});
+    return launch_fft2d_r2c(b, BF, p.planesB, p.hB, p.wB, p.N, true, LaunchCtx{lc.stream, nullptr, lc.stop}, vb);
 }
 
 // The contraction of one pass as the kernels see it.
@@ -158,7 +232,8 @@ static GemmProblem gemm_problem(const PassPlan &p, const float *AF, const float 
 // Inverse transform + crop of one pass's product (1/N^2 folded into the output scale).
 static hipError_t invert(fftconv_ctx *c, const PassPlan &p, const float *CF, float *out, float scale, int accumulate) {
     const float s = scale / ((float)p.N * (float)p.N);
-    return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c));
+    return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c),
+                            p.viewC ? &p.vC : nullptr);
 }
 
 // Contraction + inverse transform of one pass, operands already in the frequency domain.
@@ -171,10 +246,10 @@ static hipError_t contract_and_invert(fftconv_ctx *c, const PassPlan &p, const f
 
 static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB, float *out,
                     int S, int f, int fo, int h, int w, int kh, int kw, float scale, int accumulate,
-                    void *ws, size_t ws_bytes) {
+                    void *ws, size_t ws_bytes, int tile_n = -1) {
     if (!c || !opA || !opB || !out) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p);
+    int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p, tile_n);
     if (rc != FFTCONV_OK) return rc;
     if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     float *AF = at(ws, p.offA), *BF = at(ws, p.offB), *CF = at(ws, p.offC);
@@ -263,6 +338,39 @@ int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *
     return run_pass(hd, FFTCONV_ACCGRAD, gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, ws, ws_bytes);
 }
 
+size_t fftconv_tiled_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw, int tile_n) {
+    PassPlan p;
+    if (tile_n < 0 || make_plan(pass, S, f, fo, h, w, kh, kw, &p, tile_n) != FFTCONV_OK) return 0;
+    return p.total;
+}
+
+int fftconv_tile_basis(int h, int w, int kh, int kw, int tile_n) {
+    PassPlan p;
+    if (tile_n < 0 || make_plan(FFTCONV_FPROP, 1, 1, 1, h, w, kh, kw, &p, tile_n) != FFTCONV_OK) return 0;
+    return p.N;
+}
+
+int fft_conv_fprop_tiled(fftconv_handle hd, const float *x, const float *wt, float *y,
+                         int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                         void *ws, size_t ws_bytes) {
+    if (tile_n < 0) return FFTCONV_INVALID_ARG;
+    return run_pass(hd, FFTCONV_FPROP, x, wt, y, S, f, fo, h, w, kh, kw, 1.0f, 0, ws, ws_bytes, tile_n);
+}
+
+int fft_conv_bprop_tiled(fftconv_handle hd, const float *gy, const float *wt, float *gx,
+                         int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                         void *ws, size_t ws_bytes) {
+    if (tile_n < 0) return FFTCONV_INVALID_ARG;
+    return run_pass(hd, FFTCONV_BPROP, gy, wt, gx, S, f, fo, h, w, kh, kw, 1.0f, 0, ws, ws_bytes, tile_n);
+}
+
+int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, float *gw,
+                           int S, int f, int fo, int h, int w, int kh, int kw,
+                           float scale, int accumulate, int tile_n, void *ws, size_t ws_bytes) {
+    if (tile_n < 0) return FFTCONV_INVALID_ARG;
+    return run_pass(hd, FFTCONV_ACCGRAD, gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, ws, ws_bytes, tile_n);
+}
+
 static bool fft_size_ok(int n) { return n == 8 || n == 16 || n == 32 || n == 64 || n == 128; }
 
 int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in, int n) {
@@ -324,14 +432,29 @@ size_t fftconv_saved_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
     return saved_plan(p).total;
 }
 
+// Workspace of fft_conv_backward: [GYF for bprop | GYF for accGrad (tiled layers only: the two
+// passes cut gy into different windows) | GXF | GWF], one product buffer per pass because the
+// two contractions may run in one launch.
+struct BackwardPlan {
+    size_t offGYb, offGYa, offGX, offGW, total;
+};
+static BackwardPlan backward_plan(const PassPlan &pb, const PassPlan &pa) {
+    BackwardPlan b;
+    b.offGYb = 0;
+    b.offGYa = 0;
+    size_t at = align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256);
+    if (pb.tiled) { b.offGYa = at; at += align_up(pa.lay.floats(pa.planesA) * sizeof(float), 256); }
+    b.offGX = at; at += align_up(pb.lay.floats(pb.planesC) * sizeof(float), 256);
+    b.offGW = at; at += align_up(pa.lay.floats(pa.planesC) * sizeof(float), 256);
+    b.total = at;
+    return b;
+}
+
 size_t fftconv_backward_workspace_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
     PassPlan pb, pa;
     if (make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb) != FFTCONV_OK) return 0;
     if (make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa) != FFTCONV_OK) return 0;
-    const size_t gyf = align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256);
-    // one product buffer per pass: the two contractions may run in one launch
-    const size_t cb = pb.lay.floats(pb.planesC) * sizeof(float), ca = pa.lay.floats(pa.planesC) * sizeof(float);
-    return gyf + align_up(cb, 256) + align_up(ca, 256);
+    return backward_plan(pb, pa).total;
 }
 
 int fft_conv_fprop_save(fftconv_handle hd, const float *x, const float *wt, float *y,
@@ -365,19 +488,26 @@ int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
     (void)make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa);
     const SavedPlan sp = saved_plan(pf);
     if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
-    const size_t need = fftconv_backward_workspace_bytes(S, f, fo, h, w, kh, kw);
-    if ((rc = get_workspace(hd, need, &ws, ws_bytes)) != FFTCONV_OK) return rc;
+    const BackwardPlan bp = backward_plan(pb, pa);
+    if ((rc = get_workspace(hd, bp.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     const float *XF = at(const_cast<void *>(saved), sp.offX), *WF = at(const_cast<void *>(saved), sp.offW);
-    float *GYF = at(ws, 0);
-    const size_t off_gxf = align_up(pb.lay.floats(pb.planesA) * sizeof(float), 256);
-    float *GXF = at(ws, off_gxf);
-    float *GWF = at(ws, off_gxf + align_up(pb.lay.floats(pb.planesC) * sizeof(float), 256));
+    float *GYF = at(ws, bp.offGYb), *GYFa = at(ws, bp.offGYa);
+    float *GXF = at(ws, bp.offGX), *GWF = at(ws, bp.offGW);
     hd->nk = 0;
     hipError_t e;
-    if ((e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+    if (!pb.tiled) {
+        if ((e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+    } else {
+        // gy cut twice: overlapping windows for bprop, disjoint tiles for accGrad
+        LaunchCtx lc = next_ctx(hd);
+        if (gx && (e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true,
+                                        LaunchCtx{lc.stream, lc.start, gw ? nullptr : lc.stop}, &pb.vA)) != hipSuccess) return hip_fail(hd, e);
+        if (gw && (e = launch_fft2d_r2c(gy, GYFa, pa.planesA, pa.hA, pa.wA, pa.N, true,
+                                        LaunchCtx{lc.stream, gx ? nullptr : lc.start, lc.stop}, &pa.vA)) != hipSuccess) return hip_fail(hd, e);
+    }
     // bprop: GX = GY . W ; accGrad: GW = conj(GY) . X  (operand A of both plans is GYF)
     if (gx && gw) {
-        const GemmProblem qb = gemm_problem(pb, GYF, WF, GXF), qa = gemm_problem(pa, GYF, XF, GWF);
+        const GemmProblem qb = gemm_problem(pb, GYF, WF, GXF), qa = gemm_problem(pa, GYFa, XF, GWF);
         if (cgemm_pair_supported(qb, qa)) {
             // both contractions in one launch, then the two inverse transforms
             // (the one with the longer reduction first: its workgroups run longest)
@@ -389,7 +519,7 @@ int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
         }
     }
     if (gx && (e = contract_and_invert(hd, pb, GYF, WF, GXF, gx, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
-    if (gw && (e = contract_and_invert(hd, pa, GYF, XF, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
+    if (gw && (e = contract_and_invert(hd, pa, GYFa, XF, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
     return FFTCONV_OK;
 }
 

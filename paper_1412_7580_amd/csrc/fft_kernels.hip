@@ -135,6 +135,93 @@ __device__ __forceinline__ void stage_padded(float *dst, const float *src, unsig
     }
 }
 
+// ------------------------------------------------------------------ tiled operands
+// Image offset and window origin (before the view's oy / ox) of plane p of a tiled operand.
+struct PlaneOrigin {
+    long long base;
+    int y0, x0;
+};
+__device__ __forceinline__ PlaneOrigin plane_origin(const PlaneView &v, long p) {
+    const long m = p / v.C;
+    const int ch = (int)(p - m * v.C);
+    const long q = m / v.ntx;
+    const int tx = (int)(m - q * v.ntx);
+    const long s = q / v.nty;
+    const int ty = (int)(q - s * v.nty);
+    return PlaneOrigin{((s * v.C + ch) * (long long)v.H) * v.W, ty * v.dy, tx * v.dx};
+}
+
+// Per-workgroup table of the origins of its np planes, kept in LDS at `info`
+// (T x 16 bytes: bases, then y0, then x0).
+template <int T>
+struct OriginTable {
+    long long *base;
+    int *y0, *x0;
+    __device__ __forceinline__ explicit OriginTable(float *info)
+        : base(reinterpret_cast<long long *>(info)), y0(reinterpret_cast<int *>(info + 2 * T)), x0(y0 + T) {}
+    __device__ __forceinline__ void fill(const PlaneView &v, long p0, int np, int tid) {
+        if (tid < np) {
+            const PlaneOrigin o = plane_origin(v, p0 + tid);
+            base[tid] = o.base; y0[tid] = o.y0; x0[tid] = o.x0;
+        }
+        __syncthreads();
+    }
+};
+
+// Gather the h x w windows of np planes into an LDS image with row stride rs and plane
+// stride ps; elements outside the H x W image become 0.
+template <int BT, int T>
+__device__ __forceinline__ void stage_windows(float *dst, const float *img, const PlaneView &v,
+                                              const OriginTable<T> &tab, int np, unsigned h, unsigned w,
+                                              unsigned rs, unsigned ps, MagicDiv div_w, MagicDiv div_h, int tid) {
+    constexpr int U = 8;
+    const unsigned total = (unsigned)np * h * w;
+    for (unsigned b = tid; b < total; b += BT * U) {
+        float val[U];
+        unsigned off[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned e = b + u * BT;
+            val[u] = 0.f; off[u] = 0;
+            if (e < total) {
+                const unsigned row = mdiv(e, div_w);
+                const unsigned c = e - row * w;
+                const unsigned pl = mdiv(row, div_h);
+                const unsigned r = row - pl * h;
+                off[u] = pl * ps + r * rs + c;
+                const int gy = tab.y0[pl] + v.oy + (int)r, gx = tab.x0[pl] + v.ox + (int)c;
+                if ((unsigned)gy < (unsigned)v.H && (unsigned)gx < (unsigned)v.W)
+                    val[u] = img[tab.base[pl] + (long long)gy * v.W + gx];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (b + u * BT < total) dst[off[u]] = val[u];
+    }
+}
+
+// Scatter the h x w windows at offset (oy, ox) of an LDS image of np planes of sh x sw floats
+// to their places in the H x W images; elements outside the image are dropped.
+template <int BT, int T>
+__device__ __forceinline__ void unstage_windows(float *img, const float *src, const PlaneView &v,
+                                                const OriginTable<T> &tab, int np, unsigned h, unsigned w,
+                                                unsigned sh, unsigned sw, MagicDiv div_w, MagicDiv div_h,
+                                                int tid, bool accumulate) {
+    const unsigned total = (unsigned)np * h * w;
+    for (unsigned e = tid; e < total; e += BT) {
+        const unsigned row = mdiv(e, div_w);
+        const unsigned c = e - row * w;
+        const unsigned pl = mdiv(row, div_h);
+        const unsigned r = row - pl * h;
+        const int gy = tab.y0[pl] + (int)r, gx = tab.x0[pl] + (int)c;
+        if (gy < v.H && gx < v.W) {
+            float *d = img + tab.base[pl] + (long long)gy * v.W + gx;
+            const float val = src[(pl * sh + r + v.oy) * sw + c + v.ox];
+            if (accumulate) *d += val; else *d = val;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ 2-D forward
 struct Fwd2dParams {
     const float *in;
@@ -149,6 +236,9 @@ struct Fwd2dParams {
     int linear;       // staged planes need no padding: LDS image == global image
     int vec_ok;       // input base and every block start are 16-byte aligned
     int out_vec_ok;   // output base and every block start are 16-byte aligned
+    int tiled;        // planes are windows of images (view); origin table at LDS float info_off
+    int info_off;
+    PlaneView view;
 };
 
 // Store helpers for the two output layouts.  `base` is uniform over the workgroup (block
@@ -186,7 +276,12 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
     const int np = left < T ? (int)left : T;
 
     // ---- stage the contiguous block of np planes into LDS (coalesced reads)
-    {
+    if (prm.tiled) {
+        OriginTable<T> tab(smem + prm.info_off);
+        tab.fill(prm.view, p0, np, tid);
+        stage_windows<BT, T>(sin, prm.in, prm.view, tab, np, h_in, w_in, prm.RS, prm.IPS, prm.div_wv,
+                             prm.div_h, tid);
+    } else {
         const float *src = prm.in + p0 * hw;
         if (prm.linear) {
             stage_linear<BT>(sin, src, (unsigned)np * hw, tid, prm.vec_ok != 0);
@@ -357,6 +452,11 @@ struct Inv2dParams {
     int accumulate;
     int vec_ok;       // output base and every block start are 16-byte aligned
     int in_vec_ok;    // natural layout only: input base is 16-byte aligned
+    int tiled;        // outputs are windows of images (view); origin table at LDS float info_off
+    int info_off;
+    int win_h, win_w; // tiled: size of the window taken at (view.oy, view.ox) of the h_out x w_out block
+    MagicDiv div_w, div_h;
+    PlaneView view;
 };
 
 template <int L, int G, int T, bool CONV, bool ISTAGE>
@@ -472,6 +572,15 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
         }
     }
     __syncthreads();
+    if constexpr (CONV) {
+        if (prm.tiled) {
+            OriginTable<T> tab(smem + prm.info_off);
+            tab.fill(prm.view, p0, np, tid);
+            unstage_windows<BT, T>(prm.out, sout, prm.view, tab, np, prm.win_h, prm.win_w, h_out, w_out,
+                                   prm.div_w, prm.div_h, tid, prm.accumulate != 0);
+            return;
+        }
+    }
     {
         float *dst = prm.out + p0 * (long)h_out * w_out;
         const unsigned total = (unsigned)np * h_out * w_out;
@@ -661,7 +770,8 @@ int fft2d_tile_log2(int N) {
 }
 
 template <int L, int G, int T>
-static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in, int w_in, size_t *lds) {
+static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in, int w_in, size_t *lds,
+                              const PlaneView *view = nullptr) {
     constexpr int N = L * G, NH = N / 2;
     Fwd2dParams prm;
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_in = h_in; prm.w_in = w_in;
@@ -690,15 +800,29 @@ static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in
     prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
     const size_t a = ((size_t)T * prm.IPS + N) * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
     *lds = a > b ? a : b;
+    prm.tiled = 0; prm.info_off = 0; prm.view = PlaneView{};
+    if (view) {   // gathered windows: scalar loads, padded image, origin table behind everything else
+        prm.tiled = 1; prm.view = *view;
+        prm.linear = 0; prm.vecw = 1;
+        prm.div_wv = make_magic((unsigned)w_in);
+    }
     return prm;
+}
+
+// LDS bytes of a launch whose blocks keep an origin table of T planes behind `lds` bytes of
+// other data; *info_off receives the table's offset in floats.
+static size_t with_origin_table(size_t lds, int T, int *info_off) {
+    const size_t at = (lds + 7) / 8 * 8;
+    *info_off = (int)(at / sizeof(float));
+    return at + (size_t)T * 16;
 }
 
 template <int L, int G, int T>
 static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, int w_in,
-                            bool conv, LaunchCtx st) {
+                            bool conv, LaunchCtx st, const PlaneView *view) {
     constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
     size_t lds;
-    const Fwd2dParams prm = make_fwd2d<L, G, T>(in, out, planes, h_in, w_in, &lds);
+    Fwd2dParams prm = make_fwd2d<L, G, T>(in, out, planes, h_in, w_in, &lds, view);
     // Measured: staging the output through LDS pays for the natural layout (short runs per
     // lane otherwise) and costs for the plane-tiled layout, whose direct stores already fill
     // whole runs of T planes.
@@ -707,6 +831,7 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
         const size_t c = (size_t)T * N * (NH + 1) * 2 * sizeof(float);
         if (c > lds) lds = c;
     }
+    if (prm.tiled) lds = with_origin_table(lds, T, &prm.info_off);
     const unsigned grid = (unsigned)((planes + T - 1) / T);
     hipError_t e;
     auto go = [&](auto k) -> hipError_t {
@@ -728,7 +853,8 @@ static hipError_t run_fwd2d_multi(const FwdOperand *ops, int nops, LaunchCtx st)
         m.first[o] = blocks;
         if (o < nops) {
             size_t l;
-            m.op[o] = make_fwd2d<L, G, T>(ops[o].in, ops[o].out, ops[o].planes, ops[o].h_in, ops[o].w_in, &l);
+            m.op[o] = make_fwd2d<L, G, T>(ops[o].in, ops[o].out, ops[o].planes, ops[o].h_in, ops[o].w_in, &l,
+                                          ops[o].view);
             if (l > lds) lds = l;
             blocks += (unsigned)((ops[o].planes + T - 1) / T);
         } else {
@@ -737,6 +863,15 @@ static hipError_t run_fwd2d_multi(const FwdOperand *ops, int nops, LaunchCtx st)
     }
     m.first[3] = blocks;
     for (int o = nops; o < 3; ++o) m.first[o] = blocks;   // unused operands own no blocks
+    {   // one origin table position for all operands, behind the largest footprint
+        int info_off = 0;
+        bool any = false;
+        for (int o = 0; o < nops; ++o) any = any || m.op[o].tiled;
+        if (any) {
+            lds = with_origin_table(lds, T, &info_off);
+            for (int o = 0; o < 3; ++o) m.op[o].info_off = info_off;
+        }
+    }
     auto k = fft2d_r2c_multi_kernel<L, G, T>;
     hipError_t e;
     if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
@@ -759,23 +894,33 @@ hipError_t launch_fft2d_r2c_multi(const FwdOperand *ops, int nops, int N, Launch
 }
 
 hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
-                            bool conv, LaunchCtx st) {
+                            bool conv, LaunchCtx st, const PlaneView *view) {
     if (planes <= 0) return hipSuccess;
+    if (view && !conv) return hipErrorInvalidValue;
     switch (N) {
-        case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, st);
-        case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st);
-        case 32: return run_fwd2d<32, 1, 16>(in, out, planes, h_in, w_in, conv, st);
-        case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st);   // (64,1): 25 % slower, (16,4): 5 % slower
-        case 128: return run_fwd2d<32, 4, 1>(in, out, planes, h_in, w_in, conv, st);
+        case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
+        case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
+        case 32: return run_fwd2d<32, 1, 16>(in, out, planes, h_in, w_in, conv, st, view);
+        case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st, view);   // (64,1): 25 % slower, (16,4): 5 % slower
+        case 128: return run_fwd2d<32, 4, 1>(in, out, planes, h_in, w_in, conv, st, view);
         default: return hipErrorInvalidValue;
     }
 }
 
 template <int L, int G, int T>
 static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out, int w_out,
-                            bool conv, float scale, bool accumulate, LaunchCtx st) {
+                            bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view) {
     constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
     Inv2dParams prm;
+    prm.tiled = 0; prm.info_off = 0; prm.win_h = prm.win_w = 0; prm.view = PlaneView{};
+    prm.div_w = prm.div_h = MagicDiv{0};
+    if (view) {
+        // the block assembled in LDS spans the transform's rows / columns up to the window's end
+        prm.tiled = 1; prm.view = *view;
+        prm.win_h = h_out; prm.win_w = w_out;
+        prm.div_w = make_magic((unsigned)w_out); prm.div_h = make_magic((unsigned)h_out);
+        h_out += view->oy; w_out += view->ox;
+    }
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_out = h_out; prm.w_out = w_out;
     prm.MPS = (h_out * NH) | 1;
     prm.lay.tsh = fft2d_tile_log2(N);
@@ -793,6 +938,7 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
         const size_t c = (size_t)T * N * (NH + 1) * sizeof(float2);
         if (c > lds) lds = c;
     }
+    if (prm.tiled) lds = with_origin_table(lds, T, &prm.info_off);
     const unsigned grid = (unsigned)((planes + T - 1) / T);
     hipError_t e;
     auto go = [&](auto k) -> hipError_t {
@@ -805,18 +951,20 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
 }
 
 hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int h_out, int w_out,
-                            bool conv, float scale, bool accumulate, LaunchCtx st) {
+                            bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view) {
     if (planes <= 0) return hipSuccess;
+    if (view && (!conv || view->oy + h_out > N || view->ox + w_out > N)) return hipErrorInvalidValue;
+    const int rows = h_out + (view ? view->oy : 0);   // rows of the transform that are computed
     switch (N) {
-        case 8: return run_inv2d<8, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
-        case 16: return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 8: return run_inv2d<8, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 16: return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 32:
-            if (conv && 2 * h_out > 32) return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
-            return run_inv2d<16, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+            if (conv && 2 * rows > 32) return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+            return run_inv2d<16, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         // the inverse gains from more lanes per line (fewer registers, shorter serial chains):
         // (16,4) measured 15..25 % faster than (32,2) here, (16,2) 20 % faster than (32,1) at 32
-        case 64: return run_inv2d<16, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
-        case 128: return run_inv2d<32, 4, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st);
+        case 64: return run_inv2d<16, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 128: return run_inv2d<32, 4, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         default: return hipErrorInvalidValue;
     }
 }

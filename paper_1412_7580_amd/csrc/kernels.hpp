@@ -46,14 +46,30 @@ struct FreqLayout {
     }
 };
 
+// How the planes of a tiled operand map to memory (tiling of large inputs into small
+// transforms, Section 6 of the paper).  Plane p = (sample-tile m, channel p % C) with
+// m = (s * nty + ty) * ntx + tx, and the plane's data is a window of image (s, channel):
+//   forward: rows ty*dy + oy ... of H, columns tx*dx + ox ... of W; elements outside the
+//            image read as 0 (the origin may be negative);
+//   inverse: rows oy ... and columns ox ... of the transform's output go to rows ty*dy ...
+//            and columns tx*dx ... of the image; elements outside the image are dropped.
+struct PlaneView {
+    int C;
+    int nty, ntx;
+    int dy, dx;
+    int oy, ox;
+    int H, W;
+};
+
 // Planes per workgroup (= layout tile) of the 2-D kernels for basis N.
 int fft2d_tile_log2(int N);
 
 // 2-D R2C of `planes` planes [h_in x w_in] zero-padded to N x N.
 //   conv layout: out = FreqLayout buffer (tile = fft2d_tile_log2(N)).
 //   natural layout: out = [planes][N][N/2+1][2].
+// With a view, `in` is the image tensor and h_in x w_in the window size.
 hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, int w_in, int N,
-                            bool conv_layout, LaunchCtx st);
+                            bool conv_layout, LaunchCtx st, const PlaneView *view = nullptr);
 
 // The same transform of up to three operand tensors (plane-tiled layout) in ONE launch.
 struct FwdOperand {
@@ -61,13 +77,17 @@ struct FwdOperand {
     float *out;
     long planes;
     int h_in, w_in;
+    const PlaneView *view = nullptr;
 };
 hipError_t launch_fft2d_r2c_multi(const FwdOperand *ops, int nops, int N, LaunchCtx st);
 
 // 2-D C2R + crop.  out[planes][h_out][w_out] = scale * real inverse (the caller folds 1/N^2
 // into `scale`), added to the previous contents when accumulate is set.
+// With a view (plane-tiled layout only), `out` is the image tensor and h_out x w_out the size
+// of the window taken from each transform at offset (view->oy, view->ox).
 hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int h_out, int w_out,
-                            bool conv_layout, float scale, bool accumulate, LaunchCtx st);
+                            bool conv_layout, float scale, bool accumulate, LaunchCtx st,
+                            const PlaneView *view = nullptr);
 
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
 hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);

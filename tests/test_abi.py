@@ -33,10 +33,23 @@ def test_host_only_calls():
     need = lib.fftconv_workspace_bytes(0, 16, 16, 16, 13, 13, 3, 3)
     assert need == 3 * 256 * 144 * 2 * 4
     assert lib.fftconv_saved_bytes(16, 16, 16, 13, 13, 3, 3) == 2 * 256 * 144 * 2 * 4
-    # invalid (kernel larger than input) and unsupported (basis 256) shapes
+    # invalid (kernel larger than input, no such pass) and unsupported (kernel beyond every basis) shapes
     assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 4, 4, 5, 5) == 0
-    assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 200, 200, 3, 3) == 0
+    assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 200, 200, 130, 130) == 0
     assert lib.fftconv_workspace_bytes(3, 1, 1, 1, 8, 8, 3, 3) == 0
+    # an image beyond the largest basis is tiled: 200x200, 3x3 kernel -> the basis with the
+    # fewest bins overall, and the same workspace as the explicit tiled call with that choice
+    n = lib.fftconv_tile_basis(200, 200, 3, 3, 0)
+    assert n in (8, 16, 32, 64, 128)
+    assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 200, 200, 3, 3) == \
+        lib.fftconv_tiled_workspace_bytes(0, 1, 1, 1, 200, 200, 3, 3, n) > 0
+    # forced basis 8 on a 20x20 image with a 3x3 kernel: 6x6 output tiles, 3x3 of them
+    T = 64   # planes per workgroup at basis 8: buffers are padded to whole plane tiles
+    pad = lambda planes: -(-planes // T) * T
+    assert lib.fftconv_tiled_workspace_bytes(0, 2, 3, 4, 20, 20, 3, 3, 8) == \
+        (pad(2 * 9 * 3) + pad(4 * 3) + pad(2 * 9 * 4)) * 40 * 2 * 4
+    assert lib.fftconv_tiled_workspace_bytes(0, 2, 3, 4, 20, 20, 3, 3, 12) == 0
+    assert lib.fftconv_tile_basis(20, 20, 9, 9, 8) == 0
 
 
 def test_no_oracle_in_product():

@@ -1,0 +1,146 @@
+"""Parity of the tiled passes (tiling of large inputs into small transforms, Section 6 of the
+paper) against the time-domain oracle (GPU, C ABI).
+
+Tiling changes how the result is computed, not what it is: the oracle is the same direct
+definition as for the untiled passes and the bound is the same, max|err| / max|ref| <= 1e-4
+over the whole output tensor."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1412_7580_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def hd(lib):
+    h = lib.Handle(0)
+    yield h
+    h.close()
+
+
+def _relerr(got, ref):
+    return float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def _np(t):
+    return t.cpu().numpy().astype(np.float64)
+
+
+# (shape, tile basis): several tiles per image with ragged last tiles in one or both
+# directions, rectangular images and kernels, a window larger than the image (one tile),
+# plane counts that are not multiples of the kernels' plane tile, every basis up to 64, and
+# the library's own choice (0).
+TILED = [
+    (dict(S=2, f=3, fo=4, h=20, w=20, kh=3, kw=3), 8),
+    (dict(S=2, f=3, fo=2, h=21, w=17, kh=3, kw=5), 8),
+    (dict(S=1, f=2, fo=3, h=40, w=33, kh=5, kw=5), 16),
+    (dict(S=3, f=5, fo=3, h=37, w=41, kh=2, kw=4), 16),
+    (dict(S=2, f=2, fo=2, h=30, w=30, kh=7, kw=7), 32),
+    (dict(S=1, f=2, fo=2, h=70, w=50, kh=9, kw=3), 32),
+    (dict(S=1, f=1, fo=2, h=100, w=90, kh=5, kw=5), 64),
+    (dict(S=1, f=2, fo=1, h=90, w=130, kh=33, kw=17), 64),
+    (dict(S=2, f=3, fo=3, h=45, w=45, kh=5, kw=5), 0),
+    (dict(S=1, f=1, fo=1, h=9, w=9, kh=8, kw=8), 8),
+    (dict(S=5, f=9, fo=7, h=24, w=24, kh=1, kw=1), 8),
+]
+IDS = ["S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c) + f"_n{n}" for c, n in TILED]
+
+
+@pytest.mark.parametrize("cfg,tile_n", TILED, ids=IDS)
+def test_tiled_passes(hd, cfg, tile_n):
+    x, w, gy = synth.conv_inputs(seed=300, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    e = _relerr(_np(hd.fft_conv_fprop_tiled(dx, dw, tile_n)), oracle.conv_fprop(x, w))
+    assert e <= TOL, ("fprop", e)
+    e = _relerr(_np(hd.fft_conv_bprop_tiled(dgy, dw, cfg["h"], cfg["w"], tile_n)),
+                oracle.conv_bprop(gy, w, cfg["h"], cfg["w"]))
+    assert e <= TOL, ("bprop", e)
+    e = _relerr(_np(hd.fft_conv_accgrad_tiled(dx, dgy, tile_n)), oracle.conv_accgrad(x, gy))
+    assert e <= TOL, ("accgrad", e)
+
+
+def test_tiled_equals_untiled_at_c2_shape(hd):
+    """AlexNet-like second layer at a reduced plane count: tiled (basis 16) and untiled
+    (basis 32) results agree with the oracle and hence with each other."""
+    cfg = dict(S=8, f=16, fo=12, h=27, w=27, kh=5, kw=5)
+    x, w, gy = synth.conv_inputs(seed=301, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    ref = oracle.conv_fprop(x, w)
+    a, b = _np(hd.fft_conv_fprop_tiled(dx, dw, 16)), _np(hd.fft_conv_fprop(dx, dw))
+    assert _relerr(a, ref) <= TOL and _relerr(b, ref) <= TOL
+    ref = oracle.conv_accgrad(x, gy)
+    a, b = _np(hd.fft_conv_accgrad_tiled(dx, dgy, 16)), _np(hd.fft_conv_accgrad(dx, dgy))
+    assert _relerr(a, ref) <= TOL and _relerr(b, ref) <= TOL
+
+
+def test_large_images_tile_by_themselves(hd):
+    """Images beyond the largest basis (128): the ordinary entry points, and the
+    transform-reuse pair, tile on their own."""
+    import torch
+    cfg = dict(S=1, f=2, fo=3, h=150, w=137, kh=5, kw=3)
+    x, w, gy = synth.conv_inputs(seed=302, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    ry, rgx, rgw = oracle.conv_fprop(x, w), oracle.conv_bprop(gy, w, cfg["h"], cfg["w"]), oracle.conv_accgrad(x, gy)
+    assert _relerr(_np(hd.fft_conv_fprop(dx, dw)), ry) <= TOL
+    assert _relerr(_np(hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"])), rgx) <= TOL
+    assert _relerr(_np(hd.fft_conv_accgrad(dx, dgy)), rgw) <= TOL
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
+    assert saved.numel() > 0
+    y = hd.fft_conv_fprop_save(dx, dw, saved)
+    gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    assert _relerr(_np(y), ry) <= TOL
+    assert _relerr(_np(gx), rgx) <= TOL
+    assert _relerr(_np(gw), rgw) <= TOL
+
+
+def test_tiled_accgrad_scale_and_accumulate(hd):
+    import torch
+    cfg = dict(S=2, f=3, fo=2, h=26, w=22, kh=3, kw=3)
+    x, w, gy = synth.conv_inputs(seed=303, **cfg)
+    dx, dgy = _dev(x), _dev(gy)
+    ref = oracle.conv_accgrad(x, gy)
+    gw0 = torch.full((cfg["fo"], cfg["f"], cfg["kh"], cfg["kw"]), 2.0, device="cuda")
+    got = hd.fft_conv_accgrad_tiled(dx, dgy, 8, gw=gw0, scale=0.5, accumulate=True)
+    assert _relerr(_np(got), 2.0 + 0.5 * ref) <= TOL
+
+
+def test_tiled_workspace_and_errors(hd, lib):
+    import torch
+    cfg = dict(S=2, f=2, fo=2, h=20, w=20, kh=3, kw=3)
+    x, w, _ = synth.conv_inputs(seed=304, **cfg)
+    dx, dw = _dev(x), _dev(w)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    need = hd.tiled_workspace_bytes(lib.FPROP, *dims, 8)
+    assert need > 0
+    ws = torch.empty(need // 4, device="cuda", dtype=torch.float32)
+    y = hd.fft_conv_fprop_tiled(dx, dw, 8, ws=ws)
+    assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
+    with pytest.raises(lib.FFTConvError, match="workspace too small"):
+        hd.fft_conv_fprop_tiled(dx, dw, 8, ws=ws[: need // 4 - 64])
+    for bad in (-1, 12, 256):
+        with pytest.raises(lib.FFTConvError, match="invalid argument"):
+            hd.fft_conv_fprop_tiled(dx, dw, bad)
+    big_k = torch.zeros((1, 1, 9, 9), device="cuda")
+    with pytest.raises(lib.FFTConvError, match="invalid argument"):      # basis smaller than the kernel
+        hd.fft_conv_fprop_tiled(torch.zeros((1, 1, 20, 20), device="cuda"), big_k, 8)
+    assert hd.tile_basis(20, 20, 3, 3, 16) == 16
+    assert hd.tile_basis(200, 200, 5, 5, 0) in (8, 16, 32, 64, 128)
+    assert hd.tile_basis(20, 20, 3, 3, 12) == 0
+
+
+def test_tiled_is_deterministic(hd):
+    cfg = dict(S=2, f=4, fo=4, h=30, w=30, kh=3, kw=3)
+    x, w, gy = synth.conv_inputs(seed=305, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    a = hd.fft_conv_bprop_tiled(dgy, dw, cfg["h"], cfg["w"], 16).clone()
+    b = hd.fft_conv_bprop_tiled(dgy, dw, cfg["h"], cfg["w"], 16)
+    assert bool((a == b).all())
