@@ -234,6 +234,62 @@ def fft_sweep(hd, max_bytes=1 << 28, reps=3):
     return out
 
 
+def tiled_layers(hd, reps=10):
+    """Tiling (Section 6 of the paper) on two layers: an image beyond the largest basis, which
+    the ordinary entry points tile by themselves, and a mid-size layer run untiled and tiled.
+    Timing only (uniform[-1,1) inputs drawn on the device from a fixed seed); parity of the
+    tiled path is covered by the tests."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(6)
+
+    def mk(*shape):
+        return torch.rand(shape, device="cuda", generator=gen) * 2 - 1
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    out = {}
+    S, f, fo, h, w, k = 16, 64, 64, 224, 224, 5
+    x, wt, gy = mk(S, f, h, w), mk(fo, f, k, k), mk(S, fo, h - k + 1, w - k + 1)
+    y, gx, gw = torch.empty_like(gy), torch.empty_like(x), torch.empty_like(wt)
+    saved = torch.empty(hd.saved_bytes(S, f, fo, h, w, k, k) // 4, device="cuda", dtype=torch.float32)
+    fl = 3 * 2.0 * S * f * fo * k * k * (h - k + 1) * (w - k + 1)
+
+    def step():
+        hd.fft_conv_fprop_save(x, wt, saved, y=y)
+        hd.fft_conv_backward(gy, saved, f, h, w, k, k, gx=gx, gw=gw)
+    sec = timed(step)
+    out["S16_f64_f'64_224x224_k5"] = {"tile_basis": hd.tile_basis(h, w, k, k, 0), "ms_per_step": round(sec * 1e3, 4),
+                                      "effective_TFLOPs": round(fl / sec / 1e12, 2),
+                                      "calls": "fft_conv_fprop_save + fft_conv_backward (tile by themselves)"}
+    del x, wt, gy, y, gx, gw, saved
+    S, f, fo, h, w, k = 32, 96, 96, 55, 55, 5
+    x, wt, gy = mk(S, f, h, w), mk(fo, f, k, k), mk(S, fo, h - k + 1, w - k + 1)
+    y, gx, gw = torch.empty_like(gy), torch.empty_like(x), torch.empty_like(wt)
+    fl = 3 * 2.0 * S * f * fo * k * k * (h - k + 1) * (w - k + 1)
+
+    def untiled():
+        hd.fft_conv_fprop(x, wt, y=y); hd.fft_conv_bprop(gy, wt, h, w, gx=gx); hd.fft_conv_accgrad(x, gy, gw=gw)
+
+    def tiled():
+        hd.fft_conv_fprop_tiled(x, wt, 0, y=y); hd.fft_conv_bprop_tiled(gy, wt, h, w, 0, gx=gx)
+        hd.fft_conv_accgrad_tiled(x, gy, 0, gw=gw)
+    su, st = timed(untiled), timed(tiled)
+    out["S32_f96_f'96_55x55_k5"] = {"untiled_basis": 64, "untiled_ms_per_step": round(su * 1e3, 4),
+                                    "untiled_effective_TFLOPs": round(fl / su / 1e12, 2),
+                                    "tile_basis": hd.tile_basis(h, w, k, k, 0), "tiled_ms_per_step": round(st * 1e3, 4),
+                                    "tiled_effective_TFLOPs": round(fl / st / 1e12, 2),
+                                    "calls": "three independent passes each way"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -379,6 +435,8 @@ def main():
                 ent["effective_TFLOPs"] = round(direct_flops(ocfg) * 3 / s2 / 1e12, 2)
             extra[other] = ent
         del t
+        torch.cuda.empty_cache()
+        extra["tiled_layers"] = tiled_layers(hd)
         torch.cuda.empty_cache()
         extra["fft_sweep_256MiB"] = fft_sweep(hd)
         out["extra"] = extra

@@ -92,9 +92,10 @@ int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *
  * tile_n = d + kh - 1 (columns alike): fprop and bprop by overlapping input windows, accGrad
  * by summing the per-tile correlations, the tile index joining the minibatch index in the
  * reduction.  Results equal those of the untiled calls up to rounding.  tile_n is a power of
- * two in 8..128, at least max(kh, kw); 0 lets the library choose (the basis with the fewest
- * frequency bins overall).  The untiled entry points above tile by themselves, with that
- * choice, exactly when max(h, w) > 128.  Arguments, layouts and errors as for the untiled
+ * two in 8..128, at least max(kh, kw); 0 lets the library choose (the basis with the lowest
+ * estimated cost: tiles x bins per tile x a measured per-basis factor).  The untiled entry
+ * points above tile by themselves, with that choice, exactly when max(h, w) > 128.
+ * Arguments, layouts and errors as for the untiled
  * calls; tile_n < 0, not a power of two or smaller than the kernel gives FFTCONV_INVALID_ARG.
  */
 size_t fftconv_tiled_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw, int tile_n);

@@ -55,15 +55,20 @@ static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 static bool pow2_basis(int n) { return n == 8 || n == 16 || n == 32 || n == 64 || n == 128; }
 
 // Tile basis used when the caller leaves the choice to the library: the power of two that
-// minimises (number of tiles) x (bins per tile), a proxy for both the contraction's work and
-// the frequency tensors' size.  Output tiles are (n - kh + 1) x (n - kw + 1).
+// minimises (number of tiles) x (bins per tile) x (relative cost of a bin at that basis).
+// The first two factors count the contraction's work and the frequency tensors' size; the
+// third is measured (224x224 5x5 and 3x3, 160x160 11x11, 55x55 5x5 layers on this chip):
+// basis 32 and 64 run at the same cost per bin, 16 about 1.3x, 8 about 2.5x (many tiny planes),
+// 128 about 3x (one plane per workgroup, scalar gathers in the contraction).
+// Output tiles are (n - kh + 1) x (n - kw + 1).
 static int pick_tile_basis(int h, int w, int kh, int kw) {
     const int oh = h - kh + 1, ow = w - kw + 1;
     int best = 0;
     double best_cost = 0;
     for (int n = 8; n <= 128; n <<= 1) {
         if (n < kh || n < kw) continue;
-        const double cost = (double)ceil_div(oh, n - kh + 1) * ceil_div(ow, n - kw + 1) * n * (n / 2 + 1);
+        const double weight = n == 8 ? 2.5 : n == 16 ? 1.3 : n == 32 ? 1.0 : n == 64 ? 1.05 : 3.0;
+        const double cost = (double)ceil_div(oh, n - kh + 1) * ceil_div(ow, n - kw + 1) * n * (n / 2 + 1) * weight;
         if (!best || cost < best_cost) { best = n; best_cost = cost; }
     }
     return best;
