@@ -300,6 +300,8 @@ def main():
     ap.add_argument("--separate-passes", action="store_true",
                     help="time the three independent pass calls instead of fprop_save + backward")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the FFT sweep")
+    ap.add_argument("--tiled-only", action="store_true",
+                    help="only time the tiled layers of the extra block and print them (for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy a few times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -324,6 +326,9 @@ def main():
     from paper_1412_7580_amd import synth
 
     hd = pkg.Handle(0)
+    if args.tiled_only:
+        print(json.dumps({"tiled_layers": tiled_layers(hd)}))
+        return
     name = args.workload
     cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k != "passes"}
     passes = synth.CONV_CONFIGS[name]["passes"]

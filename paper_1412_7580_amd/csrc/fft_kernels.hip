@@ -169,54 +169,63 @@ struct OriginTable {
 };
 
 // Gather the h x w windows of np planes into an LDS image with row stride rs and plane
-// stride ps; elements outside the H x W image become 0.
-template <int BT, int T>
+// stride ps; elements outside the H x W image become 0.  V floats per load: V = 4 needs every
+// window column origin, W, w and the image base to be multiples of 4 floats, so that a
+// group of 4 lies wholly inside or outside the image and is 16-byte aligned; div_w divides
+// by w / V.
+template <int BT, int T, int V>
 __device__ __forceinline__ void stage_windows(float *dst, const float *img, const PlaneView &v,
                                               const OriginTable<T> &tab, int np, unsigned h, unsigned w,
                                               unsigned rs, unsigned ps, MagicDiv div_w, MagicDiv div_h, int tid) {
-    constexpr int U = 8;
-    const unsigned total = (unsigned)np * h * w;
+    constexpr int U = (V == 1) ? 8 : 4;
+    typedef float vec_t __attribute__((ext_vector_type(V)));
+    const unsigned wv = w / V, total = (unsigned)np * h * wv;
     for (unsigned b = tid; b < total; b += BT * U) {
-        float val[U];
+        vec_t val[U];
         unsigned off[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const unsigned e = b + u * BT;
-            val[u] = 0.f; off[u] = 0;
+            val[u] = vec_t(0.f); off[u] = 0;
             if (e < total) {
                 const unsigned row = mdiv(e, div_w);
-                const unsigned c = e - row * w;
+                const unsigned c = (e - row * wv) * V;
                 const unsigned pl = mdiv(row, div_h);
                 const unsigned r = row - pl * h;
                 off[u] = pl * ps + r * rs + c;
                 const int gy = tab.y0[pl] + v.oy + (int)r, gx = tab.x0[pl] + v.ox + (int)c;
                 if ((unsigned)gy < (unsigned)v.H && (unsigned)gx < (unsigned)v.W)
-                    val[u] = img[tab.base[pl] + (long long)gy * v.W + gx];
+                    val[u] = *reinterpret_cast<const vec_t *>(img + tab.base[pl] + (long long)gy * v.W + gx);
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (b + u * BT < total) dst[off[u]] = val[u];
+            if (b + u * BT < total) {
+#pragma unroll
+                for (int q = 0; q < V; ++q) dst[off[u] + q] = val[u][q];
+            }
     }
 }
 
 // Scatter the h x w windows at offset (oy, ox) of an LDS image of np planes of sh x sw floats
-// to their places in the H x W images; elements outside the image are dropped.
-template <int BT, int T>
+// to their places in the H x W images; elements outside the image are dropped.  V = 4 under the
+// same alignment conditions as for the gather, plus sw and ox multiples of 4.
+template <int BT, int T, int V>
 __device__ __forceinline__ void unstage_windows(float *img, const float *src, const PlaneView &v,
                                                 const OriginTable<T> &tab, int np, unsigned h, unsigned w,
                                                 unsigned sh, unsigned sw, MagicDiv div_w, MagicDiv div_h,
                                                 int tid, bool accumulate) {
-    const unsigned total = (unsigned)np * h * w;
+    typedef float vec_t __attribute__((ext_vector_type(V)));
+    const unsigned wv = w / V, total = (unsigned)np * h * wv;
     for (unsigned e = tid; e < total; e += BT) {
         const unsigned row = mdiv(e, div_w);
-        const unsigned c = e - row * w;
+        const unsigned c = (e - row * wv) * V;
         const unsigned pl = mdiv(row, div_h);
         const unsigned r = row - pl * h;
         const int gy = tab.y0[pl] + (int)r, gx = tab.x0[pl] + (int)c;
         if (gy < v.H && gx < v.W) {
-            float *d = img + tab.base[pl] + (long long)gy * v.W + gx;
-            const float val = src[(pl * sh + r + v.oy) * sw + c + v.ox];
+            vec_t *d = reinterpret_cast<vec_t *>(img + tab.base[pl] + (long long)gy * v.W + gx);
+            const vec_t val = *reinterpret_cast<const vec_t *>(src + (pl * sh + r + v.oy) * sw + c + v.ox);
             if (accumulate) *d += val; else *d = val;
         }
     }
@@ -279,8 +288,12 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
     if (prm.tiled) {
         OriginTable<T> tab(smem + prm.info_off);
         tab.fill(prm.view, p0, np, tid);
-        stage_windows<BT, T>(sin, prm.in, prm.view, tab, np, h_in, w_in, prm.RS, prm.IPS, prm.div_wv,
-                             prm.div_h, tid);
+        if (prm.vecw == 4)
+            stage_windows<BT, T, 4>(sin, prm.in, prm.view, tab, np, h_in, w_in, prm.RS, prm.IPS, prm.div_wv,
+                                    prm.div_h, tid);
+        else
+            stage_windows<BT, T, 1>(sin, prm.in, prm.view, tab, np, h_in, w_in, prm.RS, prm.IPS, prm.div_wv,
+                                    prm.div_h, tid);
     } else {
         const float *src = prm.in + p0 * hw;
         if (prm.linear) {
@@ -576,8 +589,12 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
         if (prm.tiled) {
             OriginTable<T> tab(smem + prm.info_off);
             tab.fill(prm.view, p0, np, tid);
-            unstage_windows<BT, T>(prm.out, sout, prm.view, tab, np, prm.win_h, prm.win_w, h_out, w_out,
-                                   prm.div_w, prm.div_h, tid, prm.accumulate != 0);
+            if (prm.vec_ok)
+                unstage_windows<BT, T, 4>(prm.out, sout, prm.view, tab, np, prm.win_h, prm.win_w, h_out, w_out,
+                                          prm.div_w, prm.div_h, tid, prm.accumulate != 0);
+            else
+                unstage_windows<BT, T, 1>(prm.out, sout, prm.view, tab, np, prm.win_h, prm.win_w, h_out, w_out,
+                                          prm.div_w, prm.div_h, tid, prm.accumulate != 0);
             return;
         }
     }
@@ -803,8 +820,11 @@ static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in
     prm.tiled = 0; prm.info_off = 0; prm.view = PlaneView{};
     if (view) {   // gathered windows: scalar loads, padded image, origin table behind everything else
         prm.tiled = 1; prm.view = *view;
-        prm.linear = 0; prm.vecw = 1;
-        prm.div_wv = make_magic((unsigned)w_in);
+        prm.linear = 0;
+        const bool v4 = ((size_t)in & 15) == 0 && view->W % 4 == 0 && view->dx % 4 == 0 && view->ox % 4 == 0 &&
+                        w_in % 4 == 0;
+        prm.vecw = v4 ? 4 : 1;
+        prm.div_wv = make_magic((unsigned)(w_in / prm.vecw));
     }
     return prm;
 }
@@ -914,11 +934,14 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     Inv2dParams prm;
     prm.tiled = 0; prm.info_off = 0; prm.win_h = prm.win_w = 0; prm.view = PlaneView{};
     prm.div_w = prm.div_h = MagicDiv{0};
+    bool tiled_vec = false;
     if (view) {
         // the block assembled in LDS spans the transform's rows / columns up to the window's end
         prm.tiled = 1; prm.view = *view;
         prm.win_h = h_out; prm.win_w = w_out;
-        prm.div_w = make_magic((unsigned)w_out); prm.div_h = make_magic((unsigned)h_out);
+        tiled_vec = ((size_t)out & 15) == 0 && view->W % 4 == 0 && view->dx % 4 == 0 && view->ox % 4 == 0 &&
+                    w_out % 4 == 0;    // then the LDS block's row length ox + w_out is a multiple of 4 too
+        prm.div_w = make_magic((unsigned)(tiled_vec ? w_out / 4 : w_out)); prm.div_h = make_magic((unsigned)h_out);
         h_out += view->oy; w_out += view->ox;
     }
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_out = h_out; prm.w_out = w_out;
@@ -927,6 +950,7 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     prm.lay.bins = N * (NH + 1);
     prm.scale = scale; prm.accumulate = accumulate ? 1 : 0;
     prm.vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * h_out * w_out) % 4 == 0) ? 1 : 0;
+    if (view) prm.vec_ok = tiled_vec ? 1 : 0;   // tiled: 16-byte scatter of the windows
     prm.in_vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)T * prm.MPS * sizeof(float2), b = (size_t)T * h_out * w_out * sizeof(float);
     size_t lds = a > b ? a : b;

@@ -50,6 +50,10 @@ TILED = [
     (dict(S=2, f=3, fo=3, h=45, w=45, kh=5, kw=5), 0),
     (dict(S=1, f=1, fo=1, h=9, w=9, kh=8, kw=8), 8),
     (dict(S=5, f=9, fo=7, h=24, w=24, kh=1, kw=1), 8),
+    # widths, tile pitches and offsets that are multiples of 4: the 16-byte gather / scatter
+    (dict(S=2, f=3, fo=2, h=40, w=40, kh=5, kw=5), 16),
+    (dict(S=1, f=4, fo=3, h=64, w=48, kh=5, kw=5), 32),
+    (dict(S=1, f=2, fo=2, h=37, w=44, kh=3, kw=9), 16),
 ]
 IDS = ["S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c) + f"_n{n}" for c, n in TILED]
 
