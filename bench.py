@@ -287,6 +287,27 @@ def tiled_layers(hd, reps=10):
                                     "tile_basis": hd.tile_basis(h, w, k, k, 0), "tiled_ms_per_step": round(st * 1e3, 4),
                                     "tiled_effective_TFLOPs": round(fl / st / 1e12, 2),
                                     "calls": "three independent passes each way"}
+    del x, wt, gy, y, gx, gw
+    # a layer whose untiled basis would be 128: the ordinary entry points tile it by themselves;
+    # tile basis 128 (one window per image) stands for the untiled basis
+    S, f, fo, h, w, k = 16, 128, 128, 112, 112, 3
+    x, wt, gy = mk(S, f, h, w), mk(fo, f, k, k), mk(S, fo, h - k + 1, w - k + 1)
+    y, gx, gw = torch.empty_like(gy), torch.empty_like(x), torch.empty_like(wt)
+    fl = 3 * 2.0 * S * f * fo * k * k * (h - k + 1) * (w - k + 1)
+
+    def ordinary():
+        hd.fft_conv_fprop(x, wt, y=y); hd.fft_conv_bprop(gy, wt, h, w, gx=gx); hd.fft_conv_accgrad(x, gy, gw=gw)
+
+    def one_tile():
+        hd.fft_conv_fprop_tiled(x, wt, 128, y=y); hd.fft_conv_bprop_tiled(gy, wt, h, w, 128, gx=gx)
+        hd.fft_conv_accgrad_tiled(x, gy, 128, gw=gw)
+    so, s1 = timed(ordinary), timed(one_tile)
+    out["S16_f128_f'128_112x112_k3"] = {"tile_basis": hd.tile_basis(h, w, k, k, 0), "ms_per_step": round(so * 1e3, 4),
+                                        "effective_TFLOPs": round(fl / so / 1e12, 2),
+                                        "basis128_ms_per_step": round(s1 * 1e3, 4),
+                                        "basis128_effective_TFLOPs": round(fl / s1 / 1e12, 2),
+                                        "calls": "three independent passes; ordinary entry points (tile by themselves) "
+                                                 "vs one 128-basis window per image"}
     return out
 
 

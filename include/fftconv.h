@@ -20,8 +20,9 @@
  *    is launched, so on an error other than FFTCONV_HIP_ERROR no device work was issued.
  *  - The Fourier basis is square with N = the smallest power of two >= max(h, w),
  *    at least 8 and at most 128 (the range of the paper's 2-D kernels, Section 5.3).
- *    Layers that would need a larger basis are tiled (Section 6): the passes then run on
- *    windows of the images with a small basis, with identical results.
+ *    Layers that would need a larger basis, and layers for which it is clearly cheaper, are
+ *    tiled (Section 6): the passes then run on windows of the images with a small basis,
+ *    with identical results.
  */
 #ifndef FFTCONV_H
 #define FFTCONV_H
@@ -93,8 +94,9 @@ int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *
  * by summing the per-tile correlations, the tile index joining the minibatch index in the
  * reduction.  Results equal those of the untiled calls up to rounding.  tile_n is a power of
  * two in 8..128, at least max(kh, kw); 0 lets the library choose (the basis with the lowest
- * estimated cost: tiles x bins per tile x a measured per-basis factor).  The untiled entry
- * points above tile by themselves, with that choice, exactly when max(h, w) > 128.
+ * estimated cost: tiles x bins per tile x a measured per-basis factor).  The entry points
+ * above tile by themselves, with that choice, when max(h, w) > 128 and when the estimate is
+ * clearly below that of the untiled basis (in practice: layers whose untiled basis is 128).
  * Arguments, layouts and errors as for the untiled
  * calls; tile_n < 0, not a power of two or smaller than the kernel gives FFTCONV_INVALID_ARG.
  */

@@ -54,6 +54,8 @@ TILED = [
     (dict(S=2, f=3, fo=2, h=40, w=40, kh=5, kw=5), 16),
     (dict(S=1, f=4, fo=3, h=64, w=48, kh=5, kw=5), 32),
     (dict(S=1, f=2, fo=2, h=37, w=44, kh=3, kw=9), 16),
+    # one tile at the largest basis: the conv-layout kernels of basis 128
+    (dict(S=1, f=2, fo=3, h=100, w=128, kh=9, kw=11), 128),
 ]
 IDS = ["S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c) + f"_n{n}" for c, n in TILED]
 
