@@ -148,7 +148,11 @@ def test_repeat_calls_are_deterministic(hd):
     assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("cfg", [SMALL[3], SMALL[6], SMALL[9], dict(S=9, f=20, fo=12, h=16, w=16, kh=3, kw=3)],
+# (the last two take the one-launch form of the two backward contractions, with ragged tiles:
+# accGrad first when its reduction, S, is the longer one, else bprop first)
+@pytest.mark.parametrize("cfg", [SMALL[3], SMALL[6], SMALL[9], dict(S=9, f=20, fo=12, h=16, w=16, kh=3, kw=3),
+                                 dict(S=140, f=8, fo=12, h=8, w=8, kh=3, kw=3),
+                                 dict(S=4, f=72, fo=68, h=9, w=9, kh=3, kw=3)],
                          ids=lambda c: "S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c))
 def test_fprop_save_and_backward(hd, cfg):
     """Transform reuse: fprop_save + backward must give what the three independent passes give
