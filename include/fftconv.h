@@ -114,6 +114,26 @@ int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, f
                            float scale, int accumulate, int tile_n, void *ws, size_t ws_bytes);
 
 /*
+ * Passes of a layer whose input images are surrounded by pad_h rows and pad_w columns of zeros
+ * on every side (the p_h, p_w of Section 2).  No padded copy of x is made: the padding is the
+ * part of a window that falls outside the image (the implicit zero padding of Section 5.1).
+ * x[S,f,h,w] and gx keep their unpadded shape; y and gy are
+ * [S,fo,h+2pad_h-kh+1,w+2pad_w-kw+1].  With pad_h = pad_w = 0 these are the ordinary passes.
+ * Negative padding or a kernel larger than the padded image gives FFTCONV_INVALID_ARG.
+ */
+size_t fftconv_padded_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw,
+                                      int pad_h, int pad_w);
+int fft_conv_fprop_padded(fftconv_handle hd, const float *x, const float *wt, float *y,
+                          int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                          void *ws, size_t ws_bytes);
+int fft_conv_bprop_padded(fftconv_handle hd, const float *gy, const float *wt, float *gx,
+                          int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                          void *ws, size_t ws_bytes);
+int fft_conv_accgrad_padded(fftconv_handle hd, const float *x, const float *gy, float *gw,
+                            int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                            float scale, int accumulate, void *ws, size_t ws_bytes);
+
+/*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
  * (Supplement, DFT definition); n in {8,16,32,64,128}.  Inputs shorter than n are
  * zero-padded implicitly while loading (the clipping of Section 5.1), no padded copy is

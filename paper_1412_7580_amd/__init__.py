@@ -21,6 +21,8 @@ SYMBOLS = [
     "fftconv_saved_bytes", "fftconv_backward_workspace_bytes", "fft_conv_fprop_save", "fft_conv_backward",
     "fftconv_tiled_workspace_bytes", "fftconv_tile_basis",
     "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled",
+    "fftconv_padded_workspace_bytes",
+    "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
 ]
 
 
@@ -69,6 +71,11 @@ def load_library():
     lib.fft_conv_fprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
     lib.fft_conv_bprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
     lib.fft_conv_accgrad_tiled.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i, i, vp, sz]
+    lib.fftconv_padded_workspace_bytes.argtypes = [i] * 10
+    lib.fftconv_padded_workspace_bytes.restype = sz
+    lib.fft_conv_fprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
+    lib.fft_conv_bprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
+    lib.fft_conv_accgrad_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [f, i, vp, sz]
     _lib = lib
     return lib
 
@@ -266,6 +273,56 @@ class Handle:
         _check(self._lib.fft_conv_accgrad_tiled(self._h, _dev_f32(x, "x"), _dev_f32(gy, "gy"), _dev_f32(gw, "gw"),
                                                 S, f, fo, h, w, kh, kw, float(scale), 1 if accumulate else 0,
                                                 int(tile_n), *self._ws(ws)), "fft_conv_accgrad_tiled")
+        return gw
+
+    # ---- zero-padded layers ---------------------------------------------------------------
+    def padded_workspace_bytes(self, pass_, S, f, fo, h, w, kh, kw, pad_h, pad_w) -> int:
+        return int(self._lib.fftconv_padded_workspace_bytes(pass_, S, f, fo, h, w, kh, kw, pad_h, pad_w))
+
+    def fft_conv_fprop_padded(self, x, wt, pad_h, pad_w, y=None, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f:
+            raise FFTConvError("x and wt disagree on the number of input planes")
+        if y is None:
+            y = torch.empty((S, fo, h + 2 * pad_h - kh + 1, w + 2 * pad_w - kw + 1), device=x.device,
+                            dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop_padded(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
+                                               S, f, fo, h, w, kh, kw, int(pad_h), int(pad_w), *self._ws(ws)),
+               "fft_conv_fprop_padded")
+        return y
+
+    def fft_conv_bprop_padded(self, gy, wt, h, w, pad_h, pad_w, gx=None, ws=None):
+        import torch
+        S, fo, oh, ow = gy.shape
+        fo2, f, kh, kw = wt.shape
+        if fo2 != fo or oh != h + 2 * pad_h - kh + 1 or ow != w + 2 * pad_w - kw + 1:
+            raise FFTConvError("gy, wt, (h, w) and the padding disagree")
+        if gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_bprop_padded(self._h, _dev_f32(gy, "gy"), _dev_f32(wt, "wt"), _dev_f32(gx, "gx"),
+                                               S, f, fo, h, w, kh, kw, int(pad_h), int(pad_w), *self._ws(ws)),
+               "fft_conv_bprop_padded")
+        return gx
+
+    def fft_conv_accgrad_padded(self, x, gy, pad_h, pad_w, gw=None, scale=1.0, accumulate=False, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        S2, fo, oh, ow = gy.shape
+        if S2 != S:
+            raise FFTConvError("x and gy disagree on the minibatch size")
+        kh, kw = h + 2 * pad_h - oh + 1, w + 2 * pad_w - ow + 1
+        if gw is None:
+            if accumulate:
+                raise FFTConvError("accumulate needs an existing gw")
+            gw = torch.empty((fo, f, kh, kw), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_accgrad_padded(self._h, _dev_f32(x, "x"), _dev_f32(gy, "gy"), _dev_f32(gw, "gw"),
+                                                 S, f, fo, h, w, kh, kw, int(pad_h), int(pad_w), float(scale),
+                                                 1 if accumulate else 0, *self._ws(ws)), "fft_conv_accgrad_padded")
         return gw
 
     @staticmethod

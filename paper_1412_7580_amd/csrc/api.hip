@@ -79,23 +79,31 @@ static int pick_tile_basis(int h, int w, int kh, int kw, double *cost_out = null
 // when the estimate says tiling is clearly cheaper (in practice the layers whose untiled basis
 // would be 128: measured 2..5x faster tiled at basis 32 or 64); 0 = tile with the library's
 // choice of basis; else tile with basis tile_n.
-static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int kw, PassPlan *p, int tile_n = -1) {
+// ph, pw: rows / columns of zeros around every input image (Section 2's p_h, p_w); the output
+// is then (h + 2 ph - kh + 1) x (w + 2 pw - kw + 1).  Padded layers always run on windows (a
+// single window per image when the padded image fits the basis): the padding is the part of
+// a window that lies outside the image and reads as zero.
+static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int kw, PassPlan *p, int tile_n = -1,
+                     int ph = 0, int pw = 0) {
     if (S <= 0 || f <= 0 || fo <= 0 || h <= 0 || w <= 0 || kh <= 0 || kw <= 0) return FFTCONV_INVALID_ARG;
-    if (kh > h || kw > w) return FFTCONV_INVALID_ARG;
+    if (ph < 0 || pw < 0) return FFTCONV_INVALID_ARG;
+    const int hp = h + 2 * ph, wp = w + 2 * pw;             // padded image
+    if (kh > hp || kw > wp) return FFTCONV_INVALID_ARG;
     if (pass < 0 || pass > 2) return FFTCONV_INVALID_ARG;
     if (tile_n > 0 && (!pow2_basis(tile_n) || tile_n < kh || tile_n < kw)) return FFTCONV_INVALID_ARG;
-    int N = basis_size(h, w);
-    bool tiled = tile_n >= 0;
+    int N = basis_size(hp, wp);
+    bool tiled = tile_n >= 0 || ph > 0 || pw > 0;
+    if (tiled && tile_n < 0) tile_n = 0;
     if (N > 128) { tiled = true; if (tile_n < 0) tile_n = 0; }
     if (!tiled) {
         double cost = 0;
-        const int tn = pick_tile_basis(h, w, kh, kw, &cost);
+        const int tn = pick_tile_basis(hp, wp, kh, kw, &cost);
         if (tn && tn < N && cost < 0.8 * N * (N / 2 + 1) * basis_weight(N)) { tiled = true; tile_n = tn; }
     }
-    if (tiled && tile_n == 0) tile_n = pick_tile_basis(h, w, kh, kw);
+    if (tiled && tile_n == 0) tile_n = pick_tile_basis(hp, wp, kh, kw);
     if (tiled && tile_n == 0) return FFTCONV_UNSUPPORTED;   // kernel larger than every basis
     if (tiled) N = tile_n;
-    const int oh = h - kh + 1, ow = w - kw + 1;
+    const int oh = hp - kh + 1, ow = wp - kw + 1;
     const int dy = N - kh + 1, dx = N - kw + 1;             // output tile (tiled plans only)
     p->N = N;
     p->bins = N * (N / 2 + 1);
@@ -111,11 +119,12 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
             long Sm = S;
             p->hA = h;  p->wA = w;  p->hC = oh; p->wC = ow;
             if (tiled) {
-                // y[a0 + r] needs x[a0 + r + u]: windows of N rows starting at the tile origin
+                // y[a0 + r] needs padded x[a0 + r + u]: windows of N rows starting ph rows
+                // before the tile origin
                 const int nty = ceil_div(oh, dy), ntx = ceil_div(ow, dx);
                 Sm = (long)S * nty * ntx;
-                p->viewA = true; p->vA = PlaneView{f, nty, ntx, dy, dx, 0, 0, h, w};
-                p->hA = imin(N, h); p->wA = imin(N, w);
+                p->viewA = true; p->vA = PlaneView{f, nty, ntx, dy, dx, -ph, -pw, h, w};
+                p->hA = imin(N, h + ph); p->wA = imin(N, w + pw);
                 p->viewC = true; p->vC = PlaneView{fo, nty, ntx, dy, dx, 0, 0, oh, ow};
                 p->hC = imin(dy, oh); p->wC = imin(dx, ow);
             }
@@ -132,11 +141,12 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
             long Sm = S;
             p->hA = oh; p->wA = ow; p->hC = h;  p->wC = w;
             if (tiled) {
-                // gx[p0 + t] = sum_u gy[p0 + t - u] w[u]: windows of N rows starting kh - 1 rows
-                // before the tile origin; the cyclic result is valid from row kh - 1 on
+                // gx[p0 + t] = sum_u gy[p0 + t + ph - u] w[u]: windows of N rows starting
+                // kh - 1 - ph rows before the tile origin; the cyclic result is valid from row
+                // kh - 1 on
                 const int nty = ceil_div(h, dy), ntx = ceil_div(w, dx);
                 Sm = (long)S * nty * ntx;
-                p->viewA = true; p->vA = PlaneView{fo, nty, ntx, dy, dx, -(kh - 1), -(kw - 1), oh, ow};
+                p->viewA = true; p->vA = PlaneView{fo, nty, ntx, dy, dx, ph - (kh - 1), pw - (kw - 1), oh, ow};
                 p->hA = N; p->wA = N;
                 p->viewC = true; p->vC = PlaneView{f, nty, ntx, dy, dx, kh - 1, kw - 1, h, w};
                 p->hC = imin(dy, h); p->wC = imin(dx, w);
@@ -154,14 +164,14 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
             long Sm = S;
             p->hA = oh; p->wA = ow; p->hB = h;  p->wB = w;
             if (tiled) {
-                // gw[u] = sum over samples and tiles of (gy tile) correlated with (x window):
-                // the tile index joins the sample index in the reduction
+                // gw[u] = sum over samples and tiles of (gy tile) correlated with (padded x
+                // window): the tile index joins the sample index in the reduction
                 const int nty = ceil_div(oh, dy), ntx = ceil_div(ow, dx);
                 Sm = (long)S * nty * ntx;
                 p->viewA = true; p->vA = PlaneView{fo, nty, ntx, dy, dx, 0, 0, oh, ow};
                 p->hA = imin(dy, oh); p->wA = imin(dx, ow);
-                p->viewB = true; p->vB = PlaneView{f, nty, ntx, dy, dx, 0, 0, h, w};
-                p->hB = imin(N, h); p->wB = imin(N, w);
+                p->viewB = true; p->vB = PlaneView{f, nty, ntx, dy, dx, -ph, -pw, h, w};
+                p->hB = imin(N, h + ph); p->wB = imin(N, w + pw);
             }
             p->planesA = Sm * fo; p->conjA = true;
             p->planesB = Sm * f;
@@ -259,10 +269,10 @@ static hipError_t contract_and_invert(fftconv_ctx *c, const PassPlan &p, const f
 
 static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB, float *out,
                     int S, int f, int fo, int h, int w, int kh, int kw, float scale, int accumulate,
-                    void *ws, size_t ws_bytes, int tile_n = -1) {
+                    void *ws, size_t ws_bytes, int tile_n = -1, int ph = 0, int pw = 0) {
     if (!c || !opA || !opB || !out) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p, tile_n);
+    int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw);
     if (rc != FFTCONV_OK) return rc;
     if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     float *AF = at(ws, p.offA), *BF = at(ws, p.offB), *CF = at(ws, p.offC);
@@ -382,6 +392,32 @@ int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, f
                            float scale, int accumulate, int tile_n, void *ws, size_t ws_bytes) {
     if (tile_n < 0) return FFTCONV_INVALID_ARG;
     return run_pass(hd, FFTCONV_ACCGRAD, gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, ws, ws_bytes, tile_n);
+}
+
+size_t fftconv_padded_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw,
+                                      int pad_h, int pad_w) {
+    PassPlan p;
+    if (make_plan(pass, S, f, fo, h, w, kh, kw, &p, -1, pad_h, pad_w) != FFTCONV_OK) return 0;
+    return p.total;
+}
+
+int fft_conv_fprop_padded(fftconv_handle hd, const float *x, const float *wt, float *y,
+                          int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                          void *ws, size_t ws_bytes) {
+    return run_pass(hd, FFTCONV_FPROP, x, wt, y, S, f, fo, h, w, kh, kw, 1.0f, 0, ws, ws_bytes, -1, pad_h, pad_w);
+}
+
+int fft_conv_bprop_padded(fftconv_handle hd, const float *gy, const float *wt, float *gx,
+                          int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                          void *ws, size_t ws_bytes) {
+    return run_pass(hd, FFTCONV_BPROP, gy, wt, gx, S, f, fo, h, w, kh, kw, 1.0f, 0, ws, ws_bytes, -1, pad_h, pad_w);
+}
+
+int fft_conv_accgrad_padded(fftconv_handle hd, const float *x, const float *gy, float *gw,
+                            int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                            float scale, int accumulate, void *ws, size_t ws_bytes) {
+    return run_pass(hd, FFTCONV_ACCGRAD, gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, ws, ws_bytes, -1,
+                    pad_h, pad_w);
 }
 
 static bool fft_size_ok(int n) { return n == 8 || n == 16 || n == 32 || n == 64 || n == 128; }
