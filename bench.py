@@ -231,6 +231,23 @@ def fft_sweep(hd, max_bytes=1 << 28, reps=3):
                 res[name] = {"ms": round(ms, 4), "GBps": round(byts / ms / 1e6, 1)}
             out[f"{dim}d_n{n}"] = res
             del x, X, y
+    # one size beyond the sweep of the benchmark definition: 1-D n = 256 (signals of 253)
+    n, ni = 256, 253
+    B = max_bytes // (4 * ni)
+    x = torch.randn((B, ni), device="cuda", dtype=torch.float32)
+    X = torch.empty((B, n // 2 + 1, 2), device="cuda")
+    y = torch.empty_like(x)
+    res = {}
+    for name, fn in (("r2c", lambda: hd.fft_r2c_1d(x, n, out=X)), ("c2r", lambda: hd.fft_c2r_1d(X, n, ni, out=y))):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        res[name] = {"ms": round(ms, 4), "GBps": round(B * (4 * ni + 8 * (n // 2 + 1)) / ms / 1e6, 1)}
+    out["1d_n256"] = res
     return out
 
 

@@ -135,7 +135,8 @@ int fft_conv_accgrad_padded(fftconv_handle hd, const float *x, const float *gy, 
 
 /*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
- * (Supplement, DFT definition); n in {8,16,32,64,128}.  Inputs shorter than n are
+ * (Supplement, DFT definition); n in {8,16,32,64,128}, and 256 for the 1-D calls (the
+ * sizes of Section 5.3).  Inputs shorter than n are
  * zero-padded implicitly while loading (the clipping of Section 5.1), no padded copy is
  * made.  Complex data are interleaved (re,im) fp32; only the Hermitian half
  * k = 0..n/2 along the innermost axis is stored (Table 1), in natural bin order.

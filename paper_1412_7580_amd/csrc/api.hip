@@ -421,10 +421,12 @@ int fft_conv_accgrad_padded(fftconv_handle hd, const float *x, const float *gy, 
 }
 
 static bool fft_size_ok(int n) { return n == 8 || n == 16 || n == 32 || n == 64 || n == 128; }
+// 1-D transforms go one size further (the range of Section 5.3 of the paper).
+static bool fft1d_size_ok(int n) { return fft_size_ok(n) || n == 256; }
 
 int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in, int n) {
     if (!hd || B < 0 || n_in <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;
-    if (!fft_size_ok(n)) return FFTCONV_UNSUPPORTED;
+    if (!fft1d_size_ok(n)) return FFTCONV_UNSUPPORTED;
     if (n_in > n) return FFTCONV_INVALID_ARG;
     hipError_t e = launch_fft1d_r2c(in, out, B, n_in, n, LaunchCtx{hd->stream, nullptr, nullptr});
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
@@ -432,7 +434,7 @@ int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in,
 
 int fft_c2r_1d(fftconv_handle hd, const float *in, float *out, long B, int n, int n_out) {
     if (!hd || B < 0 || n_out <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;
-    if (!fft_size_ok(n)) return FFTCONV_UNSUPPORTED;
+    if (!fft1d_size_ok(n)) return FFTCONV_UNSUPPORTED;
     if (n_out > n) return FFTCONV_INVALID_ARG;
     hipError_t e = launch_fft1d_c2r(in, out, B, n, n_out, LaunchCtx{hd->stream, nullptr, nullptr});
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);

@@ -1019,6 +1019,7 @@ hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n
         case 32: return run_fwd1d<32, 1, 256>(in, out, B, n_in, st);
         case 64: return run_fwd1d<32, 2, 128>(in, out, B, n_in, st);
         case 128: return run_fwd1d<32, 4, 128>(in, out, B, n_in, st);
+        case 256: return run_fwd1d<64, 4, 64>(in, out, B, n_in, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1047,6 +1048,7 @@ hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_ou
         case 32: return run_inv1d<32, 1, 256>(in, out, B, n_out, st);
         case 64: return run_inv1d<32, 2, 128>(in, out, B, n_out, st);
         case 128: return run_inv1d<32, 4, 128>(in, out, B, n_out, st);
+        case 256: return run_inv1d<64, 4, 64>(in, out, B, n_out, st);
         default: return hipErrorInvalidValue;
     }
 }
