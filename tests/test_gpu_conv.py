@@ -188,6 +188,25 @@ def test_reuse_at_c2(hd):
     assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
 
 
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_reuse_equals_separate_passes_at_full_size(hd, name):
+    """The two-call step at the full size of the larger configurations (the launch
+    configuration the benchmark times, with both backward contractions in one launch where
+    that applies): its results must be bit-identical to those of the three independent passes,
+    which the tests above check against the oracle -- same kernels, same operands, same order."""
+    import torch
+    cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k not in ("passes", "N")}
+    x, w, gy = synth.conv_inputs(seed=synth.CONV_SEEDS[name], **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
+    y = hd.fft_conv_fprop_save(dx, dw, saved)
+    gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    assert torch.equal(y, hd.fft_conv_fprop(dx, dw))
+    assert torch.equal(gx, hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"]))
+    assert torch.equal(gw, hd.fft_conv_accgrad(dx, dgy))
+
+
 def test_saved_buffer_too_small(hd, lib):
     import torch
     cfg = dict(S=2, f=3, fo=4, h=9, w=9, kh=3, kw=3)
