@@ -132,6 +132,18 @@ int fft_conv_bprop_padded(fftconv_handle hd, const float *gy, const float *wt, f
 int fft_conv_accgrad_padded(fftconv_handle hd, const float *x, const float *gy, float *gw,
                             int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
                             float scale, int accumulate, void *ws, size_t ws_bytes);
+/* The transform-reuse pair (see fft_conv_fprop_save / fft_conv_backward below) for a padded
+ * layer; the same padding must be given to all four functions. */
+size_t fftconv_saved_bytes_padded(int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w);
+size_t fftconv_backward_workspace_bytes_padded(int S, int f, int fo, int h, int w, int kh, int kw,
+                                               int pad_h, int pad_w);
+int fft_conv_fprop_save_padded(fftconv_handle hd, const float *x, const float *wt, float *y,
+                               int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                               void *saved, size_t saved_bytes, void *ws, size_t ws_bytes);
+int fft_conv_backward_padded(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                             int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                             float scale, int accumulate, const void *saved, size_t saved_bytes,
+                             void *ws, size_t ws_bytes);
 
 /*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)

@@ -23,6 +23,8 @@ SYMBOLS = [
     "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled",
     "fftconv_padded_workspace_bytes",
     "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
+    "fftconv_saved_bytes_padded", "fftconv_backward_workspace_bytes_padded",
+    "fft_conv_fprop_save_padded", "fft_conv_backward_padded",
 ]
 
 
@@ -76,6 +78,12 @@ def load_library():
     lib.fft_conv_fprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
     lib.fft_conv_bprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
     lib.fft_conv_accgrad_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [f, i, vp, sz]
+    lib.fftconv_saved_bytes_padded.argtypes = [i] * 9
+    lib.fftconv_saved_bytes_padded.restype = sz
+    lib.fftconv_backward_workspace_bytes_padded.argtypes = [i] * 9
+    lib.fftconv_backward_workspace_bytes_padded.restype = sz
+    lib.fft_conv_fprop_save_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz, vp, sz]
+    lib.fft_conv_backward_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [f, i, vp, sz, vp, sz]
     _lib = lib
     return lib
 
@@ -324,6 +332,48 @@ class Handle:
                                                  S, f, fo, h, w, kh, kw, int(pad_h), int(pad_w), float(scale),
                                                  1 if accumulate else 0, *self._ws(ws)), "fft_conv_accgrad_padded")
         return gw
+
+    def saved_bytes_padded(self, S, f, fo, h, w, kh, kw, pad_h, pad_w) -> int:
+        return int(self._lib.fftconv_saved_bytes_padded(S, f, fo, h, w, kh, kw, pad_h, pad_w))
+
+    def backward_workspace_bytes_padded(self, S, f, fo, h, w, kh, kw, pad_h, pad_w) -> int:
+        return int(self._lib.fftconv_backward_workspace_bytes_padded(S, f, fo, h, w, kh, kw, pad_h, pad_w))
+
+    def fft_conv_fprop_save_padded(self, x, wt, pad_h, pad_w, saved, y=None, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f:
+            raise FFTConvError("x and wt disagree on the number of input planes")
+        if y is None:
+            y = torch.empty((S, fo, h + 2 * pad_h - kh + 1, w + 2 * pad_w - kw + 1), device=x.device,
+                            dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop_save_padded(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
+                                                    S, f, fo, h, w, kh, kw, int(pad_h), int(pad_w),
+                                                    *self._ws(saved), *self._ws(ws)), "fft_conv_fprop_save_padded")
+        return y
+
+    def fft_conv_backward_padded(self, gy, saved, f, h, w, kh, kw, pad_h, pad_w, gx=None, gw=None,
+                                 want_gx=True, want_gw=True, scale=1.0, accumulate=False, ws=None):
+        import torch
+        S, fo, oh, ow = gy.shape
+        if oh != h + 2 * pad_h - kh + 1 or ow != w + 2 * pad_w - kw + 1:
+            raise FFTConvError("gy, (h, w, kh, kw) and the padding disagree")
+        if want_gx and gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        if want_gw and gw is None:
+            if accumulate:
+                raise FFTConvError("accumulate needs an existing gw")
+            gw = torch.empty((fo, f, kh, kw), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_backward_padded(self._h, _dev_f32(gy, "gy"),
+                                                  _dev_f32(gx, "gx") if want_gx else None,
+                                                  _dev_f32(gw, "gw") if want_gw else None,
+                                                  S, f, fo, h, w, kh, kw, int(pad_h), int(pad_w), float(scale),
+                                                  1 if accumulate else 0, *self._ws(saved), *self._ws(ws)),
+               "fft_conv_backward_padded")
+        return gx, gw
 
     @staticmethod
     def _ws(ws):

@@ -477,10 +477,18 @@ int fftconv_last_kernel_ms(fftconv_handle h, float *ms_out, int capacity, int *c
     return FFTCONV_OK;
 }
 
-size_t fftconv_saved_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
+static size_t saved_bytes_impl(int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw) {
     PassPlan p;
-    if (make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p) != FFTCONV_OK) return 0;
+    if (make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, -1, ph, pw) != FFTCONV_OK) return 0;
     return saved_plan(p).total;
+}
+
+size_t fftconv_saved_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
+    return saved_bytes_impl(S, f, fo, h, w, kh, kw, 0, 0);
+}
+
+size_t fftconv_saved_bytes_padded(int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w) {
+    return saved_bytes_impl(S, f, fo, h, w, kh, kw, pad_h, pad_w);
 }
 
 // Workspace of fft_conv_backward: [GYF for bprop | GYF for accGrad (tiled layers only: the two
@@ -501,19 +509,30 @@ static BackwardPlan backward_plan(const PassPlan &pb, const PassPlan &pa) {
     return b;
 }
 
-size_t fftconv_backward_workspace_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
+static size_t backward_workspace_impl(int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw) {
     PassPlan pb, pa;
-    if (make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb) != FFTCONV_OK) return 0;
-    if (make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa) != FFTCONV_OK) return 0;
+    if (make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, -1, ph, pw) != FFTCONV_OK) return 0;
+    if (make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, -1, ph, pw) != FFTCONV_OK) return 0;
     return backward_plan(pb, pa).total;
 }
 
-int fft_conv_fprop_save(fftconv_handle hd, const float *x, const float *wt, float *y,
-                        int S, int f, int fo, int h, int w, int kh, int kw,
-                        void *saved, size_t saved_bytes, void *ws, size_t ws_bytes) {
+size_t fftconv_backward_workspace_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
+    return backward_workspace_impl(S, f, fo, h, w, kh, kw, 0, 0);
+}
+
+size_t fftconv_backward_workspace_bytes_padded(int S, int f, int fo, int h, int w, int kh, int kw,
+                                               int pad_h, int pad_w) {
+    return backward_workspace_impl(S, f, fo, h, w, kh, kw, pad_h, pad_w);
+}
+
+}  // extern "C"
+
+static int fprop_save_impl(fftconv_handle hd, const float *x, const float *wt, float *y,
+                           int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw,
+                           void *saved, size_t saved_bytes, void *ws, size_t ws_bytes) {
     if (!hd || !x || !wt || !y || !saved) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
+    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, -1, ph, pw);
     if (rc != FFTCONV_OK) return rc;
     const SavedPlan sp = saved_plan(p);
     if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
@@ -527,16 +546,16 @@ int fft_conv_fprop_save(fftconv_handle hd, const float *x, const float *wt, floa
     return FFTCONV_OK;
 }
 
-int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
-                      int S, int f, int fo, int h, int w, int kh, int kw,
-                      float scale, int accumulate, const void *saved, size_t saved_bytes,
-                      void *ws, size_t ws_bytes) {
+static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                         int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw,
+                         float scale, int accumulate, const void *saved, size_t saved_bytes,
+                         void *ws, size_t ws_bytes) {
     if (!hd || !gy || !saved || (!gx && !gw)) return FFTCONV_INVALID_ARG;
     PassPlan pf, pb, pa;
-    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &pf);
+    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &pf, -1, ph, pw);
     if (rc != FFTCONV_OK) return rc;
-    (void)make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb);
-    (void)make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa);
+    (void)make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, -1, ph, pw);
+    (void)make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, -1, ph, pw);
     const SavedPlan sp = saved_plan(pf);
     if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
     const BackwardPlan bp = backward_plan(pb, pa);
@@ -572,6 +591,36 @@ int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
     if (gx && (e = contract_and_invert(hd, pb, GYF, WF, GXF, gx, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
     if (gw && (e = contract_and_invert(hd, pa, GYFa, XF, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
     return FFTCONV_OK;
+}
+
+extern "C" {
+
+int fft_conv_fprop_save(fftconv_handle hd, const float *x, const float *wt, float *y,
+                        int S, int f, int fo, int h, int w, int kh, int kw,
+                        void *saved, size_t saved_bytes, void *ws, size_t ws_bytes) {
+    return fprop_save_impl(hd, x, wt, y, S, f, fo, h, w, kh, kw, 0, 0, saved, saved_bytes, ws, ws_bytes);
+}
+
+int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                      int S, int f, int fo, int h, int w, int kh, int kw,
+                      float scale, int accumulate, const void *saved, size_t saved_bytes,
+                      void *ws, size_t ws_bytes) {
+    return backward_impl(hd, gy, gx, gw, S, f, fo, h, w, kh, kw, 0, 0, scale, accumulate, saved, saved_bytes, ws,
+                         ws_bytes);
+}
+
+int fft_conv_fprop_save_padded(fftconv_handle hd, const float *x, const float *wt, float *y,
+                               int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                               void *saved, size_t saved_bytes, void *ws, size_t ws_bytes) {
+    return fprop_save_impl(hd, x, wt, y, S, f, fo, h, w, kh, kw, pad_h, pad_w, saved, saved_bytes, ws, ws_bytes);
+}
+
+int fft_conv_backward_padded(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                             int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                             float scale, int accumulate, const void *saved, size_t saved_bytes,
+                             void *ws, size_t ws_bytes) {
+    return backward_impl(hd, gy, gx, gw, S, f, fo, h, w, kh, kw, pad_h, pad_w, scale, accumulate, saved,
+                         saved_bytes, ws, ws_bytes);
 }
 
 }  // extern "C"

@@ -68,6 +68,27 @@ def test_padded_passes(hd, cfg, ph, pw):
     assert e <= TOL, ("accgrad", e)
 
 
+@pytest.mark.parametrize("cfg,ph,pw", [PADDED[0], PADDED[3], PADDED[6], PADDED[7]],
+                         ids=[IDS[0], IDS[3], IDS[6], IDS[7]])
+def test_padded_reuse_pair(hd, cfg, ph, pw):
+    """fprop_save + backward of a padded layer give, bit for bit, what the three padded passes
+    give (which the test above checks against the oracle)."""
+    import torch
+    h, w = cfg["h"], cfg["w"]
+    big = dict(cfg, h=h + 2 * ph, w=w + 2 * pw)
+    xp, wt, gy = synth.conv_inputs(seed=402, **big)
+    x = np.ascontiguousarray(xp[:, :, ph:ph + h, pw:pw + w])
+    dx, dw, dgy = _dev(x), _dev(wt), _dev(gy)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], h, w, cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes_padded(*dims, ph, pw) // 4, device="cuda", dtype=torch.float32)
+    assert saved.numel() > 0 and hd.backward_workspace_bytes_padded(*dims, ph, pw) > 0
+    y = hd.fft_conv_fprop_save_padded(dx, dw, ph, pw, saved)
+    gx, gw = hd.fft_conv_backward_padded(dgy, saved, cfg["f"], h, w, cfg["kh"], cfg["kw"], ph, pw)
+    assert torch.equal(y, hd.fft_conv_fprop_padded(dx, dw, ph, pw))
+    assert torch.equal(gx, hd.fft_conv_bprop_padded(dgy, dw, h, w, ph, pw))
+    assert torch.equal(gw, hd.fft_conv_accgrad_padded(dx, dgy, ph, pw))
+
+
 def test_zero_padding_is_the_ordinary_pass(hd):
     cfg = dict(S=2, f=3, fo=2, h=14, w=14, kh=3, kw=3)
     x, wt, gy = synth.conv_inputs(seed=401, **cfg)
