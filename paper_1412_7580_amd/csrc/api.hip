@@ -569,11 +569,16 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
         if ((e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
     } else {
         // gy cut twice: overlapping windows for bprop, disjoint tiles for accGrad
+        if (gx && gw && pb.N <= 32) {   // small bases: both in one launch, as for the two operands of a pass
+            FwdOperand ops[2] = {{gy, GYF, pb.planesA, pb.hA, pb.wA, &pb.vA}, {gy, GYFa, pa.planesA, pa.hA, pa.wA, &pa.vA}};
+            if ((e = launch_fft2d_r2c_multi(ops, 2, pb.N, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+        } else {
         LaunchCtx lc = next_ctx(hd);
         if (gx && (e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true,
                                         LaunchCtx{lc.stream, lc.start, gw ? nullptr : lc.stop}, &pb.vA)) != hipSuccess) return hip_fail(hd, e);
         if (gw && (e = launch_fft2d_r2c(gy, GYFa, pa.planesA, pa.hA, pa.wA, pa.N, true,
                                         LaunchCtx{lc.stream, gx ? nullptr : lc.start, lc.stop}, &pa.vA)) != hipSuccess) return hip_fail(hd, e);
+        }
     }
     // bprop: GX = GY . W ; accGrad: GW = conj(GY) . X  (operand A of both plans is GYF)
     if (gx && gw) {
