@@ -251,6 +251,38 @@ def fft_sweep(hd, max_bytes=1 << 28, reps=3):
     return out
 
 
+def graph_replay_c1(hd, reps=200):
+    """The smallest configuration is launch-bound (three kernels of a few microseconds): time
+    its fprop eagerly and as a captured HIP graph (caller-supplied workspace, so the call
+    allocates nothing)."""
+    import torch
+    import paper_1412_7580_amd as pkg
+    from paper_1412_7580_amd import synth
+    cfg = {k: v for k, v in synth.CONV_CONFIGS["C1"].items() if k != "passes"}
+    t, _ = device_tensors(cfg, synth.CONV_SEEDS["C1"])
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    ws = torch.empty(hd.workspace_bytes(pkg.FPROP, *dims) // 4, device="cuda", dtype=torch.float32)
+
+    def call():
+        hd.fft_conv_fprop(t["x"], t["w"], y=t["y"], ws=ws)
+
+    def timed(fn):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+    eager = timed(call)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    replay = timed(graph.replay)
+    return {"eager_us_per_fprop": round(eager * 1e6, 2), "graph_replay_us_per_fprop": round(replay * 1e6, 2)}
+
+
 def tiled_layers(hd, reps=10):
     """Tiling (Section 6 of the paper) on two layers: an image beyond the largest basis, which
     the ordinary entry points tile by themselves, and a mid-size layer run untiled and tiled.
@@ -479,6 +511,7 @@ def main():
             extra[other] = ent
         del t
         torch.cuda.empty_cache()
+        extra["C1_fprop_hip_graph"] = graph_replay_c1(hd)
         extra["tiled_layers"] = tiled_layers(hd)
         torch.cuda.empty_cache()
         extra["fft_sweep_256MiB"] = fft_sweep(hd)

@@ -1,0 +1,64 @@
+"""The passes can be captured into a HIP graph and replayed (GPU, C ABI).
+
+With a caller-supplied workspace a call allocates nothing, records no memset and touches no
+host state that a replay would miss, so a captured sequence of calls must give, on every
+replay, exactly what the same calls give eagerly -- also after the inputs changed in place and
+with eager work and synchronisation between the replays."""
+import numpy as np
+import pytest
+
+from paper_1412_7580_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hd(lib):
+    h = lib.Handle(0)
+    yield h
+    h.close()
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+@pytest.mark.parametrize("cfg", [dict(S=16, f=16, fo=16, h=13, w=13, kh=3, kw=3),      # smallest benchmark layer
+                                 dict(S=2, f=4, fo=4, h=70, w=70, kh=5, kw=5)],        # a layer the library tiles
+                         ids=["13x13", "70x70_tiled"])
+def test_graph_replay_equals_eager(hd, lib, cfg):
+    import torch
+    x, w, gy = synth.conv_inputs(seed=600, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
+    ws1 = torch.empty(hd.workspace_bytes(lib.FPROP, *dims) // 4, device="cuda", dtype=torch.float32)
+    ws2 = torch.empty(hd.backward_workspace_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
+    y = torch.empty((cfg["S"], cfg["fo"], cfg["h"] - cfg["kh"] + 1, cfg["w"] - cfg["kw"] + 1), device="cuda")
+    gx, gw = torch.empty_like(dx), torch.empty_like(dw)
+    args = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+
+    def step():
+        hd.fft_conv_fprop_save(dx, dw, saved, y=y, ws=ws1)
+        hd.fft_conv_backward(dgy, saved, *args, gx=gx, gw=gw, ws=ws2)
+
+    def eager():
+        step()
+        torch.cuda.synchronize()
+        return y.clone(), gx.clone(), gw.clone()
+
+    ref = eager()                       # also the warm-up: kernel attributes are set here
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        if rep == 2:                    # new inputs, in place: replays must follow them
+            dx.mul_(0.5); dgy.add_(0.25)
+            ref = eager()
+        y.zero_(); gx.zero_(); gw.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref[0]) and torch.equal(gx, ref[1]) and torch.equal(gw, ref[2]), rep
+        _ = (dx * 2).sum().item()       # eager work and a synchronisation between replays
