@@ -265,6 +265,130 @@ __global__ void __launch_bounds__(64 * WGM * WGN, MINB) cgemm_bins_kernel(GemmPa
     cgemm_bins_body<WGM, WGN, FM, FN, TK, AKF, BKF, VEC, PD>(prm, blockIdx.x);
 }
 
+// One 32x32 quadrant (quad = 2 * row half + column half) of the 64x64 tile that workgroup
+// number vwg of prm's grid would compute, with the reduction split over the four waves: wave w
+// takes k-steps w and w + 4 of every K tile, the four partial tiles meet in LDS and each wave
+// sums and stores a quarter of the rows.  A quarter of the serial MFMA chain per wave, and PD
+// tiles of gathers in flight from the start: this is for workgroups that run when most of
+// the chip has drained (see cgemm_tail_kernel).
+template <int TK, bool AKF, bool BKF, int PD>
+__device__ __forceinline__ void cgemm_quadrant_body(const GemmParams &prm, const unsigned vwg, const int quad) {
+    constexpr int NT = 256, TQ = 32, SQ = TQ + 2;
+    constexpr int QBUF = 2 * TK * SQ;
+    static_assert(TK == 16, "two k-step pairs per wave and K tile");
+    extern __shared__ float smem[];
+    float *As = smem;                 // [2 buffers][2 comps][TK][SQ]
+    float *Bs = smem + 2 * QBUF;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tiles = prm.tiles_m * prm.tiles_n;
+    const int xcd = vwg % kXcds, slot = vwg / kXcds;
+    const int bins_per_xcd = prm.bins / kXcds;
+    const int bin = xcd * bins_per_xcd + slot / tiles;
+    const int tile = slot % tiles;
+    const int m0 = (tile / prm.tiles_n) * 64 + (quad >> 1) * TQ, n0 = (tile % prm.tiles_n) * 64 + (quad & 1) * TQ;
+    const int M = prm.M, N = prm.N, K = prm.K;
+    if (m0 >= M || n0 >= N) return;   // uniform over the workgroup
+
+    floatx16 p1, p2, p3;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { p1[v] = 0.f; p2[v] = 0.f; p3[v] = 0.f; }
+
+    TileLoader<TQ, TK, SQ, AKF, true, NT> la[PD];
+    TileLoader<TQ, TK, SQ, BKF, true, NT> lb[PD];
+    const int nkt = (K + TK - 1) / TK;
+    auto issue = [&](auto &xa, auto &xb, int kt) {
+        xa.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, kt * TK, M, K, tid);
+        xb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, kt * TK, N, K, tid);
+    };
+    static_for_gemm<0, PD>([&](auto dd) {
+        constexpr int d = decltype(dd)::value;
+        if (d < nkt) issue(la[d], lb[d], d);
+    });
+    la[0].store(As, tid);
+    lb[0].store(Bs, tid);
+    if (PD < nkt) issue(la[0], lb[0], PD);
+    __syncthreads();
+
+    const int lrow = lane & 31, lk = lane >> 5;
+    auto compute = [&](int cur) {
+        const float *a0 = As + cur * QBUF + lrow, *b0 = Bs + cur * QBUF + lrow;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = 2 * (wave + 4 * h) + lk;
+            const float a_re = a0[k * SQ], a_im = flip(a0[TK * SQ + k * SQ], prm.a_sign);
+            const float b_re = b0[k * SQ], b_im = flip(b0[TK * SQ + k * SQ], prm.b_sign);
+            p1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re, b_re, p1, 0, 0, 0);
+            p2 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_im, b_im, p2, 0, 0, 0);
+            p3 = __builtin_amdgcn_mfma_f32_32x32x2f32(a_re + a_im, b_re + b_im, p3, 0, 0, 0);
+        }
+    };
+    for (int kt0 = 0; kt0 < nkt; kt0 += PD) {
+        static_for_gemm<0, PD>([&](auto dd) {
+            constexpr int d = decltype(dd)::value;
+            constexpr int dn = (d + 1) % PD;
+            const int kt = kt0 + d;
+            if (kt < nkt) {
+                const int cur = kt & 1;
+                if (kt + 1 < nkt) {
+                    // buffer cur ^ 1 was last read in iteration kt - 1, which every wave has left
+                    la[dn].store(As + (cur ^ 1) * QBUF, tid);
+                    lb[dn].store(Bs + (cur ^ 1) * QBUF, tid);
+                    if (kt + 1 + PD < nkt) issue(la[dn], lb[dn], kt + 1 + PD);
+                }
+                compute(cur);
+                if (kt + 1 < nkt) __syncthreads();
+            }
+        });
+    }
+
+    // Partial tiles [wave][component][register][lane] -> LDS; wave w then owns registers
+    // 4w .. 4w+3, i.e. rows 8w + 4*(lane/32) + 0..3 of the quadrant (D layout of the MFMA).
+    __syncthreads();                  // every wave is done with the operand tiles
+    float *red = smem;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        red[((wave * 2 + 0) * 16 + v) * 64 + lane] = p1[v] - p2[v];
+        red[((wave * 2 + 1) * 16 + v) * 64 + lane] = p3[v] - p1[v] - p2[v];
+    }
+    __syncthreads();
+    const size_t cim = (size_t)1 << prm.layC.tsh;
+    const int n = n0 + lrow;
+#pragma unroll
+    for (int vv = 0; vv < 4; ++vv) {
+        const int v = wave * 4 + vv;
+        float cr = 0.f, ci = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            cr += red[((w * 2 + 0) * 16 + v) * 64 + lane];
+            ci += red[((w * 2 + 1) * 16 + v) * 64 + lane];
+        }
+        const int m = m0 + 8 * wave + 4 * lk + vv;
+        if (m < M && n < N) {
+            const size_t idx = prm.layC.index(m * prm.c_rs + n * prm.c_cs, bin, 0);
+            prm.C[idx] = cr;
+            prm.C[idx + cim] = ci;
+        }
+    }
+}
+
+// The 64x64 contraction with a split tail.  A grid that is a little more than a whole number
+// of rounds (resident workgroups: four per compute unit) leaves its last few workgroups to
+// run alone, each at the latency of its own loads and MFMA chain, while the rest of the chip
+// idles (measured on the 27x27 layer: 64 of 1088 workgroups, 11 of 28 us).  Those last tiles are
+// cut into quadrants: workgroups [split_from, grid) are quadrant workgroups, four per tile,
+// numbered so that a tile's quadrants run on the XCD that its bin's other tiles ran on.
+template <bool AKF, bool BKF>
+__global__ void __launch_bounds__(256, 3) cgemm_tail_kernel(GemmParams prm) {
+    if (blockIdx.x < prm.split_from) {
+        cgemm_bins_body<2, 2, 1, 1, 16, AKF, BKF, true, 1>(prm, blockIdx.x);
+    } else {
+        const unsigned r = blockIdx.x - prm.split_from;
+        const unsigned x = r % kXcds, u = r / kXcds;
+        cgemm_quadrant_body<16, AKF, BKF, 2>(prm, prm.split_from + kXcds * (u / 4) + x, (int)(u % 4));
+    }
+}
+
 // Two independent contractions in one launch (the two backward passes of a layer share
 // their first operand and neither waits for the other): workgroups [0, n1) work on p1, the
 // rest on p2.  One grid means one ramp-up and one tail instead of two, and the second
@@ -336,6 +460,7 @@ static hipError_t prepare(const GemmOperand &A, const GemmOperand &B, float *C, 
     prm.c_rs = C_rs; prm.c_cs = C_cs;
     prm.M = M; prm.N = N; prm.K = K; prm.bins = bins;
     prm.tiles_m = prm.tiles_n = 0;
+    prm.split_from = 0xffffffffu;
     prm.a_sign = A.conj ? 0x80000000u : 0u;
     prm.b_sign = B.conj ? 0x80000000u : 0u;
     const bool akf = (A.cs == 1), bkf = (B.rs == 1);
@@ -357,10 +482,46 @@ static hipError_t prepare(const GemmOperand &A, const GemmOperand &B, float *C, 
     return hipSuccess;
 }
 
+// Workgroups of the 64x64 kernel that are resident at once (four per compute unit: LDS).
+static long resident_workgroups() {
+    static long slots = 0;
+    if (!slots) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        slots = 4L * cus;
+    }
+    return slots;
+}
+
+template <bool AKF, bool BKF>
+static hipError_t run_tail(GemmParams prm, long full, long rem, LaunchCtx st) {
+    prm.split_from = (unsigned)full;
+    const size_t lds = (size_t)(2 * 2 * 16 * 66 + 2 * 2 * 16 * 66) * sizeof(float);   // >= the quadrant's 32 KB
+    auto k = cgemm_tail_kernel<AKF, BKF>;
+    if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
+    launch_kernel(k, dim3((unsigned)(full + 4 * rem)), dim3(256), lds, st, prm);
+    return hipGetLastError();
+}
+
 static hipError_t launch_prepared(const Prepared &q, LaunchCtx st) {
     const GemmParams &prm = q.prm;
     if (q.bingroup) return launch_cgemm_bingroup(prm, q.akf, q.bkf, st);
     const int shape = pick_tile();
+    if (q.vec && shape == 3 && !getenv("FFTCONV_GEMM_TILE") && !getenv("FFTCONV_GEMM_NO_TAIL")) {
+        // a short last round (at most a quarter of the resident workgroups): split its tiles
+        GemmParams p2 = prm;
+        p2.tiles_m = (p2.M + 63) / 64; p2.tiles_n = (p2.N + 63) / 64;
+        const long total = (long)p2.bins * p2.tiles_m * p2.tiles_n, slots = resident_workgroups();
+        const long rem = total % slots, full = total - rem;
+        if (full > 0 && rem > 0 && 4 * rem <= slots && rem % kXcds == 0 && full % kXcds == 0) {
+            if (q.akf && q.bkf) return run_tail<true, true>(p2, full, rem, st);
+            if (q.akf && !q.bkf) return run_tail<true, false>(p2, full, rem, st);
+            if (!q.akf && !q.bkf) return run_tail<false, false>(p2, full, rem, st);
+            return run_tail<false, true>(p2, full, rem, st);
+        }
+    }
     if (q.vec) {
         if (q.akf && q.bkf) return dispatch_tile<true, true, true>(shape, prm, st);
         if (q.akf && !q.bkf) return dispatch_tile<true, false, true>(shape, prm, st);

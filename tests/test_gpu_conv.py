@@ -60,6 +60,9 @@ SMALL = [
     dict(S=3, f=2, fo=3, h=64, w=64, kh=31, kw=31),
     dict(S=2, f=2, fo=2, h=100, w=128, kh=9, kw=11),
     dict(S=70, f=40, fo=72, h=9, w=9, kh=3, kw=3),
+    # fprop contraction of 144 bins x (4 x 2) tiles = 1152 workgroups: a short last round, whose
+    # tiles are cut into quadrants (ragged ones, and quadrants wholly outside the matrix)
+    dict(S=200, f=20, fo=72, h=13, w=13, kh=3, kw=3),
 ]
 
 
@@ -192,8 +195,10 @@ def test_reuse_at_c2(hd):
 def test_reuse_equals_separate_passes_at_full_size(hd, name):
     """The two-call step at the full size of the larger configurations (the launch
     configuration the benchmark times, with both backward contractions in one launch where
-    that applies): its results must be bit-identical to those of the three independent passes,
-    which the tests above check against the oracle -- same kernels, same operands, same order."""
+    that applies) against the three independent passes, which the tests above check against
+    the oracle.  Same transforms and the same products; only the order in which a contraction
+    sums over k may differ (a lone contraction may split the tiles of a short last round of
+    workgroups over its waves), so the results agree to rounding, far inside the 1e-4 bound."""
     import torch
     cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k not in ("passes", "N")}
     x, w, gy = synth.conv_inputs(seed=synth.CONV_SEEDS[name], **cfg)
@@ -202,9 +207,12 @@ def test_reuse_equals_separate_passes_at_full_size(hd, name):
     saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
     y = hd.fft_conv_fprop_save(dx, dw, saved)
     gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
-    assert torch.equal(y, hd.fft_conv_fprop(dx, dw))
-    assert torch.equal(gx, hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"]))
-    assert torch.equal(gw, hd.fft_conv_accgrad(dx, dgy))
+
+    def close(a, b):
+        return float((a - b).abs().max()) <= 2e-6 * float(b.abs().max())
+    assert close(y, hd.fft_conv_fprop(dx, dw))
+    assert close(gx, hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"]))
+    assert close(gw, hd.fft_conv_accgrad(dx, dgy))
 
 
 def test_saved_buffer_too_small(hd, lib):
