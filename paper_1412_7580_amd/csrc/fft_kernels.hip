@@ -285,7 +285,9 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
     const int np = left < T ? (int)left : T;
 
     // ---- stage the contiguous block of np planes into LDS (coalesced reads)
-    if (prm.tiled) {
+    bool windows = false;
+    if constexpr (CONV) windows = prm.tiled != 0;   // only the plane-tiled layout is used with views
+    if (windows) {
         OriginTable<T> tab(smem + prm.info_off);
         tab.fill(prm.view, p0, np, tid);
         if (prm.vecw == 4)
