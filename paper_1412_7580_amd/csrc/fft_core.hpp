@@ -118,22 +118,26 @@ __device__ __forceinline__ float quad_dpp(float v) {
 __device__ __forceinline__ float lane_xor1(float v) { return quad_dpp<0xB1>(v); }   // [1,0,3,2]
 __device__ __forceinline__ float lane_xor2(float v) { return quad_dpp<0x4E>(v); }   // [2,3,0,1]
 __device__ __forceinline__ float lane_xor3(float v) { return quad_dpp<0x1B>(v); }   // [3,2,1,0]
+// Lane ^ 7 of the same group of eight: DPP row_half_mirror; lane ^ 4 = (lane ^ 7) ^ 3.
+__device__ __forceinline__ float lane_xor7(float v) { return quad_dpp<0x141>(v); }
+__device__ __forceinline__ float lane_xor4(float v) { return lane_xor3(lane_xor7(v)); }
 
 // Block of output bins held by lane g after fft_group: lane g holds X[k + L*group_block(g)].
 template <int G>
 __device__ __forceinline__ int group_block(int g) {
     if constexpr (G == 4) return ((g & 1) << 1) | (g >> 1);
+    else if constexpr (G == 8) return ((g & 1) << 2) | (g & 2) | (g >> 2);
     else return g;
 }
 
-// N = L*G point FFT over G adjacent lanes (G = 1, 2 or 4).  On entry lane g holds x[g + G*m]
+// N = L*G point FFT over G adjacent lanes (G = 1, 2, 4 or 8).  On entry lane g holds x[g + G*m]
 // in register m; on exit lane g holds X[k + L*group_block<G>(g)] in register k.  All G lanes
 // of a group must be active together.  The cross-lane part is one (G = 2) or two (G = 4)
 // radix-2 decimation-in-time steps: the upper lane of each pair multiplies by the step's
 // twiddle, the pair swaps values through DPP and forms sum / difference.
 template <int L, int G, int DIR>
 __device__ __forceinline__ void fft_group(float (&re)[L], float (&im)[L], int g) {
-    static_assert(G == 1 || G == 2 || G == 4, "one lane, a lane pair or a lane quad per line");
+    static_assert(G == 1 || G == 2 || G == 4 || G == 8, "one, two, four or eight lanes per line");
     fft_leaf<L, DIR>(re, im);
     if constexpr (G == 2) {
         const float sgn = g ? -1.0f : 1.0f;
@@ -170,6 +174,41 @@ __device__ __forceinline__ void fft_group(float (&re)[L], float (&im)[L], int g)
             re[k] = lane_xor1(ur) + s2 * ur;
             im[k] = lane_xor1(ui) + s2 * ui;
         });
+    } else if constexpr (G == 8) {
+        // Three steps, pairing lanes g ^ 4, g ^ 2, g ^ 1.  With g = 4u + 2v + o: step 1 joins
+        // the stride-8 sequences g and g + 4 (twiddle w_2L^k on u = 1), step 2 the stride-4
+        // sequences (twiddle w_4L^(k + L u) on v = 1), step 3 the two stride-2 sequences
+        // (twiddle w_8L^(k + L u + 2L v) on o = 1); each lane keeps the sum (bit clear) or the
+        // difference (bit set), so lane g ends with block u + 2v + 4o.
+        const bool u = (g & 4) != 0, v = (g & 2) != 0, o = (g & 1) != 0;
+        const float s1 = u ? -1.0f : 1.0f, s2 = v ? -1.0f : 1.0f, s3 = o ? -1.0f : 1.0f;
+        static_for<0, L>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            constexpr cplx_d w1 = unit_root(DIR * k, 2 * L);
+            constexpr float c1 = (float)w1.re, d1 = (float)w1.im;
+            const float w1r = u ? c1 : 1.0f, w1i = u ? d1 : 0.0f;
+            const float tr = w1r * re[k] - w1i * im[k];
+            const float ti = w1r * im[k] + w1i * re[k];
+            const float ar = lane_xor4(tr) + s1 * tr;
+            const float ai = lane_xor4(ti) + s1 * ti;
+            constexpr cplx_d w20 = unit_root(DIR * k, 4 * L), w21 = unit_root(DIR * (k + L), 4 * L);
+            constexpr float c20 = (float)w20.re, d20 = (float)w20.im, c21 = (float)w21.re, d21 = (float)w21.im;
+            const float w2r = v ? (u ? c21 : c20) : 1.0f, w2i = v ? (u ? d21 : d20) : 0.0f;
+            const float br = w2r * ar - w2i * ai;
+            const float bi = w2r * ai + w2i * ar;
+            const float cr = lane_xor2(br) + s2 * br;
+            const float ci = lane_xor2(bi) + s2 * bi;
+            constexpr cplx_d w30 = unit_root(DIR * k, 8 * L), w31 = unit_root(DIR * (k + L), 8 * L),
+                             w32 = unit_root(DIR * (k + 2 * L), 8 * L), w33 = unit_root(DIR * (k + 3 * L), 8 * L);
+            constexpr float c30 = (float)w30.re, d30 = (float)w30.im, c31 = (float)w31.re, d31 = (float)w31.im,
+                            c32 = (float)w32.re, d32 = (float)w32.im, c33 = (float)w33.re, d33 = (float)w33.im;
+            const float w3r = o ? (v ? (u ? c33 : c32) : (u ? c31 : c30)) : 1.0f;
+            const float w3i = o ? (v ? (u ? d33 : d32) : (u ? d31 : d30)) : 0.0f;
+            const float er = w3r * cr - w3i * ci;
+            const float ei = w3r * ci + w3i * cr;
+            re[k] = lane_xor1(er) + s3 * er;
+            im[k] = lane_xor1(ei) + s3 * ei;
+        });
     }
 }
 
@@ -181,7 +220,14 @@ template <int L, int G> struct SplitRegs { static constexpr int A = (G == 1) ? L
 template <int L, int G>
 __device__ __forceinline__ int split_slot(int g, int k) {
     if constexpr (G == 2) return (g && k) ? L - k : k;
-    else {
+    else if constexpr (G == 8) {
+        // even lanes hold bins k + L b of the first line (b = group_block(g) < 4); odd lanes hold
+        // bin N - (k + L b) of the second line (b >= 4), the Nyquist bin packed into slot 0
+        const int b = group_block<8>(g);
+        if (!(g & 1)) return k + L * b;
+        if (k) return L * (7 - b) + L - k;
+        return b == 4 ? 0 : L * (8 - b);
+    } else {
         switch (g) {
             case 0: return k;
             case 2: return L + k;
@@ -222,19 +268,31 @@ __device__ __forceinline__ void split_two_real(const float (&re)[L], const float
             if constexpr (G == 2) {
                 are[0] = odd ? o0i : re[0];
                 aim[0] = odd ? im[0] : o0r;
-            } else {
+            } else if constexpr (G == 4) {
                 const float a_r = 0.5f * (re[0] + o0r), a_i = 0.5f * (im[0] - o0i);
                 const float b_r = 0.5f * (o0i + im[0]), b_i = 0.5f * (re[0] - o0r);
                 const bool up = (g >> 1) != 0;
                 are[0] = up ? (odd ? b_r : a_r) : (odd ? o0i : re[0]);
                 aim[0] = up ? (odd ? b_i : a_i) : (odd ? im[0] : o0r);
+            } else {
+                // G = 8: bin L b pairs with bin L (8 - b): lanes 0,1 hold bins 0 and N/2, lanes 2,3
+                // are neighbours, lanes 4..7 pair up as (4,7) and (5,6)
+                const bool hi = (g & 4) != 0;
+                const float p3r = lane_xor3(re[0]), p3i = lane_xor3(im[0]);
+                const float pr = hi ? p3r : o0r, pi = hi ? p3i : o0i;
+                const float a_r = 0.5f * (re[0] + pr), a_i = 0.5f * (im[0] - pi);
+                const float b_r = 0.5f * (pi + im[0]), b_i = 0.5f * (re[0] - pr);
+                const bool first = g < 2;
+                are[0] = first ? (odd ? o0i : re[0]) : (odd ? b_r : a_r);
+                aim[0] = first ? (odd ? im[0] : o0r) : (odd ? b_i : a_i);
             }
         }
         static_for<1, L>([&](auto kk) {
             constexpr int k = decltype(kk)::value;
             float orr, oi;
             if constexpr (G == 2) { orr = lane_xor1(re[L - k]); oi = lane_xor1(im[L - k]); }
-            else { orr = lane_xor3(re[L - k]); oi = lane_xor3(im[L - k]); }
+            else if constexpr (G == 4) { orr = lane_xor3(re[L - k]); oi = lane_xor3(im[L - k]); }
+            else { orr = lane_xor7(re[L - k]); oi = lane_xor7(im[L - k]); }
             const float a_r = 0.5f * (re[k] + orr), a_i = 0.5f * (im[k] - oi);
             const float b_r = 0.5f * (oi + im[k]), b_i = 0.5f * (re[k] - orr);
             are[k] = odd ? b_r : a_r;

@@ -910,7 +910,7 @@ hipError_t launch_fft2d_r2c_multi(const FwdOperand *ops, int nops, int N, Launch
         case 16: return run_fwd2d_multi<16, 1, 32>(ops, nops, st);
         case 32: return run_fwd2d_multi<32, 1, 16>(ops, nops, st);
         case 64: return run_fwd2d_multi<32, 2, 4>(ops, nops, st);
-        case 128: return run_fwd2d_multi<32, 4, 1>(ops, nops, st);
+        case 128: return run_fwd2d_multi<16, 8, 1>(ops, nops, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -924,7 +924,7 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
         case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
         case 32: return run_fwd2d<32, 1, 16>(in, out, planes, h_in, w_in, conv, st, view);
         case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st, view);   // (64,1): 25 % slower, (16,4): 5 % slower
-        case 128: return run_fwd2d<32, 4, 1>(in, out, planes, h_in, w_in, conv, st, view);
+        case 128: return run_fwd2d<16, 8, 1>(in, out, planes, h_in, w_in, conv, st, view);
         default: return hipErrorInvalidValue;
     }
 }
@@ -990,7 +990,7 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
         // the inverse gains from more lanes per line (fewer registers, shorter serial chains):
         // (16,4) measured 15..25 % faster than (32,2) here, (16,2) 20 % faster than (32,1) at 32
         case 64: return run_inv2d<16, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
-        case 128: return run_inv2d<32, 4, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 128: return run_inv2d<16, 8, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1013,15 +1013,18 @@ static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, Launc
     return hipGetLastError();
 }
 
+// Lanes per line of the 1-D kernels: more lanes with shorter register FFTs measured faster at
+// every size (fewer registers per lane, more loads in flight), e.g. n = 64: (8,8) 5.3 TB/s against
+// (32,2) 4.8; n = 256: (32,8) 4.2 against (64,4) 2.7; (2,4) at n = 8 and (4,8) at n = 32 lost.
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st) {
     if (B <= 0) return hipSuccess;
     switch (n) {
-        case 8: return run_fwd1d<8, 1, 512>(in, out, B, n_in, st);
-        case 16: return run_fwd1d<16, 1, 512>(in, out, B, n_in, st);
-        case 32: return run_fwd1d<32, 1, 256>(in, out, B, n_in, st);
-        case 64: return run_fwd1d<32, 2, 128>(in, out, B, n_in, st);
-        case 128: return run_fwd1d<32, 4, 128>(in, out, B, n_in, st);
-        case 256: return run_fwd1d<64, 4, 64>(in, out, B, n_in, st);
+        case 8: return run_fwd1d<4, 2, 512>(in, out, B, n_in, st);
+        case 16: return run_fwd1d<4, 4, 512>(in, out, B, n_in, st);
+        case 32: return run_fwd1d<8, 4, 256>(in, out, B, n_in, st);
+        case 64: return run_fwd1d<8, 8, 128>(in, out, B, n_in, st);
+        case 128: return run_fwd1d<16, 8, 128>(in, out, B, n_in, st);
+        case 256: return run_fwd1d<32, 8, 64>(in, out, B, n_in, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1045,12 +1048,12 @@ static hipError_t run_inv1d(const float *in, float *out, long B, int n_out, Laun
 hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st) {
     if (B <= 0) return hipSuccess;
     switch (n) {
-        case 8: return run_inv1d<8, 1, 512>(in, out, B, n_out, st);
-        case 16: return run_inv1d<16, 1, 512>(in, out, B, n_out, st);
-        case 32: return run_inv1d<32, 1, 256>(in, out, B, n_out, st);
-        case 64: return run_inv1d<32, 2, 128>(in, out, B, n_out, st);
-        case 128: return run_inv1d<32, 4, 128>(in, out, B, n_out, st);
-        case 256: return run_inv1d<64, 4, 64>(in, out, B, n_out, st);
+        case 8: return run_inv1d<4, 2, 512>(in, out, B, n_out, st);
+        case 16: return run_inv1d<4, 4, 512>(in, out, B, n_out, st);
+        case 32: return run_inv1d<8, 4, 256>(in, out, B, n_out, st);
+        case 64: return run_inv1d<8, 8, 128>(in, out, B, n_out, st);
+        case 128: return run_inv1d<16, 8, 128>(in, out, B, n_out, st);
+        case 256: return run_inv1d<32, 8, 64>(in, out, B, n_out, st);
         default: return hipErrorInvalidValue;
     }
 }
