@@ -921,7 +921,7 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
     if (view && !conv) return hipErrorInvalidValue;
     switch (N) {
         case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
-        case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
+        case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);   // (8,2): 12 % slower
         case 32: return run_fwd2d<16, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);   // (32,1): equal at C2, 3..5 % slower on large grids
         case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st, view);   // (64,1): 25 % slower, (16,4): 5 % slower
         case 128: return run_fwd2d<16, 8, 1>(in, out, planes, h_in, w_in, conv, st, view);
@@ -983,9 +983,15 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
     const int rows = h_out + (view ? view->oy : 0);   // rows of the transform that are computed
     switch (N) {
         case 8: return run_inv2d<8, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
-        case 16: return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 16:
+            // lane pairs when at most half the rows are kept (3x3 weight gradients: 29 us against
+            // 36 on the 13x13 layer), one lane per line otherwise (19 us against 23)
+            if (conv && 2 * rows <= 16) return run_inv2d<8, 2, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+            return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 32:
-            if (conv && 2 * rows > 32) return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+            // one lane per line only for grids of a single round of workgroups that keep most rows
+            // (the 27x27 layer: 15.0 us against 16.1); lane pairs are 3..6 % faster on large grids
+            if (conv && 2 * rows > 32 && planes <= 16 * 1024) return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
             return run_inv2d<16, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         // the inverse gains from more lanes per line (fewer registers, shorter serial chains):
         // (16,4) measured 15..25 % faster than (32,2) here, (16,2) 20 % faster than (32,1) at 32
