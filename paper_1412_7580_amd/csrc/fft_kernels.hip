@@ -995,7 +995,11 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
             return run_inv2d<16, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         // the inverse gains from more lanes per line (fewer registers, shorter serial chains):
         // (16,4) measured 15..25 % faster than (32,2) here, (16,2) 20 % faster than (32,1) at 32
-        case 64: return run_inv2d<16, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 64:
+            // eight lanes per line when (nearly) all rows are kept (64x64 input gradients: 42 us
+            // against 49), four otherwise (31x31 crops: 89 us against 92)
+            if (conv && 4 * rows > 3 * 64) return run_inv2d<8, 8, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+            return run_inv2d<16, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 128: return run_inv2d<16, 8, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         default: return hipErrorInvalidValue;
     }
