@@ -28,10 +28,19 @@ struct fftconv_ctx {
     char last_hip_error[256];
 };
 
+// Fourier bases of the 2-D transforms: the powers of two 8 ... 128 (Section 5 of the paper) and
+// the sizes 2^a * {3, 5, 7} between them (the search space of Section 3.4 restricted to one odd
+// factor).
+static const int kBases[] = {8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128};
+static bool basis_ok(int n) {
+    for (int b : kBases) if (b == n) return true;
+    return false;
+}
+// Smallest basis that holds an h x w image; above 128 for images that none holds.
 static int basis_size(int h, int w) {
-    int m = h > w ? h : w, n = 8;
-    while (n < m) n <<= 1;
-    return n;
+    const int m = h > w ? h : w;
+    for (int b : kBases) if (b >= m) return b;
+    return 256;
 }
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -52,21 +61,20 @@ struct PassPlan {
 };
 
 static int ceil_div(int a, int b) { return (a + b - 1) / b; }
-static bool pow2_basis(int n) { return n == 8 || n == 16 || n == 32 || n == 64 || n == 128; }
 
-// Tile basis used when the caller leaves the choice to the library: the power of two that
-// minimises (number of tiles) x (bins per tile) x (relative cost of a bin at that basis).
-// The first two factors count the contraction's work and the frequency tensors' size; the
-// third is measured (224x224 5x5 and 3x3, 160x160 11x11, 55x55 5x5 layers on this chip):
-// basis 32 and 64 run at the same cost per bin, 16 about 1.3x, 8 about 2.5x (many tiny planes),
-// 128 about 3x (one plane per workgroup, scalar gathers in the contraction).
-// Output tiles are (n - kh + 1) x (n - kw + 1).
-static double basis_weight(int n) { return n == 8 ? 2.5 : n == 16 ? 1.3 : n == 32 ? 1.0 : n == 64 ? 1.05 : 3.0; }
+// Tile basis used when the caller leaves the choice to the library: the basis that minimises
+// (number of tiles) x (bins per tile) x (relative cost of a bin at that basis).  The first two
+// factors count the contraction's work and the frequency tensors' size; the third is measured
+// per size class, i.e. per number of planes a workgroup transforms (224x224 5x5 and 3x3, 160x160
+// 11x11, 55x55 5x5 layers on this chip): the classes of 32 and 64 run at the same cost per bin,
+// 16 about 1.3x, 8 about 2.5x (many tiny planes), 128 about 3x (one plane per workgroup, scalar
+// gathers in the contraction).  Output tiles are (n - kh + 1) x (n - kw + 1).
+static double basis_weight(int n) { return n <= 8 ? 2.5 : n <= 16 ? 1.3 : n <= 32 ? 1.0 : n <= 64 ? 1.05 : 3.0; }
 static int pick_tile_basis(int h, int w, int kh, int kw, double *cost_out = nullptr) {
     const int oh = h - kh + 1, ow = w - kw + 1;
     int best = 0;
     double best_cost = 0;
-    for (int n = 8; n <= 128; n <<= 1) {
+    for (int n : kBases) {
         if (n < kh || n < kw) continue;
         const double cost = (double)ceil_div(oh, n - kh + 1) * ceil_div(ow, n - kw + 1) * n * (n / 2 + 1) * basis_weight(n);
         if (!best || cost < best_cost) { best = n; best_cost = cost; }
@@ -90,7 +98,7 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
     const int hp = h + 2 * ph, wp = w + 2 * pw;             // padded image
     if (kh > hp || kw > wp) return FFTCONV_INVALID_ARG;
     if (pass < 0 || pass > 2) return FFTCONV_INVALID_ARG;
-    if (tile_n > 0 && (!pow2_basis(tile_n) || tile_n < kh || tile_n < kw)) return FFTCONV_INVALID_ARG;
+    if (tile_n > 0 && (!basis_ok(tile_n) || tile_n < kh || tile_n < kw)) return FFTCONV_INVALID_ARG;
     int N = basis_size(hp, wp);
     bool tiled = tile_n >= 0 || ph > 0 || pw > 0;
     if (tiled && tile_n < 0) tile_n = 0;
@@ -106,7 +114,7 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
     const int oh = hp - kh + 1, ow = wp - kw + 1;
     const int dy = N - kh + 1, dx = N - kw + 1;             // output tile (tiled plans only)
     p->N = N;
-    p->bins = N * (N / 2 + 1);
+    p->bins = fft2d_layout_bins(N);
     p->lay.tsh = fft2d_tile_log2(N);
     p->lay.bins = p->bins;
     p->conjA = p->conjB = false;
@@ -231,7 +239,7 @@ static float *at(void *base, size_t off) { return reinterpret_cast<float *>(stat
 static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a, float *AF,
                                const float *b, float *BF) {
     const PlaneView *va = p.viewA ? &p.vA : nullptr, *vb = p.viewB ? &p.vB : nullptr;
-    if (p.N <= 32) {
+    if (p.lay.tsh >= 4) {
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, va}, {b, BF, p.planesB, p.hB, p.wB, vb}};
         return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c));
     }
@@ -420,9 +428,9 @@ int fft_conv_accgrad_padded(fftconv_handle hd, const float *x, const float *gy, 
                     pad_h, pad_w);
 }
 
-static bool fft_size_ok(int n) { return n == 8 || n == 16 || n == 32 || n == 64 || n == 128; }
-// 1-D transforms go one size further (the range of Section 5.3 of the paper).
-static bool fft1d_size_ok(int n) { return fft_size_ok(n) || n == 256; }
+static bool fft_size_ok(int n) { return basis_ok(n); }
+// 1-D transforms go one octave further (the range of Section 5.3 of the paper).
+static bool fft1d_size_ok(int n) { return basis_ok(n) || n == 160 || n == 192 || n == 224 || n == 256; }
 
 int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in, int n) {
     if (!hd || B < 0 || n_in <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;
@@ -569,7 +577,7 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
         if ((e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
     } else {
         // gy cut twice: overlapping windows for bprop, disjoint tiles for accGrad
-        if (gx && gw && pb.N <= 32) {   // small bases: both in one launch, as for the two operands of a pass
+        if (gx && gw && pb.lay.tsh >= 4) {   // small bases: both in one launch, as for the two operands of a pass
             FwdOperand ops[2] = {{gy, GYF, pb.planesA, pb.hA, pb.wA, &pb.vA}, {gy, GYFa, pa.planesA, pa.hA, pa.wA, &pa.vA}};
             if ((e = launch_fft2d_r2c_multi(ops, 2, pb.N, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
         } else {

@@ -30,15 +30,28 @@ constexpr double cos_small(double x) {
     return sum;
 }
 struct cplx_d { double re, im; };
-// exp(+2 pi i k / n) for n a power of two <= 1024, by octant reduction so that exact
-// values (0, +-1) and symmetries come out exactly.
+// exp(+2 pi i k / n), by octant reduction so that exact values (0, +-1) and symmetries come
+// out exactly.  Powers of two up to 1024 keep their own path (angles in 1024ths of a turn);
+// any other n reduces 8k/n to an octant and a remainder.
 constexpr cplx_d unit_root(int k, int n) {
-    int K = ((k % n) + n) % n * (1024 / n);
-    int q = K / 256, r = K % 256;
+    const bool pow2 = (n & (n - 1)) == 0 && n <= 1024;
+    int q = 0;
     double c = 0, s = 0;
-    if (r <= 128) { double a = 2.0 * kPi * r / 1024.0; c = cos_small(a); s = sin_small(a); }
-    else { double a = 2.0 * kPi * (256 - r) / 1024.0; c = sin_small(a); s = cos_small(a); }
-    if (r == 0) { c = 1.0; s = 0.0; }
+    if (pow2) {
+        int K = ((k % n) + n) % n * (1024 / n);
+        q = K / 256;
+        int r = K % 256;
+        if (r <= 128) { double a = 2.0 * kPi * r / 1024.0; c = cos_small(a); s = sin_small(a); }
+        else { double a = 2.0 * kPi * (256 - r) / 1024.0; c = sin_small(a); s = cos_small(a); }
+        if (r == 0) { c = 1.0; s = 0.0; }
+    } else {
+        const int t = 8 * (((k % n) + n) % n);
+        const int oct = t / n, rem = t % n;          // angle = (oct + rem / n) * pi / 4
+        q = oct / 2;
+        if (oct % 2 == 0) { double a = kPi * rem / (4.0 * n); c = cos_small(a); s = sin_small(a); }
+        else { double a = kPi * (n - rem) / (4.0 * n); c = sin_small(a); s = cos_small(a); }
+        if (rem == 0 && oct % 2 == 0) { c = 1.0; s = 0.0; }
+    }
     switch (q) {
         case 0: return {c, s};
         case 1: return {-s, c};
@@ -78,6 +91,39 @@ __device__ __forceinline__ void fft_leaf(float (&re)[L], float (&im)[L]) {
             re[1] = d0r - d1i; im[1] = d0i + d1r;
             re[3] = d0r + d1i; im[3] = d0i - d1r;
         }
+    } else if constexpr (L % 2 == 1) {
+        // Odd length (3, 5, 7, ...): the definition, with the samples m and L - m paired so that
+        // bins k and L - k share their products:
+        //   X_k, X_{L-k} = x_0 + sum_m cos(2 pi mk/L) (x_m + x_{L-m})  +-  DIR i sum_m sin(2 pi mk/L) (x_m - x_{L-m})
+        constexpr int H = (L - 1) / 2;
+        float ar[H], ai[H], br[H], bi[H];
+        float s0r = re[0], s0i = im[0];
+#pragma unroll
+        for (int m = 1; m <= H; ++m) {
+            ar[m - 1] = re[m] + re[L - m]; ai[m - 1] = im[m] + im[L - m];
+            br[m - 1] = re[m] - re[L - m]; bi[m - 1] = im[m] - im[L - m];
+            s0r += ar[m - 1]; s0i += ai[m - 1];
+        }
+        const float x0r = re[0], x0i = im[0];
+        re[0] = s0r; im[0] = s0i;
+        static_for<1, H + 1>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            float pr = x0r, pi = x0i, qr = 0.f, qi = 0.f;
+            static_for<1, H + 1>([&](auto mm) {
+                constexpr int m = decltype(mm)::value;
+                constexpr cplx_d w = unit_root((m * k) % L, L);
+                constexpr float c = (float)w.re, s = (float)w.im;
+                pr += c * ar[m - 1]; pi += c * ai[m - 1];
+                qr += s * br[m - 1]; qi += s * bi[m - 1];
+            });
+            if constexpr (DIR < 0) {   // X_k = P - i Q, X_{L-k} = P + i Q
+                re[k] = pr + qi; im[k] = pi - qr;
+                re[L - k] = pr - qi; im[L - k] = pi + qr;
+            } else {
+                re[k] = pr - qi; im[k] = pi + qr;
+                re[L - k] = pr + qi; im[L - k] = pi - qr;
+            }
+        });
     } else {
         constexpr int H = L / 2;
         float er[H], ei[H], pr[H], pi[H];

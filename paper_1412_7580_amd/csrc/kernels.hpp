@@ -34,7 +34,7 @@ hipError_t allow_big_lds(const void *fn, size_t bytes);
 // without ever materialising the BDHW frequency tensors or the three transposes.
 struct FreqLayout {
     int tsh;    // log2(T)
-    int bins;   // N * (N/2 + 1)
+    int bins;   // bin stride of a plane tile: N * (N/2 + 1) rounded up to a multiple of 8
     __host__ __device__ size_t index(long plane, int bin, int c) const {
         const long pt = plane >> tsh;
         const long pl = plane & ((1L << tsh) - 1);
@@ -63,6 +63,17 @@ struct PlaneView {
 
 // Planes per workgroup (= layout tile) of the 2-D kernels for basis N.
 int fft2d_tile_log2(int N);
+// Bins per plane tile of the layout for basis N: N * (N/2 + 1) rounded up to a multiple of 8 (of
+// 32 for the bases with runs of 4 planes), so that the contraction can always cut the bins into
+// equal chunks per XCD (and whole 128-byte lines).  The padding bins, which only bases with an
+// odd factor have, are never written by the transforms nor read by the inverse; the
+// contraction multiplies whatever they hold into the padding bins of its output.
+int fft2d_layout_bins(int N);
+// Bins per plane tile of the layout for basis N: N * (N/2 + 1) rounded up to a multiple of 8, so
+// that the contraction can always cut the bins into equal chunks per XCD.  The padding bins
+// (bases 12, 20 and 28 have some) are never written by the transforms nor read by the inverse;
+// the contraction multiplies whatever they hold into padding bins of its output.
+int fft2d_layout_bins(int N);
 
 // 2-D R2C of `planes` planes [h_in x w_in] zero-padded to N x N.
 //   conv layout: out = FreqLayout buffer (tile = fft2d_tile_log2(N)).

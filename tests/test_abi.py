@@ -29,10 +29,15 @@ def test_host_only_calls():
     lib = pkg.load_library()
     assert lib.fftconv_status_string(0) == b"ok"
     assert b"workspace" in lib.fftconv_status_string(3)
-    # fprop of the smallest configuration: three frequency tensors of 256 planes, 144 bins
+    # fprop of the smallest configuration: 13x13 images take basis 14, so three frequency
+    # tensors of 256 planes and 14 * 8 = 112 bins
     need = lib.fftconv_workspace_bytes(0, 16, 16, 16, 13, 13, 3, 3)
-    assert need == 3 * 256 * 144 * 2 * 4
-    assert lib.fftconv_saved_bytes(16, 16, 16, 13, 13, 3, 3) == 2 * 256 * 144 * 2 * 4
+    assert need == 3 * 256 * 112 * 2 * 4
+    assert lib.fftconv_saved_bytes(16, 16, 16, 13, 13, 3, 3) == 2 * 256 * 112 * 2 * 4
+    # 16x16 images need basis 16 (144 bins); 27x27 take basis 28, whose 28 * 15 = 420 bins are
+    # padded to 424 so that the bins split evenly over the eight XCDs
+    assert lib.fftconv_workspace_bytes(0, 16, 16, 16, 16, 16, 3, 3) == 3 * 256 * 144 * 2 * 4
+    assert lib.fftconv_workspace_bytes(0, 16, 16, 16, 27, 27, 5, 5) == 3 * 256 * 424 * 2 * 4
     # invalid (kernel larger than input, no such pass) and unsupported (kernel beyond every basis) shapes
     assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 4, 4, 5, 5) == 0
     assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 200, 200, 130, 130) == 0
@@ -40,7 +45,7 @@ def test_host_only_calls():
     # an image beyond the largest basis is tiled: 200x200, 3x3 kernel -> the basis with the
     # fewest bins overall, and the same workspace as the explicit tiled call with that choice
     n = lib.fftconv_tile_basis(200, 200, 3, 3, 0)
-    assert n in (8, 16, 32, 64, 128)
+    assert n in (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128)
     assert lib.fftconv_workspace_bytes(0, 1, 1, 1, 200, 200, 3, 3) == \
         lib.fftconv_tiled_workspace_bytes(0, 1, 1, 1, 200, 200, 3, 3, n) > 0
     # forced basis 8 on a 20x20 image with a 3x3 kernel: 6x6 output tiles, 3x3 of them
@@ -48,7 +53,7 @@ def test_host_only_calls():
     pad = lambda planes: -(-planes // T) * T
     assert lib.fftconv_tiled_workspace_bytes(0, 2, 3, 4, 20, 20, 3, 3, 8) == \
         (pad(2 * 9 * 3) + pad(4 * 3) + pad(2 * 9 * 4)) * 40 * 2 * 4
-    assert lib.fftconv_tiled_workspace_bytes(0, 2, 3, 4, 20, 20, 3, 3, 12) == 0
+    assert lib.fftconv_tiled_workspace_bytes(0, 2, 3, 4, 20, 20, 3, 3, 18) == 0   # no such basis
     assert lib.fftconv_tile_basis(20, 20, 9, 9, 8) == 0
 
 

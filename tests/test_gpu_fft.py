@@ -1,7 +1,7 @@
 """Parity of the stand-alone FFT entry points against the naive-DFT oracle (GPU, via the C ABI).
 
 Bound: max|err| / max|ref| <= 1e-5 (fp32 transforms of length <= 128 per dimension, 256 in
-1-D: the error of an n-point fp32 FFT grows like log2(n) * 6e-8 relative to the largest output)."""
+1-D, powers of two and sizes with one factor 3, 5 or 7: the error of an n-point fp32 FFT grows like log2(n) * 6e-8 relative to the largest output)."""
 import numpy as np
 import pytest
 
@@ -10,8 +10,10 @@ from paper_1412_7580_amd import synth
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-5
-SIZES = [8, 16, 32, 64, 128]
-SIZES_1D = SIZES + [256]      # the 1-D calls go one size further (Section 5.3 of the paper)
+POW2 = [8, 16, 32, 64, 128]                            # the sizes of Section 5 of the paper
+MIXED = [12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112]   # 2^a * {3, 5, 7}: the bases of Section 3.2
+SIZES = sorted(POW2 + MIXED)
+SIZES_1D = SIZES + [160, 192, 224, 256]   # the 1-D calls go one octave further (Section 5.3)
 
 
 @pytest.fixture(scope="module")
@@ -94,7 +96,7 @@ def test_c2r_2d(hd, n, B):
 
 
 @pytest.mark.parametrize("dim", [1, 2])
-@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("n", POW2)
 def test_sweep_roundtrip_subset(hd, dim, n):
     """The FFT-sweep workload at a reduced batch: R2C from size n-3 then C2R cropped back."""
     B = 4099
@@ -117,7 +119,7 @@ def test_argument_errors(hd, lib):
     import torch
     x = torch.zeros((4, 20), device="cuda")
     with pytest.raises(lib.FFTConvError, match="unsupported"):
-        hd.fft_r2c_1d(x, 24)
+        hd.fft_r2c_1d(x, 36)            # 2^2 * 3^2: two odd factors
     with pytest.raises(lib.FFTConvError, match="invalid"):
         hd.fft_r2c_1d(x, 16)            # n_in > n
     with pytest.raises(lib.FFTConvError, match="unsupported"):
@@ -130,7 +132,7 @@ def test_argument_errors(hd, lib):
 
 
 @pytest.mark.parametrize("dim", [1, 2])
-@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("n", POW2)
 def test_sweep_full_size(hd, dim, n):
     """The FFT-sweep workload at its full size (256 MiB of input, the launch configuration the
     benchmark times): R2C checked against the oracle on the first, the last and a seeded sample

@@ -46,14 +46,14 @@ def _draw(case):
     mode = ("ordinary", "tiled", "padded")[case % 3]
     cfg = dict(S=S, f=f, fo=fo, h=h, w=w, kh=kh, kw=kw)
     if mode == "tiled":
-        bases = [n for n in (8, 16, 32, 64) if n >= max(kh, kw)]
+        bases = [n for n in (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64) if n >= max(kh, kw)]
         return cfg, mode, (int(rng.choice(bases + [0])),)
     if mode == "padded":
         return cfg, mode, (int(rng.integers(0, 4)), int(rng.integers(0, 4)))
     return cfg, mode, ()
 
 
-@pytest.mark.parametrize("case", range(45))
+@pytest.mark.parametrize("case", range(60))
 def test_random_shape(hd, case):
     cfg, mode, par = _draw(case)
     h, w = cfg["h"], cfg["w"]

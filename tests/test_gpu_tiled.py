@@ -56,6 +56,19 @@ TILED = [
     (dict(S=1, f=2, fo=2, h=37, w=44, kh=3, kw=9), 16),
     # one tile at the largest basis: the conv-layout kernels of basis 128
     (dict(S=1, f=2, fo=3, h=100, w=128, kh=9, kw=11), 128),
+    # every basis with an odd factor (Section 3.2): several ragged tiles each, and plane counts
+    # that do and do not fill the kernels' plane tiles
+    (dict(S=2, f=3, fo=4, h=25, w=31, kh=3, kw=3), 12),
+    (dict(S=2, f=5, fo=3, h=27, w=27, kh=3, kw=5), 14),
+    (dict(S=1, f=4, fo=4, h=50, w=41, kh=5, kw=5), 20),
+    (dict(S=3, f=2, fo=3, h=45, w=60, kh=7, kw=2), 24),
+    (dict(S=2, f=3, fo=2, h=60, w=57, kh=5, kw=5), 28),
+    (dict(S=1, f=2, fo=3, h=90, w=75, kh=9, kw=9), 40),
+    (dict(S=1, f=3, fo=2, h=100, w=95, kh=11, kw=5), 48),
+    (dict(S=1, f=2, fo=2, h=110, w=60, kh=7, kw=7), 56),
+    (dict(S=1, f=2, fo=1, h=150, w=81, kh=5, kw=9), 80),
+    (dict(S=1, f=1, fo=2, h=100, w=190, kh=13, kw=3), 96),
+    (dict(S=1, f=2, fo=2, h=112, w=120, kh=9, kw=9), 112),
 ]
 IDS = ["S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c) + f"_n{n}" for c, n in TILED]
 
@@ -132,15 +145,16 @@ def test_tiled_workspace_and_errors(hd, lib):
     assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
     with pytest.raises(lib.FFTConvError, match="workspace too small"):
         hd.fft_conv_fprop_tiled(dx, dw, 8, ws=ws[: need // 4 - 64])
-    for bad in (-1, 12, 256):
+    for bad in (-1, 18, 256):
         with pytest.raises(lib.FFTConvError, match="invalid argument"):
             hd.fft_conv_fprop_tiled(dx, dw, bad)
     big_k = torch.zeros((1, 1, 9, 9), device="cuda")
     with pytest.raises(lib.FFTConvError, match="invalid argument"):      # basis smaller than the kernel
         hd.fft_conv_fprop_tiled(torch.zeros((1, 1, 20, 20), device="cuda"), big_k, 8)
     assert hd.tile_basis(20, 20, 3, 3, 16) == 16
-    assert hd.tile_basis(200, 200, 5, 5, 0) in (8, 16, 32, 64, 128)
-    assert hd.tile_basis(20, 20, 3, 3, 12) == 0
+    assert hd.tile_basis(200, 200, 5, 5, 0) in (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128)
+    assert hd.tile_basis(20, 20, 3, 3, 12) == 12
+    assert hd.tile_basis(20, 20, 3, 3, 18) == 0
 
 
 def test_tiled_is_deterministic(hd):
