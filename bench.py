@@ -74,20 +74,43 @@ def direct_flops(cfg):
     return 2 * S * f * fo * kh * kw * (h - kh + 1) * (w - kw + 1)
 
 
-def run_step(hd, t, cfg, passes, reuse=False):
+def run_step(hd, t, cfg, passes, reuse=False, basis=None):
     """One step.  reuse=True: fft_conv_fprop_save + fft_conv_backward (x and w are transformed
-    once, gy once); reuse=False: the three independent passes."""
+    once, gy once); reuse=False: the three independent passes.  basis=None leaves the Fourier
+    basis to the library (the smallest one that holds the image); a number names it (the *_tiled
+    entry points: a basis that holds the whole image runs the untiled pipeline at that basis)."""
+    dims = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
     if reuse and len(passes) == 3:
-        hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
-        hd.fft_conv_backward(t["gy"], t["saved"], cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"],
-                             gx=t["gx"], gw=t["gw"])
+        if basis is None:
+            hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
+            hd.fft_conv_backward(t["gy"], t["saved"], *dims, gx=t["gx"], gw=t["gw"])
+        else:
+            hd.fft_conv_fprop_save_tiled(t["x"], t["w"], basis, t["saved"], y=t["y"])
+            hd.fft_conv_backward_tiled(t["gy"], t["saved"], *dims, basis, gx=t["gx"], gw=t["gw"])
         return
     if "fprop" in passes:
-        hd.fft_conv_fprop(t["x"], t["w"], y=t["y"])
+        if basis is None:
+            hd.fft_conv_fprop(t["x"], t["w"], y=t["y"])
+        else:
+            hd.fft_conv_fprop_tiled(t["x"], t["w"], basis, y=t["y"])
     if "bprop" in passes:
-        hd.fft_conv_bprop(t["gy"], t["w"], cfg["h"], cfg["w"], gx=t["gx"])
+        if basis is None:
+            hd.fft_conv_bprop(t["gy"], t["w"], cfg["h"], cfg["w"], gx=t["gx"])
+        else:
+            hd.fft_conv_bprop_tiled(t["gy"], t["w"], cfg["h"], cfg["w"], basis, gx=t["gx"])
     if "accgrad" in passes:
-        hd.fft_conv_accgrad(t["x"], t["gy"], gw=t["gw"])
+        if basis is None:
+            hd.fft_conv_accgrad(t["x"], t["gy"], gw=t["gw"])
+        else:
+            hd.fft_conv_accgrad_tiled(t["x"], t["gy"], basis, gw=t["gw"])
+
+
+BASES = (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128)
+
+
+def library_basis(cfg):
+    """The basis the ordinary entry points use for an untiled layer: the smallest that holds the image."""
+    return next(b for b in BASES if b >= max(cfg["h"], cfg["w"]))
 
 
 def device_tensors(cfg, seed):
@@ -99,25 +122,26 @@ def device_tensors(cfg, seed):
     return t, (x, w, gy)
 
 
-def add_saved(hd, t, cfg):
+def add_saved(hd, t, cfg, basis=None):
     import torch
-    n = hd.saved_bytes(cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    n = hd.saved_bytes(*dims) if basis is None else hd.saved_bytes_tiled(*dims, basis)
     t["saved"] = torch.empty(n // 4, device="cuda", dtype=torch.float32)
 
 
-def time_steps(hd, t, cfg, passes, steps, warmup, reuse=False):
+def time_steps(hd, t, cfg, passes, steps, warmup, reuse=False, basis=None):
     import torch
     for _ in range(warmup):
-        run_step(hd, t, cfg, passes, reuse)
+        run_step(hd, t, cfg, passes, reuse, basis)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        run_step(hd, t, cfg, passes, reuse)
+        run_step(hd, t, cfg, passes, reuse, basis)
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) / steps
 
 
-def profile_stages(hd, t, cfg, passes, steps):
+def profile_stages(hd, t, cfg, passes, steps, basis=None):
     """Average execution time (ms) of each kernel of each pass over `steps` repetitions, from the
     start/stop events the library attaches to every dispatch on its stream.
     Returns {pass: [fft, contraction, ifft]}."""
@@ -126,7 +150,7 @@ def profile_stages(hd, t, cfg, passes, steps):
     acc = {p: [0.0] * 3 for p in passes}
     for _ in range(steps):
         for p in passes:
-            run_step(hd, t, cfg, (p,))
+            run_step(hd, t, cfg, (p,), False, basis)
             ms = hd.last_kernel_ms()
             for i in range(3):
                 acc[p][i] += ms[i]
@@ -141,16 +165,22 @@ BACKWARD_KERNELS = {5: ("backward.fft", "bprop.contraction", "bprop.ifft", "accg
                     4: ("backward.fft", "backward.contraction", "bprop.ifft", "accgrad.ifft")}
 
 
-def profile_reuse_step(hd, t, cfg, steps):
+def profile_reuse_step(hd, t, cfg, steps, basis=None):
     """Same for the two-call step with transform reuse: {kernel name: ms}."""
     import torch
     hd.set_profiling(True)
     acc = {}
+    dims = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
     for _ in range(steps):
-        hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
+        if basis is None:
+            hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
+        else:
+            hd.fft_conv_fprop_save_tiled(t["x"], t["w"], basis, t["saved"], y=t["y"])
         a = hd.last_kernel_ms()
-        hd.fft_conv_backward(t["gy"], t["saved"], cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"],
-                             gx=t["gx"], gw=t["gw"])
+        if basis is None:
+            hd.fft_conv_backward(t["gy"], t["saved"], *dims, gx=t["gx"], gw=t["gw"])
+        else:
+            hd.fft_conv_backward_tiled(t["gy"], t["saved"], *dims, basis, gx=t["gx"], gw=t["gw"])
         b = hd.last_kernel_ms()
         for k, v in zip(FPROP_KERNELS + BACKWARD_KERNELS[len(b)], a + b):
             acc[k] = acc.get(k, 0.0) + v
@@ -285,7 +315,8 @@ def graph_replay_c1(hd, reps=200):
 
 def tiled_layers(hd, reps=10):
     """Tiling (Section 6 of the paper) on two layers: an image beyond the largest basis, which
-    the ordinary entry points tile by themselves, and a mid-size layer run untiled and tiled.
+    the ordinary entry points tile by themselves, a mid-size layer run untiled and tiled, and a
+    layer between the two whose basis is also chosen by measurement (fftconv_autotune_basis).
     Timing only (uniform[-1,1) inputs drawn on the device from a fixed seed); parity of the
     tiled path is covered by the tests."""
     import torch
@@ -331,14 +362,14 @@ def tiled_layers(hd, reps=10):
         hd.fft_conv_fprop_tiled(x, wt, 0, y=y); hd.fft_conv_bprop_tiled(gy, wt, h, w, 0, gx=gx)
         hd.fft_conv_accgrad_tiled(x, gy, 0, gw=gw)
     su, st = timed(untiled), timed(tiled)
-    out["S32_f96_f'96_55x55_k5"] = {"untiled_basis": 64, "untiled_ms_per_step": round(su * 1e3, 4),
+    out["S32_f96_f'96_55x55_k5"] = {"untiled_basis": 56, "untiled_ms_per_step": round(su * 1e3, 4),
                                     "untiled_effective_TFLOPs": round(fl / su / 1e12, 2),
                                     "tile_basis": hd.tile_basis(h, w, k, k, 0), "tiled_ms_per_step": round(st * 1e3, 4),
                                     "tiled_effective_TFLOPs": round(fl / st / 1e12, 2),
                                     "calls": "three independent passes each way"}
     del x, wt, gy, y, gx, gw
-    # a layer whose untiled basis would be 128: the ordinary entry points tile it by themselves;
-    # tile basis 128 (one window per image) stands for the untiled basis
+    # a layer whose untiled basis would be 112: the ordinary entry points tile it by themselves;
+    # naming basis 128 runs the untiled pipeline (one 128x128 transform per image)
     S, f, fo, h, w, k = 16, 128, 128, 112, 112, 3
     x, wt, gy = mk(S, f, h, w), mk(fo, f, k, k), mk(S, fo, h - k + 1, w - k + 1)
     y, gx, gw = torch.empty_like(gy), torch.empty_like(x), torch.empty_like(wt)
@@ -356,7 +387,11 @@ def tiled_layers(hd, reps=10):
                                         "basis128_ms_per_step": round(s1 * 1e3, 4),
                                         "basis128_effective_TFLOPs": round(fl / s1 / 1e12, 2),
                                         "calls": "three independent passes; ordinary entry points (tile by themselves) "
-                                                 "vs one 128-basis window per image"}
+                                                 "vs the untiled pipeline on basis 128"}
+    # basis selection by measurement against the library's static estimate
+    n_auto, ms_auto = hd.autotune_basis(x, wt, gy, y=y, gx=gx, gw=gw, reps=3)
+    out["S16_f128_f'128_112x112_k3"]["autotuned_basis"] = n_auto
+    out["S16_f128_f'128_112x112_k3"]["autotuned_ms_per_step"] = round(ms_auto, 4)
     return out
 
 
@@ -369,6 +404,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-passes", action="store_true",
                     help="time the three independent pass calls instead of fprop_save + backward")
+    ap.add_argument("--library-basis", action="store_true",
+                    help="leave the Fourier basis to the library (28x28 for C2) instead of the one the "
+                         "configuration names")
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the FFT sweep")
     ap.add_argument("--tiled-only", action="store_true",
                     help="only time the tiled layers of the extra block and print them (for profiling runs)")
@@ -404,10 +442,15 @@ def main():
     passes = synth.CONV_CONFIGS[name]["passes"]
     t, host = device_tensors(cfg, synth.CONV_SEEDS[name])
 
+    # The headline runs on the Fourier basis the configuration names (FFT 32x32 for C2); the
+    # library's own choice, the smallest basis that holds the image, is timed next to it below.
+    basis = None if args.library_basis else cfg["N"]
+    if args.library_basis:
+        cfg["N"] = library_basis(cfg)
     reuse = (len(passes) == 3) and not args.separate_passes
     if reuse:
-        add_saved(hd, t, cfg)
-    sec = time_steps(hd, t, cfg, passes, args.steps, args.warmup, reuse)
+        add_saved(hd, t, cfg, basis)
+    sec = time_steps(hd, t, cfg, passes, args.steps, args.warmup, reuse, basis)
     flops = direct_flops(cfg) * len(passes)
     value = flops / sec / 1e12
 
@@ -423,7 +466,7 @@ def main():
         return ent
 
     if reuse:
-        km = profile_reuse_step(hd, t, cfg, prof_steps)
+        km = profile_reuse_step(hd, t, cfg, prof_steps, basis)
         for k, ms in km.items():
             p, s_ = k.split(".")
             if k == "fprop.fft":
@@ -438,7 +481,7 @@ def main():
             kernels[k] = entry(ms, model)
             kernels[k]["_model"] = model
     else:
-        stage_ms = profile_stages(hd, t, cfg, passes, prof_steps)
+        stage_ms = profile_stages(hd, t, cfg, passes, prof_steps, basis)
         for p in passes:
             for i, s_ in enumerate(STAGES):
                 kernels[f"{p}.{s_}"] = entry(stage_ms[p][i], models[p][s_])
@@ -485,10 +528,29 @@ def main():
         out["cpu_baseline"] = cpu_baseline(cfg, host)
     if not args.no_extra:
         extra = {}
+        def measure(c, ps, b, n):
+            """Separate passes and, for three-pass workloads, the reuse step of configuration c on
+            basis b (None: the library's choice)."""
+            s3 = time_steps(hd, t, c, ps, n, 5, False, b)
+            sm = profile_stages(hd, t, c, ps, 5, b)
+            ent = {"basis": library_basis(c) if b is None else b,
+                   "ms_per_step_separate_passes": round(s3 * 1e3, 4),
+                   "effective_TFLOPs_separate_passes": round(direct_flops(c) * len(ps) / s3 / 1e12, 2),
+                   "kernel_ms[fft,contraction,ifft]": {p: [round(v, 4) for v in sm[p]] for p in ps}}
+            if len(ps) == 3:
+                add_saved(hd, t, c, b)
+                s2 = time_steps(hd, t, c, ps, n, 5, True, b)
+                ent["ms_per_step"] = round(s2 * 1e3, 4)
+                ent["effective_TFLOPs"] = round(direct_flops(c) * 3 / s2 / 1e12, 2)
+            return ent
+
         if reuse:
-            s3 = time_steps(hd, t, cfg, passes, max(10, args.steps // 4), 5, False)
+            s3 = time_steps(hd, t, cfg, passes, max(10, args.steps // 4), 5, False, basis)
             extra[name + "_separate_passes"] = {"ms_per_step": round(s3 * 1e3, 5),
                                                 "effective_TFLOPs": round(flops / s3 / 1e12, 2)}
+        if basis is not None and library_basis(cfg) != basis:
+            # the same workload with the basis left to the library (Section 3.4's basis search)
+            extra[name + "_library_basis"] = measure(cfg, passes, None, max(10, args.steps // 2))
         for other in ("C1", "C3", "C4"):
             if other == name:
                 continue
@@ -498,17 +560,9 @@ def main():
             opasses = synth.CONV_CONFIGS[other]["passes"]
             t, _ = device_tensors(ocfg, synth.CONV_SEEDS[other])
             n = 20 if other == "C4" else 50
-            s3 = time_steps(hd, t, ocfg, opasses, n, 5)
-            sm = profile_stages(hd, t, ocfg, opasses, 5)
-            ent = {"ms_per_step_separate_passes": round(s3 * 1e3, 4),
-                   "effective_TFLOPs_separate_passes": round(direct_flops(ocfg) * len(opasses) / s3 / 1e12, 2),
-                   "kernel_ms[fft,contraction,ifft]": {p: [round(v, 4) for v in sm[p]] for p in opasses}}
-            if len(opasses) == 3:
-                add_saved(hd, t, ocfg)
-                s2 = time_steps(hd, t, ocfg, opasses, n, 5, True)
-                ent["ms_per_step"] = round(s2 * 1e3, 4)
-                ent["effective_TFLOPs"] = round(direct_flops(ocfg) * 3 / s2 / 1e12, 2)
-            extra[other] = ent
+            extra[other] = measure(ocfg, opasses, ocfg["N"], n)
+            if library_basis(ocfg) != ocfg["N"]:
+                extra[other + "_library_basis"] = measure(ocfg, opasses, None, n)
         del t
         torch.cuda.empty_cache()
         extra["C1_fprop_hip_graph"] = graph_replay_c1(hd)

@@ -38,7 +38,7 @@ typedef struct fftconv_ctx *fftconv_handle;
 typedef enum {
     FFTCONV_OK = 0,
     FFTCONV_INVALID_ARG = 1,         /* null pointer, non-positive size, kernel larger than input, n_in > n ... */
-    FFTCONV_UNSUPPORTED = 2,         /* Fourier basis outside {8,16,32,64,128}; kernel larger than 128 */
+    FFTCONV_UNSUPPORTED = 2,         /* transform size that is not one of the bases; kernel larger than 128 */
     FFTCONV_WORKSPACE_TOO_SMALL = 3, /* caller-supplied workspace smaller than fftconv_workspace_bytes() */
     FFTCONV_HIP_ERROR = 4            /* allocation or launch failure reported by the HIP runtime */
 } fftconv_status;
@@ -63,6 +63,10 @@ size_t fftconv_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int
  * The three passes (Section 2; pipeline of Table 1; clipping sizes of Section 3.1).
  *   S minibatch, f input planes, fo output planes (f'), h x w input, kh x kw kernel,
  *   oh = h-kh+1, ow = w-kw+1.  Stride 1, no margin padding (Section 2 excludes strides).
+ * Fourier basis: the smallest of 8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64 that holds the
+ * image, square (the powers of two of Section 5 and, between them, the sizes 2^a x {3, 5, 7}
+ * of the search space of Section 3.4); larger images are tiled (see the tiled passes below).
+ * The same basis serves all three passes of a layer.
  * `ws`/`ws_bytes`: optional caller-owned device scratch of at least
  * fftconv_workspace_bytes(); with ws == NULL the handle grows and reuses its own buffer
  * (hipMalloc on first use or growth only).
@@ -92,13 +96,15 @@ int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *
  * input rows, so a large convolution splits into many small ones on a basis of
  * tile_n = d + kh - 1 (columns alike): fprop and bprop by overlapping input windows, accGrad
  * by summing the per-tile correlations, the tile index joining the minibatch index in the
- * reduction.  Results equal those of the untiled calls up to rounding.  tile_n is a power of
- * two in 8..128, at least max(kh, kw); 0 lets the library choose (the basis with the lowest
- * estimated cost: tiles x bins per tile x a measured per-basis factor).  The entry points
- * above tile by themselves, with that choice, when max(h, w) > 128 and when the estimate is
- * clearly below that of the untiled basis (in practice: layers whose untiled basis is 128).
- * Arguments, layouts and errors as for the untiled
- * calls; tile_n < 0, not a power of two or smaller than the kernel gives FFTCONV_INVALID_ARG.
+ * reduction.  Results equal those of the untiled calls up to rounding.  tile_n is one of the
+ * bases 8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128, at least max(kh, kw); 0
+ * lets the library choose (the basis with the lowest estimated cost: tiles x bins per tile x a
+ * measured per-basis factor).  A tile_n that holds the whole image (tile_n >= max(h, w)) runs
+ * the untiled pipeline at that basis: this is how a caller names the Fourier basis of a layer.
+ * The entry points above tile by themselves, with the library's choice, when max(h, w) > 128
+ * and when the estimate is clearly below that of the untiled basis (in practice: layers whose
+ * untiled basis is 80 or more).  Arguments, layouts and errors as for the untiled calls;
+ * tile_n < 0, not a basis or smaller than the kernel gives FFTCONV_INVALID_ARG.
  */
 size_t fftconv_tiled_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw, int tile_n);
 /* The basis a tiled call with this tile_n uses (host only; 0 for invalid arguments). */
@@ -112,6 +118,22 @@ int fft_conv_bprop_tiled(fftconv_handle hd, const float *gy, const float *wt, fl
 int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, float *gw,
                            int S, int f, int fo, int h, int w, int kh, int kw,
                            float scale, int accumulate, int tile_n, void *ws, size_t ws_bytes);
+
+/*
+ * Basis selection by measurement (the strategy selection of Section 3.4, here over the Fourier
+ * basis alone): runs fprop, bprop and accGrad of the layer at every basis that holds the
+ * kernel and whose estimated cost is within 3x of the lowest estimate, `reps` times each after
+ * one untimed run, and returns the basis with the shortest time for the three passes in
+ * *basis_out, for use as tile_n of the calls above (the caller caches it per layer shape).
+ * *ms_out, if not NULL, receives that time in milliseconds.  x, wt, gy are the layer's
+ * operands (device, read only); y, gx, gw (device) are overwritten and hold the chosen basis's
+ * results on return.  Uses the handle's own workspace, which grows to the largest candidate's
+ * need.  Synchronous: returns after the last run has finished.  Errors as for the passes;
+ * reps <= 0 or a NULL pointer other than ms_out gives FFTCONV_INVALID_ARG.
+ */
+int fftconv_autotune_basis(fftconv_handle hd, const float *x, const float *wt, const float *gy,
+                           float *y, float *gx, float *gw, int S, int f, int fo, int h, int w, int kh, int kw,
+                           int reps, int *basis_out, float *ms_out);
 
 /*
  * Passes of a layer whose input images are surrounded by pad_h rows and pad_w columns of zeros
@@ -144,11 +166,24 @@ int fft_conv_backward_padded(fftconv_handle hd, const float *gy, float *gx, floa
                              int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
                              float scale, int accumulate, const void *saved, size_t saved_bytes,
                              void *ws, size_t ws_bytes);
+/* The transform-reuse pair on a named basis (tile_n as for the tiled passes, e.g. the result
+ * of fftconv_autotune_basis); the same tile_n must be given to all four functions. */
+size_t fftconv_saved_bytes_tiled(int S, int f, int fo, int h, int w, int kh, int kw, int tile_n);
+size_t fftconv_backward_workspace_bytes_tiled(int S, int f, int fo, int h, int w, int kh, int kw, int tile_n);
+int fft_conv_fprop_save_tiled(fftconv_handle hd, const float *x, const float *wt, float *y,
+                              int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                              void *saved, size_t saved_bytes, void *ws, size_t ws_bytes);
+int fft_conv_backward_tiled(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                            int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                            float scale, int accumulate, const void *saved, size_t saved_bytes,
+                            void *ws, size_t ws_bytes);
 
 /*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
- * (Supplement, DFT definition); n in {8,16,32,64,128}, and 256 for the 1-D calls (the
- * sizes of Section 5.3).  Inputs shorter than n are
+ * (Supplement, DFT definition); n is a power of two in 8..128 (256 for the 1-D calls: the
+ * sizes of Section 5.3) or one of 12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112 (and 160, 192,
+ * 224 for the 1-D calls): 2^a x {3, 5, 7}, sizes Section 3.2 takes from cuFFT; any other n
+ * gives FFTCONV_UNSUPPORTED.  Inputs shorter than n are
  * zero-padded implicitly while loading (the clipping of Section 5.1), no padded copy is
  * made.  Complex data are interleaved (re,im) fp32; only the Hermitian half
  * k = 0..n/2 along the innermost axis is stored (Table 1), in natural bin order.

@@ -20,7 +20,9 @@ SYMBOLS = [
     "fftconv_set_profiling", "fftconv_last_kernel_ms",
     "fftconv_saved_bytes", "fftconv_backward_workspace_bytes", "fft_conv_fprop_save", "fft_conv_backward",
     "fftconv_tiled_workspace_bytes", "fftconv_tile_basis",
-    "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled",
+    "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled", "fftconv_autotune_basis",
+    "fftconv_saved_bytes_tiled", "fftconv_backward_workspace_bytes_tiled",
+    "fft_conv_fprop_save_tiled", "fft_conv_backward_tiled",
     "fftconv_padded_workspace_bytes",
     "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
     "fftconv_saved_bytes_padded", "fftconv_backward_workspace_bytes_padded",
@@ -73,6 +75,13 @@ def load_library():
     lib.fft_conv_fprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
     lib.fft_conv_bprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
     lib.fft_conv_accgrad_tiled.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i, i, vp, sz]
+    lib.fftconv_autotune_basis.argtypes = [vp] * 7 + [i] * 8 + [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
+    lib.fftconv_saved_bytes_tiled.argtypes = [i] * 8
+    lib.fftconv_saved_bytes_tiled.restype = sz
+    lib.fftconv_backward_workspace_bytes_tiled.argtypes = [i] * 8
+    lib.fftconv_backward_workspace_bytes_tiled.restype = sz
+    lib.fft_conv_fprop_save_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz, vp, sz]
+    lib.fft_conv_backward_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [f, i, vp, sz, vp, sz]
     lib.fftconv_padded_workspace_bytes.argtypes = [i] * 10
     lib.fftconv_padded_workspace_bytes.restype = sz
     lib.fft_conv_fprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
@@ -282,6 +291,65 @@ class Handle:
                                                 S, f, fo, h, w, kh, kw, float(scale), 1 if accumulate else 0,
                                                 int(tile_n), *self._ws(ws)), "fft_conv_accgrad_tiled")
         return gw
+
+    def autotune_basis(self, x, wt, gy, y=None, gx=None, gw=None, reps=3):
+        """Times the three passes at every candidate basis; returns (basis, ms of the three passes)."""
+        import torch
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f or tuple(gy.shape) != (S, fo, h - kh + 1, w - kw + 1):
+            raise FFTConvError("x, wt and gy disagree on the layer's shape")
+        y = torch.empty_like(gy) if y is None else y
+        gx = torch.empty_like(x) if gx is None else gx
+        gw = torch.empty_like(wt) if gw is None else gw
+        basis, ms = ctypes.c_int(0), ctypes.c_float(0.0)
+        self._sync_stream()
+        _check(self._lib.fftconv_autotune_basis(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(gy, "gy"),
+                                                _dev_f32(y, "y"), _dev_f32(gx, "gx"), _dev_f32(gw, "gw"),
+                                                S, f, fo, h, w, kh, kw, int(reps), ctypes.byref(basis), ctypes.byref(ms)),
+               "fftconv_autotune_basis")
+        return int(basis.value), float(ms.value)
+
+    def saved_bytes_tiled(self, S, f, fo, h, w, kh, kw, tile_n) -> int:
+        return int(self._lib.fftconv_saved_bytes_tiled(S, f, fo, h, w, kh, kw, tile_n))
+
+    def backward_workspace_bytes_tiled(self, S, f, fo, h, w, kh, kw, tile_n) -> int:
+        return int(self._lib.fftconv_backward_workspace_bytes_tiled(S, f, fo, h, w, kh, kw, tile_n))
+
+    def fft_conv_fprop_save_tiled(self, x, wt, tile_n, saved, y=None, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f:
+            raise FFTConvError("x and wt disagree on the number of input planes")
+        if y is None:
+            y = torch.empty((S, fo, h - kh + 1, w - kw + 1), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop_save_tiled(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
+                                                   S, f, fo, h, w, kh, kw, int(tile_n), *self._ws(saved), *self._ws(ws)),
+               "fft_conv_fprop_save_tiled")
+        return y
+
+    def fft_conv_backward_tiled(self, gy, saved, f, h, w, kh, kw, tile_n, gx=None, gw=None, want_gx=True,
+                                want_gw=True, scale=1.0, accumulate=False, ws=None):
+        import torch
+        S, fo, oh, ow = gy.shape
+        if oh != h - kh + 1 or ow != w - kw + 1:
+            raise FFTConvError("gy and (h, w, kh, kw) disagree")
+        if want_gx and gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        if want_gw and gw is None:
+            if accumulate:
+                raise FFTConvError("accumulate needs an existing gw")
+            gw = torch.empty((fo, f, kh, kw), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_backward_tiled(self._h, _dev_f32(gy, "gy"),
+                                                 _dev_f32(gx, "gx") if want_gx else None,
+                                                 _dev_f32(gw, "gw") if want_gw else None,
+                                                 S, f, fo, h, w, kh, kw, int(tile_n), float(scale),
+                                                 1 if accumulate else 0, *self._ws(saved), *self._ws(ws)),
+               "fft_conv_backward_tiled")
+        return gx, gw
 
     # ---- zero-padded layers ---------------------------------------------------------------
     def padded_workspace_bytes(self, pass_, S, f, fo, h, w, kh, kw, pad_h, pad_w) -> int:

@@ -64,19 +64,29 @@ static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // Tile basis used when the caller leaves the choice to the library: the basis that minimises
 // (number of tiles) x (bins per tile) x (relative cost of a bin at that basis).  The first two
-// factors count the contraction's work and the frequency tensors' size; the third is measured
-// per size class, i.e. per number of planes a workgroup transforms (224x224 5x5 and 3x3, 160x160
-// 11x11, 55x55 5x5 layers on this chip): the classes of 32 and 64 run at the same cost per bin,
-// 16 about 1.3x, 8 about 2.5x (many tiny planes), 128 about 3x (one plane per workgroup, scalar
-// gathers in the contraction).  Output tiles are (n - kh + 1) x (n - kw + 1).
-static double basis_weight(int n) { return n <= 8 ? 2.5 : n <= 16 ? 1.3 : n <= 32 ? 1.0 : n <= 64 ? 1.05 : 3.0; }
+// factors count the contraction's work and the frequency tensors' size; the tile count is the
+// mean over the three passes (fprop and accGrad tile the output, bprop the input), so that all
+// passes of a layer get the same basis and can share transforms.  The third factor is measured
+// (time of the three passes per tile-bin on 224x224 5x5 and 3x3, 160x160 11x11 and 72x72 7x7
+// layers on this chip, relative to basis 32): flat from 16 to 32, about 10 % more from 40 to 56,
+// 20 % at 64, more at the small bases (many tiny planes, long reductions in accGrad), and
+// 2.4 .. 2.9x from 80 on (one plane per workgroup, scalar gathers in the contraction).
+// Output tiles are (n - kh + 1) x (n - kw + 1).
+static double basis_weight(int n) {
+    return n <= 8 ? 1.6 : n <= 12 ? 1.2 : n <= 14 ? 1.1 : n <= 16 ? 1.05 : n <= 32 ? 1.0 : n <= 56 ? 1.1 : n <= 64 ? 1.2
+                                                                                          : n <= 112 ? 2.4 : 2.9;
+}
+static double basis_cost(int n, int h, int w, int kh, int kw) {
+    const int oh = h - kh + 1, ow = w - kw + 1, dy = n - kh + 1, dx = n - kw + 1;
+    const double tiles = (2.0 * ceil_div(oh, dy) * ceil_div(ow, dx) + (double)ceil_div(h, dy) * ceil_div(w, dx)) / 3.0;
+    return tiles * n * (n / 2 + 1) * basis_weight(n);
+}
 static int pick_tile_basis(int h, int w, int kh, int kw, double *cost_out = nullptr) {
-    const int oh = h - kh + 1, ow = w - kw + 1;
     int best = 0;
     double best_cost = 0;
     for (int n : kBases) {
         if (n < kh || n < kw) continue;
-        const double cost = (double)ceil_div(oh, n - kh + 1) * ceil_div(ow, n - kw + 1) * n * (n / 2 + 1) * basis_weight(n);
+        const double cost = basis_cost(n, h, w, kh, kw);
         if (!best || cost < best_cost) { best = n; best_cost = cost; }
     }
     if (cost_out) *cost_out = best_cost;
@@ -85,8 +95,8 @@ static int pick_tile_basis(int h, int w, int kh, int kw, double *cost_out = null
 
 // tile_n: -1 = the ordinary entry points: tile when the layer needs it (basis above 128) or
 // when the estimate says tiling is clearly cheaper (in practice the layers whose untiled basis
-// would be 128: measured 2..5x faster tiled at basis 32 or 64); 0 = tile with the library's
-// choice of basis; else tile with basis tile_n.
+// would be 80 or more: measured 2..5x faster tiled at a basis between 24 and 64); 0 = tile with
+// the library's choice of basis; else use basis tile_n, tiled unless it holds the whole image.
 // ph, pw: rows / columns of zeros around every input image (Section 2's p_h, p_w); the output
 // is then (h + 2 ph - kh + 1) x (w + 2 pw - kw + 1).  Padded layers always run on windows (a
 // single window per image when the padded image fits the basis): the padding is the part of
@@ -101,9 +111,12 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
     if (tile_n > 0 && (!basis_ok(tile_n) || tile_n < kh || tile_n < kw)) return FFTCONV_INVALID_ARG;
     int N = basis_size(hp, wp);
     bool tiled = tile_n >= 0 || ph > 0 || pw > 0;
+    // a named basis that holds the whole (unpadded) image: the ordinary untiled plan at that basis
+    const bool whole = tile_n > 0 && ph == 0 && pw == 0 && tile_n >= h && tile_n >= w;
+    if (whole) { tiled = false; N = tile_n; }
     if (tiled && tile_n < 0) tile_n = 0;
     if (N > 128) { tiled = true; if (tile_n < 0) tile_n = 0; }
-    if (!tiled) {
+    if (!tiled && !whole) {
         double cost = 0;
         const int tn = pick_tile_basis(hp, wp, kh, kw, &cost);
         if (tn && tn < N && cost < 0.8 * N * (N / 2 + 1) * basis_weight(N)) { tiled = true; tile_n = tn; }
@@ -402,6 +415,55 @@ int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, f
     return run_pass(hd, FFTCONV_ACCGRAD, gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, ws, ws_bytes, tile_n);
 }
 
+int fftconv_autotune_basis(fftconv_handle hd, const float *x, const float *wt, const float *gy,
+                           float *y, float *gx, float *gw, int S, int f, int fo, int h, int w, int kh, int kw,
+                           int reps, int *basis_out, float *ms_out) {
+    if (!hd || !x || !wt || !gy || !y || !gx || !gw || !basis_out || reps <= 0) return FFTCONV_INVALID_ARG;
+    *basis_out = 0;
+    PassPlan probe;
+    if (int st = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &probe, 0); st != FFTCONV_OK) return st;
+    // Candidates: every basis that holds the kernel and whose estimated cost is within 3x of
+    // the lowest estimate (the rest are far off and would only cost workspace and time).
+    double low = 0;
+    for (int n : kBases)
+        if (n >= kh && n >= kw) { const double c = basis_cost(n, h, w, kh, kw); if (low == 0 || c < low) low = c; }
+    hipEvent_t t0, t1;
+    if (hipEventCreate(&t0) != hipSuccess) return FFTCONV_HIP_ERROR;
+    if (hipEventCreate(&t1) != hipSuccess) { (void)hipEventDestroy(t0); return FFTCONV_HIP_ERROR; }
+    const int was_profiling = hd->profiling;
+    hd->profiling = 0;
+    int status = FFTCONV_OK, best = 0;
+    float best_ms = 0;
+    auto step = [&](int n) -> int {
+        int st;
+        if ((st = run_pass(hd, FFTCONV_FPROP, x, wt, y, S, f, fo, h, w, kh, kw, 1.0f, 0, nullptr, 0, n)) != FFTCONV_OK) return st;
+        if ((st = run_pass(hd, FFTCONV_BPROP, gy, wt, gx, S, f, fo, h, w, kh, kw, 1.0f, 0, nullptr, 0, n)) != FFTCONV_OK) return st;
+        return run_pass(hd, FFTCONV_ACCGRAD, gy, x, gw, S, f, fo, h, w, kh, kw, 1.0f, 0, nullptr, 0, n);
+    };
+    for (int n : kBases) {
+        if (n < kh || n < kw || basis_cost(n, h, w, kh, kw) > 3.0 * low) continue;
+        if ((status = step(n)) != FFTCONV_OK) break;                       // warm-up, grows the workspace
+        hipError_t e = hipEventRecord(t0, hd->stream);
+        for (int r = 0; r < reps && status == FFTCONV_OK; ++r) status = step(n);
+        if (status != FFTCONV_OK) break;
+        if (e == hipSuccess) e = hipEventRecord(t1, hd->stream);
+        if (e == hipSuccess) e = hipEventSynchronize(t1);
+        float ms = 0;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+        if (e != hipSuccess) { status = hip_fail(hd, e); break; }
+        ms /= (float)reps;
+        if (!best || ms < best_ms) { best = n; best_ms = ms; }
+    }
+    hd->profiling = was_profiling;
+    (void)hipEventDestroy(t0); (void)hipEventDestroy(t1);
+    if (status != FFTCONV_OK) return status;
+    // leave the outputs as the chosen basis computes them
+    if ((status = step(best)) != FFTCONV_OK) return status;
+    *basis_out = best;
+    if (ms_out) *ms_out = best_ms;
+    return FFTCONV_OK;
+}
+
 size_t fftconv_padded_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int kh, int kw,
                                       int pad_h, int pad_w) {
     PassPlan p;
@@ -485,9 +547,9 @@ int fftconv_last_kernel_ms(fftconv_handle h, float *ms_out, int capacity, int *c
     return FFTCONV_OK;
 }
 
-static size_t saved_bytes_impl(int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw) {
+static size_t saved_bytes_impl(int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw, int tile_n = -1) {
     PassPlan p;
-    if (make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, -1, ph, pw) != FFTCONV_OK) return 0;
+    if (make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw) != FFTCONV_OK) return 0;
     return saved_plan(p).total;
 }
 
@@ -497,6 +559,10 @@ size_t fftconv_saved_bytes(int S, int f, int fo, int h, int w, int kh, int kw) {
 
 size_t fftconv_saved_bytes_padded(int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w) {
     return saved_bytes_impl(S, f, fo, h, w, kh, kw, pad_h, pad_w);
+}
+
+size_t fftconv_saved_bytes_tiled(int S, int f, int fo, int h, int w, int kh, int kw, int tile_n) {
+    return tile_n < 0 ? 0 : saved_bytes_impl(S, f, fo, h, w, kh, kw, 0, 0, tile_n);
 }
 
 // Workspace of fft_conv_backward: [GYF for bprop | GYF for accGrad (tiled layers only: the two
@@ -517,10 +583,11 @@ static BackwardPlan backward_plan(const PassPlan &pb, const PassPlan &pa) {
     return b;
 }
 
-static size_t backward_workspace_impl(int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw) {
+static size_t backward_workspace_impl(int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw,
+                                      int tile_n = -1) {
     PassPlan pb, pa;
-    if (make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, -1, ph, pw) != FFTCONV_OK) return 0;
-    if (make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, -1, ph, pw) != FFTCONV_OK) return 0;
+    if (make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, tile_n, ph, pw) != FFTCONV_OK) return 0;
+    if (make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, tile_n, ph, pw) != FFTCONV_OK) return 0;
     return backward_plan(pb, pa).total;
 }
 
@@ -533,14 +600,18 @@ size_t fftconv_backward_workspace_bytes_padded(int S, int f, int fo, int h, int 
     return backward_workspace_impl(S, f, fo, h, w, kh, kw, pad_h, pad_w);
 }
 
+size_t fftconv_backward_workspace_bytes_tiled(int S, int f, int fo, int h, int w, int kh, int kw, int tile_n) {
+    return tile_n < 0 ? 0 : backward_workspace_impl(S, f, fo, h, w, kh, kw, 0, 0, tile_n);
+}
+
 }  // extern "C"
 
 static int fprop_save_impl(fftconv_handle hd, const float *x, const float *wt, float *y,
                            int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw,
-                           void *saved, size_t saved_bytes, void *ws, size_t ws_bytes) {
+                           void *saved, size_t saved_bytes, void *ws, size_t ws_bytes, int tile_n = -1) {
     if (!hd || !x || !wt || !y || !saved) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, -1, ph, pw);
+    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw);
     if (rc != FFTCONV_OK) return rc;
     const SavedPlan sp = saved_plan(p);
     if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
@@ -557,13 +628,13 @@ static int fprop_save_impl(fftconv_handle hd, const float *x, const float *wt, f
 static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *gw,
                          int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw,
                          float scale, int accumulate, const void *saved, size_t saved_bytes,
-                         void *ws, size_t ws_bytes) {
+                         void *ws, size_t ws_bytes, int tile_n = -1) {
     if (!hd || !gy || !saved || (!gx && !gw)) return FFTCONV_INVALID_ARG;
     PassPlan pf, pb, pa;
-    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &pf, -1, ph, pw);
+    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &pf, tile_n, ph, pw);
     if (rc != FFTCONV_OK) return rc;
-    (void)make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, -1, ph, pw);
-    (void)make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, -1, ph, pw);
+    (void)make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, tile_n, ph, pw);
+    (void)make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, tile_n, ph, pw);
     const SavedPlan sp = saved_plan(pf);
     if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
     const BackwardPlan bp = backward_plan(pb, pa);
@@ -634,6 +705,22 @@ int fft_conv_backward_padded(fftconv_handle hd, const float *gy, float *gx, floa
                              void *ws, size_t ws_bytes) {
     return backward_impl(hd, gy, gx, gw, S, f, fo, h, w, kh, kw, pad_h, pad_w, scale, accumulate, saved,
                          saved_bytes, ws, ws_bytes);
+}
+
+int fft_conv_fprop_save_tiled(fftconv_handle hd, const float *x, const float *wt, float *y,
+                              int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                              void *saved, size_t saved_bytes, void *ws, size_t ws_bytes) {
+    if (tile_n < 0) return FFTCONV_INVALID_ARG;
+    return fprop_save_impl(hd, x, wt, y, S, f, fo, h, w, kh, kw, 0, 0, saved, saved_bytes, ws, ws_bytes, tile_n);
+}
+
+int fft_conv_backward_tiled(fftconv_handle hd, const float *gy, float *gx, float *gw,
+                            int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                            float scale, int accumulate, const void *saved, size_t saved_bytes,
+                            void *ws, size_t ws_bytes) {
+    if (tile_n < 0) return FFTCONV_INVALID_ARG;
+    return backward_impl(hd, gy, gx, gw, S, f, fo, h, w, kh, kw, 0, 0, scale, accumulate, saved, saved_bytes, ws,
+                         ws_bytes, tile_n);
 }
 
 }  // extern "C"

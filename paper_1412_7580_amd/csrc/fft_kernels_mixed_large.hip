@@ -2,11 +2,11 @@
 // per-lane part of the line), and the dispatch of every size that is not a power of two.
 #include "fft_kernels_impl.hpp"
 
-#include <cstdlib>
-
 namespace fc {
 
-#define FC_ALT(name) (getenv(name) != nullptr)
+// Lanes per line, measured on 64-channel layers of 11x11 ... 54x54 images: the forward
+// transforms like long per-lane parts (one lane per line up to 14, two up to 28, four up to 56),
+// the inverses shorter ones, as for the powers of two.
 
 hipError_t launch_fft2d_r2c_multi_small(const FwdOperand *ops, int nops, int N, LaunchCtx st);
 hipError_t launch_fft2d_r2c_small(const float *in, float *out, long planes, int h_in, int w_in, int N,
@@ -16,9 +16,9 @@ hipError_t launch_fft2d_c2r_small(const float *in, float *out, long planes, int 
 
 hipError_t launch_fft2d_r2c_multi_mixed(const FwdOperand *ops, int nops, int N, LaunchCtx st) {
     switch (N) {
-        case 40: return FC_ALT("FFTCONV_ALT40") ? run_fwd2d_multi<5, 8, 4>(ops, nops, st) : run_fwd2d_multi<10, 4, 4>(ops, nops, st);
-        case 48: return FC_ALT("FFTCONV_ALT48") ? run_fwd2d_multi<6, 8, 4>(ops, nops, st) : run_fwd2d_multi<12, 4, 4>(ops, nops, st);
-        case 56: return FC_ALT("FFTCONV_ALT56") ? run_fwd2d_multi<7, 8, 4>(ops, nops, st) : run_fwd2d_multi<14, 4, 4>(ops, nops, st);
+        case 40: return run_fwd2d_multi<10, 4, 4>(ops, nops, st);
+        case 48: return run_fwd2d_multi<12, 4, 4>(ops, nops, st);
+        case 56: return run_fwd2d_multi<14, 4, 4>(ops, nops, st);
         case 80: return run_fwd2d_multi<10, 8, 1>(ops, nops, st);
         case 96: return run_fwd2d_multi<12, 8, 1>(ops, nops, st);
         case 112: return run_fwd2d_multi<14, 8, 1>(ops, nops, st);
@@ -29,9 +29,9 @@ hipError_t launch_fft2d_r2c_multi_mixed(const FwdOperand *ops, int nops, int N, 
 hipError_t launch_fft2d_r2c_mixed(const float *in, float *out, long planes, int h_in, int w_in, int N,
                                   bool conv, LaunchCtx st, const PlaneView *view) {
     switch (N) {
-        case 40: return FC_ALT("FFTCONV_ALT40") ? run_fwd2d<5, 8, 4>(in, out, planes, h_in, w_in, conv, st, view) : run_fwd2d<10, 4, 4>(in, out, planes, h_in, w_in, conv, st, view);
-        case 48: return FC_ALT("FFTCONV_ALT48") ? run_fwd2d<6, 8, 4>(in, out, planes, h_in, w_in, conv, st, view) : run_fwd2d<12, 4, 4>(in, out, planes, h_in, w_in, conv, st, view);
-        case 56: return FC_ALT("FFTCONV_ALT56") ? run_fwd2d<7, 8, 4>(in, out, planes, h_in, w_in, conv, st, view) : run_fwd2d<14, 4, 4>(in, out, planes, h_in, w_in, conv, st, view);
+        case 40: return run_fwd2d<10, 4, 4>(in, out, planes, h_in, w_in, conv, st, view);
+        case 48: return run_fwd2d<12, 4, 4>(in, out, planes, h_in, w_in, conv, st, view);
+        case 56: return run_fwd2d<14, 4, 4>(in, out, planes, h_in, w_in, conv, st, view);
         case 80: return run_fwd2d<10, 8, 1>(in, out, planes, h_in, w_in, conv, st, view);
         case 96: return run_fwd2d<12, 8, 1>(in, out, planes, h_in, w_in, conv, st, view);
         case 112: return run_fwd2d<14, 8, 1>(in, out, planes, h_in, w_in, conv, st, view);
@@ -42,9 +42,9 @@ hipError_t launch_fft2d_r2c_mixed(const float *in, float *out, long planes, int 
 hipError_t launch_fft2d_c2r_mixed(const float *in, float *out, long planes, int N, int h_out, int w_out,
                                   bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view) {
     switch (N) {
-        case 40: return FC_ALT("FFTCONV_IALT40") ? run_inv2d<10, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view) : run_inv2d<5, 8, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
-        case 48: return FC_ALT("FFTCONV_IALT48") ? run_inv2d<12, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view) : run_inv2d<6, 8, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
-        case 56: return FC_ALT("FFTCONV_IALT56") ? run_inv2d<14, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view) : run_inv2d<7, 8, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 40: return run_inv2d<10, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 48: return run_inv2d<12, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 56: return run_inv2d<14, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 80: return run_inv2d<10, 8, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 96: return run_inv2d<12, 8, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 112: return run_inv2d<14, 8, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);

@@ -164,3 +164,61 @@ def test_tiled_is_deterministic(hd):
     a = hd.fft_conv_bprop_tiled(dgy, dw, cfg["h"], cfg["w"], 16).clone()
     b = hd.fft_conv_bprop_tiled(dgy, dw, cfg["h"], cfg["w"], 16)
     assert bool((a == b).all())
+
+
+BASES = (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128)
+
+
+@pytest.mark.parametrize("n", [28, 32, 40, 56])
+def test_named_basis_that_holds_the_image(hd, n):
+    """tile_n >= max(h, w): the untiled pipeline at that basis (three frequency tensors, one
+    transform per plane), for all three passes."""
+    cfg = dict(S=3, f=5, fo=4, h=27, w=25, kh=5, kw=4)
+    x, w, gy = synth.conv_inputs(seed=310, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    assert _relerr(_np(hd.fft_conv_fprop_tiled(dx, dw, n)), oracle.conv_fprop(x, w)) <= TOL
+    assert _relerr(_np(hd.fft_conv_bprop_tiled(dgy, dw, 27, 25, n)), oracle.conv_bprop(gy, w, 27, 25)) <= TOL
+    assert _relerr(_np(hd.fft_conv_accgrad_tiled(dx, dgy, n)), oracle.conv_accgrad(x, gy)) <= TOL
+    T = {28: 16, 32: 16, 40: 4, 56: 4}[n]
+    bins = {28: 424, 32: 544, 40: 864, 56: 1632}[n]     # n * (n/2 + 1), padded to the layout's unit
+    pad = lambda planes: -(-planes // T) * T
+    assert hd.tiled_workspace_bytes(0, 3, 5, 4, 27, 25, 5, 4, n) == (pad(15) + pad(20) + pad(12)) * bins * 2 * 4
+
+
+def test_autotune_basis(hd):
+    """The measured choice is one of the candidate bases, and the outputs left behind are the
+    chosen basis's results (checked against the oracle and against the tiled calls)."""
+    import torch
+    cfg = dict(S=4, f=8, fo=8, h=30, w=26, kh=3, kw=5)
+    x, w, gy = synth.conv_inputs(seed=311, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    y, gx, gw = torch.empty_like(dgy), torch.empty_like(dx), torch.empty_like(dw)
+    n, ms = hd.autotune_basis(dx, dw, dgy, y=y, gx=gx, gw=gw, reps=2)
+    assert n in BASES and n >= 5 and ms > 0
+    assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
+    assert _relerr(_np(gx), oracle.conv_bprop(gy, w, 30, 26)) <= TOL
+    assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
+    assert torch.equal(y, hd.fft_conv_fprop_tiled(dx, dw, n))
+    assert torch.equal(gx, hd.fft_conv_bprop_tiled(dgy, dw, 30, 26, n))
+    assert torch.equal(gw, hd.fft_conv_accgrad_tiled(dx, dgy, n))
+
+
+@pytest.mark.parametrize("cfg,n", [(dict(S=3, f=4, fo=5, h=27, w=27, kh=5, kw=5), 32),     # named basis, untiled
+                                   (dict(S=3, f=4, fo=5, h=27, w=27, kh=5, kw=5), 28),
+                                   (dict(S=2, f=3, fo=4, h=45, w=50, kh=3, kw=5), 24)])    # tiled
+def test_reuse_pair_on_a_named_basis(hd, cfg, n):
+    """fft_conv_fprop_save_tiled + fft_conv_backward_tiled equal the three tiled passes."""
+    import torch
+    x, w, gy = synth.conv_inputs(seed=312, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes_tiled(*dims, n) // 4, device="cuda")
+    assert saved.numel() > 0 and hd.backward_workspace_bytes_tiled(*dims, n) > 0
+    y = hd.fft_conv_fprop_save_tiled(dx, dw, n, saved)
+    gx, gw = hd.fft_conv_backward_tiled(dgy, saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"], n)
+    assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
+    assert _relerr(_np(gx), oracle.conv_bprop(gy, w, cfg["h"], cfg["w"])) <= TOL
+    assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
+    assert torch.equal(y, hd.fft_conv_fprop_tiled(dx, dw, n))
+    with pytest.raises(Exception, match="workspace too small"):
+        hd.fft_conv_fprop_save_tiled(dx, dw, n, saved[:-64])
