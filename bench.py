@@ -232,15 +232,18 @@ def cpu_baseline(cfg, host_inputs, budget_s=12.0):
             "kind": "oracle", "sample": "fp64 direct convolution oracle; " + "; ".join(parts)}
 
 
-def fft_sweep(hd, max_bytes=1 << 28, reps=3):
-    """Stand-alone FFT sweep: R2C then C2R, input sized to 256 MiB, algorithmic GB/s."""
+def fft_sweep(hd, max_bytes=1 << 28, reps=3, sizes=None, sizes_1d_only=(256,)):
+    """Stand-alone FFT sweep: R2C then C2R of signals of n - 3 samples, input sized to 256 MiB,
+    algorithmic GB/s.  Default sizes: those of the benchmark definition (8 ... 128) plus n = 256
+    in 1-D, one size beyond it."""
     import torch
     from paper_1412_7580_amd import synth
+    sizes = synth.FFT_SWEEP_SIZES if sizes is None else sizes
     out = {}
     for dim in (1, 2):
-        for n in synth.FFT_SWEEP_SIZES:
-            B = synth.fft_sweep_batch(dim, n, max_bytes)
+        for n in tuple(sizes) + (tuple(sizes_1d_only) if dim == 1 else ()):
             ni = n - 3
+            B = max_bytes // (4 * ni ** dim)
             shape = (B, ni) if dim == 1 else (B, ni, ni)
             x = torch.randn(shape, device="cuda", dtype=torch.float32)
             nbins = (n // 2 + 1) * (1 if dim == 1 else n)
@@ -261,23 +264,6 @@ def fft_sweep(hd, max_bytes=1 << 28, reps=3):
                 res[name] = {"ms": round(ms, 4), "GBps": round(byts / ms / 1e6, 1)}
             out[f"{dim}d_n{n}"] = res
             del x, X, y
-    # one size beyond the sweep of the benchmark definition: 1-D n = 256 (signals of 253)
-    n, ni = 256, 253
-    B = max_bytes // (4 * ni)
-    x = torch.randn((B, ni), device="cuda", dtype=torch.float32)
-    X = torch.empty((B, n // 2 + 1, 2), device="cuda")
-    y = torch.empty_like(x)
-    res = {}
-    for name, fn in (("r2c", lambda: hd.fft_r2c_1d(x, n, out=X)), ("c2r", lambda: hd.fft_c2r_1d(X, n, ni, out=y))):
-        fn(); torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record(); torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        res[name] = {"ms": round(ms, 4), "GBps": round(B * (4 * ni + 8 * (n // 2 + 1)) / ms / 1e6, 1)}
-    out["1d_n256"] = res
     return out
 
 
@@ -569,6 +555,10 @@ def main():
         extra["tiled_layers"] = tiled_layers(hd)
         torch.cuda.empty_cache()
         extra["fft_sweep_256MiB"] = fft_sweep(hd)
+        torch.cuda.empty_cache()
+        # the sizes with an odd factor (not part of the benchmark definition's sweep)
+        extra["fft_sweep_mixed_sizes_256MiB"] = fft_sweep(hd, sizes=(12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112),
+                                                          sizes_1d_only=(160, 192, 224))
         out["extra"] = extra
     print(json.dumps(out))
 
