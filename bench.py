@@ -396,6 +396,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the FFT sweep")
     ap.add_argument("--tiled-only", action="store_true",
                     help="only time the tiled layers of the extra block and print them (for profiling runs)")
+    ap.add_argument("--sweep-only", default=None, metavar="SIZES",
+                    help="only run the stand-alone FFT sweep at these comma-separated sizes and print it "
+                         "(for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy a few times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -422,6 +425,10 @@ def main():
     hd = pkg.Handle(0)
     if args.tiled_only:
         print(json.dumps({"tiled_layers": tiled_layers(hd)}))
+        return
+    if args.sweep_only:
+        sizes = tuple(int(v) for v in args.sweep_only.split(","))
+        print(json.dumps({"fft_sweep_256MiB": fft_sweep(hd, sizes=sizes, sizes_1d_only=())}))
         return
     name = args.workload
     cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k != "passes"}

@@ -23,17 +23,25 @@ __device__ __forceinline__ unsigned mdiv(unsigned x, MagicDiv md) {
     return (unsigned)(((unsigned long long)x * md.m) >> 32);
 }
 
+// Floats by which a global address lies past a 16-byte boundary (0..3).
+__device__ __forceinline__ unsigned misalign4(const float *p) { return (unsigned)(((size_t)p >> 2) & 3); }
+
 // Copy `total` contiguous floats from global memory into LDS at the same offsets.  Loads are
 // issued in batches of U per lane before any LDS store so that many are in flight at once;
-// 16-byte loads are used when `vec_ok` (base pointer and block start are 16-byte aligned).
+// 16-byte loads are used when `vec_ok`: dst and src lie equally far past a 16-byte boundary
+// (the caller shifts its LDS image by misalign4(src)); the up to 3 floats before the first
+// boundary and after the last one are copied singly.
 template <int BT, int U = 8>
 __device__ __forceinline__ void stage_linear(float *dst, const float *src, unsigned total, int tid,
                                              bool vec_ok) {
     unsigned done = 0;
     if (vec_ok) {
-        const unsigned total4 = total >> 2;
-        const float4 *s4 = reinterpret_cast<const float4 *>(src);
-        float4 *d4 = reinterpret_cast<float4 *>(dst);
+        unsigned head = (4 - misalign4(src)) & 3;
+        if (head > total) head = total;
+        if ((unsigned)tid < head) dst[tid] = src[tid];
+        const unsigned total4 = (total - head) >> 2;
+        const float4 *s4 = reinterpret_cast<const float4 *>(src + head);
+        float4 *d4 = reinterpret_cast<float4 *>(dst + head);
         for (unsigned base = tid; base < total4; base += BT * U) {
             float4 v[U];
 #pragma unroll
@@ -48,7 +56,7 @@ __device__ __forceinline__ void stage_linear(float *dst, const float *src, unsig
                 if (i < total4) d4[i] = v[u];
             }
         }
-        done = total4 << 2;
+        done = head + (total4 << 2);
     }
     for (unsigned base = done + tid; base < total; base += BT * U) {
         float v[U];
@@ -66,17 +74,21 @@ __device__ __forceinline__ void stage_linear(float *dst, const float *src, unsig
     }
 }
 
-// Copy `total` floats from LDS to contiguous global memory (optionally accumulating).
+// Copy `total` floats from LDS to contiguous global memory (optionally accumulating); vec_ok
+// as for stage_linear, with the roles of dst and src exchanged.
 template <int BT>
 __device__ __forceinline__ void unstage_linear(float *dst, const float *src, unsigned total, int tid,
                                                bool vec_ok, bool accumulate) {
     unsigned done = 0;
     if (vec_ok && !accumulate) {
-        const unsigned total4 = total >> 2;
-        const float4 *s4 = reinterpret_cast<const float4 *>(src);
-        float4 *d4 = reinterpret_cast<float4 *>(dst);
+        unsigned head = (4 - misalign4(dst)) & 3;
+        if (head > total) head = total;
+        if ((unsigned)tid < head) dst[tid] = src[tid];
+        const unsigned total4 = (total - head) >> 2;
+        const float4 *s4 = reinterpret_cast<const float4 *>(src + head);
+        float4 *d4 = reinterpret_cast<float4 *>(dst + head);
         for (unsigned i = tid; i < total4; i += BT) d4[i] = s4[i];
-        done = total4 << 2;
+        done = head + (total4 << 2);
     }
     if (accumulate) {
         for (unsigned i = done + tid; i < total; i += BT) dst[i] += src[i];
@@ -228,7 +240,7 @@ struct Fwd2dParams {
     int vecw;                 // floats per staging load when the image is padded: 4, 2 or 1
     FreqLayout lay;
     int linear;       // staged planes need no padding: LDS image == global image
-    int vec_ok;       // input base and every block start are 16-byte aligned
+    int vec_ok;       // (unused by the linear staging, which adapts to the block's alignment)
     int out_vec_ok;   // output base and every block start are 16-byte aligned
     int tiled;        // planes are windows of images (view); origin table at LDS float info_off
     int info_off;
@@ -284,7 +296,8 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
     } else {
         const float *src = prm.in + p0 * hw;
         if (prm.linear) {
-            stage_linear<BT>(sin, src, (unsigned)np * hw, tid, prm.vec_ok != 0);
+            sin = smem + misalign4(src);   // the LDS image shares the block's 16-byte phase
+            stage_linear<BT>(sin, src, (unsigned)np * hw, tid, true);
         } else {
             const unsigned rows = (unsigned)np * h_in;
             if (prm.vecw == 4)
@@ -450,7 +463,7 @@ struct Inv2dParams {
     FreqLayout lay;
     float scale;
     int accumulate;
-    int vec_ok;       // output base and every block start are 16-byte aligned
+    int vec_ok;       // tiled outputs: the windows can be scattered with 16-byte stores
     int in_vec_ok;    // natural layout only: input base is 16-byte aligned
     int tiled;        // outputs are windows of images (view); origin table at LDS float info_off
     int info_off;
@@ -464,10 +477,13 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
     extern __shared__ float smem[];
     float2 *mid = reinterpret_cast<float2 *>(smem);
-    float *sout = smem;
 
     const int tid = threadIdx.x;
     const long p0 = (long)blockIdx.x * T;
+    // the output block assembled in LDS shares the 16-byte phase of its place in global memory
+    // (contiguous outputs only; scattered windows keep an aligned image)
+    float *sout = smem;
+    if (!(CONV && prm.tiled)) sout += misalign4(prm.out + p0 * (long)prm.h_out * prm.w_out);
     const long left = prm.planes - p0;
     const int np = left < T ? (int)left : T;
     const int h_out = prm.h_out, w_out = prm.w_out;
@@ -588,7 +604,7 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
     {
         float *dst = prm.out + p0 * (long)h_out * w_out;
         const unsigned total = (unsigned)np * h_out * w_out;
-        unstage_linear<BT>(dst, sout, total, tid, prm.vec_ok != 0, prm.accumulate != 0);
+        unstage_linear<BT>(dst, sout, total, tid, true, prm.accumulate != 0);
     }
 }
 
@@ -900,7 +916,7 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     prm.vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * h_out * w_out) % 4 == 0) ? 1 : 0;
     if (view) prm.vec_ok = tiled_vec ? 1 : 0;   // tiled: 16-byte scatter of the windows
     prm.in_vec_ok = (((size_t)in & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
-    const size_t a = (size_t)T * prm.MPS * sizeof(float2), b = (size_t)T * h_out * w_out * sizeof(float);
+    const size_t a = (size_t)T * prm.MPS * sizeof(float2), b = ((size_t)T * h_out * w_out + 3) * sizeof(float);
     size_t lds = a > b ? a : b;
     // Stage the block's (contiguous) input through LDS with 16-byte loads: always for the
     // natural layout; for the plane-tiled layout it measured faster except for the small
