@@ -395,12 +395,24 @@ __global__ void __launch_bounds__(256, 3) cgemm_tail_kernel(GemmParams prm) {
 // problem's workgroups fill the slots that the first one's stragglers leave idle.
 struct GemmPairParams {
     GemmParams p1, p2;
-    unsigned n1;
+    unsigned n1;       // workgroups of p1
+    unsigned split2;   // p2's workgroups from this number on are cut into quadrants (as in
+                       // cgemm_tail_kernel); equal to p2's workgroup count when none are
 };
 template <bool AKF1, bool BKF1, bool AKF2, bool BKF2>
 __global__ void __launch_bounds__(256, 3) cgemm_pair_kernel(GemmPairParams pp) {
-    if (blockIdx.x < pp.n1) cgemm_bins_body<2, 2, 1, 1, 16, AKF1, BKF1, true, 1>(pp.p1, blockIdx.x);
-    else cgemm_bins_body<2, 2, 1, 1, 16, AKF2, BKF2, true, 1>(pp.p2, blockIdx.x - pp.n1);
+    if (blockIdx.x < pp.n1) {
+        cgemm_bins_body<2, 2, 1, 1, 16, AKF1, BKF1, true, 1>(pp.p1, blockIdx.x);
+        return;
+    }
+    const unsigned b = blockIdx.x - pp.n1;
+    if (b < pp.split2) {
+        cgemm_bins_body<2, 2, 1, 1, 16, AKF2, BKF2, true, 1>(pp.p2, b);
+    } else {
+        const unsigned r = b - pp.split2;
+        const unsigned x = r % kXcds, u = r / kXcds;
+        cgemm_quadrant_body<16, AKF2, BKF2, 2>(pp.p2, pp.split2 + kXcds * (u / 4) + x, (int)(u % 4));
+    }
 }
 
 template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int MINB, int PD = 1>
@@ -551,10 +563,18 @@ static hipError_t run_pair(GemmPairParams &pp, LaunchCtx st) {
     const long n1 = (long)pp.p1.bins * pp.p1.tiles_m * pp.p1.tiles_n;
     const long n2 = (long)pp.p2.bins * pp.p2.tiles_m * pp.p2.tiles_n;
     pp.n1 = (unsigned)n1;     // a multiple of the XCD count, as bins is
-    const size_t lds = (size_t)(2 * 2 * TK * (TM + 2) + 2 * 2 * TK * (TN + 2)) * sizeof(float);
+    // a short last round (at most a quarter of the resident workgroups), all of it p2's: split
+    // its tiles into quadrants (the 27x27 layer on basis 28: 424 + 848 workgroups, 248 left over)
+    const long slots = resident_workgroups(), rem = (n1 + n2) % slots, full = n1 + n2 - rem;
+    long split = n2;
+    if (!getenv("FFTCONV_GEMM_NO_TAIL") && full > 0 && rem > 0 && 4 * rem <= slots && rem <= n2 && rem % kXcds == 0 &&
+        (n2 - rem) % kXcds == 0)
+        split = n2 - rem;
+    pp.split2 = (unsigned)split;
+    const size_t lds = (size_t)(2 * 2 * TK * (TM + 2) + 2 * 2 * TK * (TN + 2)) * sizeof(float);   // >= the quadrant's
     auto k = cgemm_pair_kernel<AKF1, BKF1, AKF2, BKF2>;
     if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
-    launch_kernel(k, dim3((unsigned)(n1 + n2)), dim3(256), lds, st, pp);
+    launch_kernel(k, dim3((unsigned)(n1 + split + 4 * (n2 - split))), dim3(256), lds, st, pp);
     return hipGetLastError();
 }
 
