@@ -7,7 +7,7 @@ import pytest
 import oracle
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
-SIZES = [8, 16, 32, 64, 128]
+SIZES = [8, 12, 14, 16, 20, 28, 32, 56, 64, 96, 128]   # powers of two and sizes with a factor 3, 5 or 7
 
 
 def test_closed_forms_from_fixture():
@@ -65,7 +65,7 @@ def test_c2r_ignores_imag_of_self_conjugate_bins():
     np.testing.assert_allclose(oracle.idft_c2r_1d(Y, n, n), oracle.idft_c2r_1d(X, n, n), atol=1e-14)
 
 
-@pytest.mark.parametrize("n", [8, 16])
+@pytest.mark.parametrize("n", [8, 12, 14, 16])
 def test_2d_vs_bruteforce_and_hermitian(n):
     rng = np.random.default_rng(20 + n)
     x = rng.standard_normal((n, n))
@@ -102,7 +102,10 @@ def test_2d_axis_order():
     np.testing.assert_allclose(X, e, atol=1e-11)
 
 
-@pytest.mark.parametrize("h,wd,kh,kw,N", [(7, 7, 3, 3, 8), (13, 13, 3, 3, 16), (8, 6, 5, 2, 8), (16, 16, 9, 9, 16)])
+# the basis only has to hold the image: 13x13 on 14 and 27x25 on 28 (the bprop result then fills
+# the basis up to its last row) as well as the powers of two
+@pytest.mark.parametrize("h,wd,kh,kw,N", [(7, 7, 3, 3, 8), (13, 13, 3, 3, 16), (8, 6, 5, 2, 8), (16, 16, 9, 9, 16),
+                                          (13, 13, 3, 3, 14), (27, 25, 5, 4, 28), (12, 12, 5, 5, 12)])
 def test_convolution_theorem_all_passes(h, wd, kh, kw, N):
     """Section 2's frequency-domain identity, and the two 'similar' forms for
     bprop (no conjugate) and accGrad (conjugate on the gradient), checked
