@@ -5,8 +5,9 @@
 namespace fc {
 
 // Lanes per line, measured on 64-channel layers of 11x11 ... 54x54 images: the forward
-// transforms like long per-lane parts (one lane per line up to 14, two up to 28, four up to 56),
-// the inverses shorter ones, as for the powers of two.
+// transforms like long per-lane parts (one lane per line up to 28, e.g. basis 20: 13.7 us
+// against 18.1 with lane pairs; four lanes from 40 to 56), the inverses mostly shorter ones, as
+// for the powers of two.
 
 hipError_t launch_fft2d_r2c_multi_small(const FwdOperand *ops, int nops, int N, LaunchCtx st);
 hipError_t launch_fft2d_r2c_small(const float *in, float *out, long planes, int h_in, int w_in, int N,

@@ -6,16 +6,24 @@
 namespace fc {
 
 // Lanes per line, measured on 64-channel layers of 11x11 ... 54x54 images: the forward
-// transforms like long per-lane parts (one lane per line up to 14, two up to 28, four up to 56),
-// the inverses shorter ones, as for the powers of two.
+// transforms like long per-lane parts (one lane per line up to 28, e.g. basis 20: 13.7 us
+// against 18.1 with lane pairs; four lanes from 40 to 56), the inverses mostly shorter ones, as
+// for the powers of two.
 
 hipError_t launch_fft2d_r2c_multi_small(const FwdOperand *ops, int nops, int N, LaunchCtx st) {
     switch (N) {
         case 12: return run_fwd2d_multi<12, 1, 32>(ops, nops, st);
         case 14: return run_fwd2d_multi<14, 1, 32>(ops, nops, st);
-        case 20: return run_fwd2d_multi<10, 2, 16>(ops, nops, st);
-        case 24: return run_fwd2d_multi<12, 2, 16>(ops, nops, st);
-        case 28: return run_fwd2d_multi<14, 2, 16>(ops, nops, st);
+        case 20: {
+            // one lane per line on grids of a few rounds of workgroups (18x18 layer: 13.7 us against
+            // 18.1), lane pairs on large tiled grids (224x224 in 16x16 tiles: 547 us against 616)
+            long planes = 0;
+            for (int o = 0; o < nops; ++o) planes += ops[o].planes;
+            if (planes > 32768) return run_fwd2d_multi<10, 2, 16>(ops, nops, st);
+            return run_fwd2d_multi<20, 1, 16>(ops, nops, st);
+        }
+        case 24: return run_fwd2d_multi<24, 1, 16>(ops, nops, st);
+        case 28: return run_fwd2d_multi<28, 1, 16>(ops, nops, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -25,9 +33,16 @@ hipError_t launch_fft2d_r2c_small(const float *in, float *out, long planes, int 
     switch (N) {
         case 12: return run_fwd2d<12, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
         case 14: return run_fwd2d<14, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
-        case 20: return run_fwd2d<10, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);
-        case 24: return run_fwd2d<12, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);
-        case 28: return run_fwd2d<14, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);
+        // (the natural layout, whose batches are large, keeps lane pairs: 4.9 against 4.7 TB/s at 28)
+        case 20:
+            if (!conv || planes > 32768) return run_fwd2d<10, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);
+            return run_fwd2d<20, 1, 16>(in, out, planes, h_in, w_in, conv, st, view);
+        case 24:
+            if (!conv) return run_fwd2d<12, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);
+            return run_fwd2d<24, 1, 16>(in, out, planes, h_in, w_in, conv, st, view);
+        case 28:
+            if (!conv) return run_fwd2d<14, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);
+            return run_fwd2d<28, 1, 16>(in, out, planes, h_in, w_in, conv, st, view);
         default: return hipErrorInvalidValue;
     }
 }
@@ -37,13 +52,15 @@ hipError_t launch_fft2d_c2r_small(const float *in, float *out, long planes, int 
     switch (N) {
         case 12: return run_inv2d<3, 4, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 14: return run_inv2d<7, 2, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
-        case 20: return run_inv2d<10, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 20:
+            if (!conv) return run_inv2d<10, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+            return run_inv2d<20, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 24: return run_inv2d<6, 4, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 28:
-            // lane pairs when nearly all rows are kept (27x27 input gradients: 13.9 us against 14.7),
-            // four lanes per line otherwise (5x5 weight gradients: 6.5 against 6.8)
+            // one lane per line when nearly all rows are kept (27x27 input gradients: 13.5 us
+            // against 14.1), four otherwise (5x5 weight gradients: 6.6 against 8.0)
             if (conv && 4 * (h_out + (view ? view->oy : 0)) > 3 * 28)
-                return run_inv2d<14, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+                return run_inv2d<28, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
             return run_inv2d<7, 4, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         default: return hipErrorInvalidValue;
     }
