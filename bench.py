@@ -381,6 +381,47 @@ def tiled_layers(hd, reps=10):
     return out
 
 
+def table4_layers(hd, reps=10):
+    """The five layer shapes of the paper's Table 4 (S = 128) on synthetic inputs, three
+    independent passes each with the library's own choice of basis / tiling, next to the times
+    the paper prints for its cuFFT-based implementation on a Tesla K40m (context: another
+    machine, another decade; not a target)."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    layers = {   # name: (f, f', h = w, k, paper's cuFFT-convolution ms for fprop, bprop, accGrad)
+        "L1": (3, 96, 128, 11, (80.98, 66.49, 69.63)),
+        "L2": (64, 64, 64, 9, (46.44, 46.25, 47.03)),
+        "L3": (128, 128, 32, 9, (17.77, 16.97, 17.00)),
+        "L4": (128, 128, 16, 7, (4.88, 4.71, 4.70)),
+        "L5": (384, 384, 13, 3, (21.35, 20.22, 21.26)),
+    }
+    out = {}
+    S = 128
+    for name, (f, fo, h, k, paper_ms) in layers.items():
+        mk = lambda *shape: torch.rand(shape, device="cuda", generator=gen) * 2 - 1
+        x, wt, gy = mk(S, f, h, h), mk(fo, f, k, k), mk(S, fo, h - k + 1, h - k + 1)
+        y, gx, gw = torch.empty_like(gy), torch.empty_like(x), torch.empty_like(wt)
+        calls = (lambda: hd.fft_conv_fprop(x, wt, y=y), lambda: hd.fft_conv_bprop(gy, wt, h, h, gx=gx),
+                 lambda: hd.fft_conv_accgrad(x, gy, gw=gw))
+        ms = []
+        for fn in calls:
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            ms.append((time.perf_counter() - t0) / reps * 1e3)
+        fl = 2.0 * S * f * fo * k * k * (h - k + 1) ** 2
+        out[name] = {"shape": f"S=128 f={f} f'={fo} {h}x{h} k{k}",
+                     "ms[fprop,bprop,accgrad]": [round(v, 4) for v in ms],
+                     "effective_TFLOPs[fprop,bprop,accgrad]": [round(fl / (v * 1e-3) / 1e12, 1) for v in ms],
+                     "paper_K40m_cuFFT_conv_ms[fprop,bprop,accgrad]": list(paper_ms)}
+        del x, wt, gy, y, gx, gw
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -560,6 +601,8 @@ def main():
         torch.cuda.empty_cache()
         extra["C1_fprop_hip_graph"] = graph_replay_c1(hd)
         extra["tiled_layers"] = tiled_layers(hd)
+        torch.cuda.empty_cache()
+        extra["paper_table4_layers"] = table4_layers(hd)
         torch.cuda.empty_cache()
         extra["fft_sweep_256MiB"] = fft_sweep(hd)
         torch.cuda.empty_cache()
