@@ -42,6 +42,42 @@ struct TileLoader {
     static constexpr int NV = VEC ? (ROWS * TK / 4 + NT - 1) / NT : (ROWS * TK + NT - 1) / NT;
     float4 vr[VEC ? NV : 1], vi[VEC ? NV : 1];
     float sr[VEC ? 1 : NV], si[VEC ? 1 : NV];
+    unsigned boff[VEC ? NV : 1];   // fast addressing: byte offset of vector i from the tile's uniform base
+
+    // Fast addressing (16-byte gathers whose strided index moves in whole plane tiles, see
+    // fast_addressing()): the element index splits into a part that is uniform over the
+    // workgroup and changes with the K tile, which the scalar unit computes, and a per-lane
+    // part that never changes, computed here once.  A gather then costs no vector arithmetic.
+    __device__ __forceinline__ void prepare_fast(const FreqLayout &lay, long rs, long cs, int r0, int R, int tid) {
+        static_assert(VEC, "fast addressing is for 16-byte gathers");
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int v = tid + i * NT;
+            int rr, kk;
+            if constexpr (KF) { kk = (v % (TK / 4)) * 4; rr = v / (TK / 4); }
+            else { rr = (v % (ROWS / 4)) * 4; kk = v / (ROWS / 4); }
+            size_t o;
+            if constexpr (KF) o = (size_t)rr * rs * lay.bins * 2 + lay.part(kk);
+            else o = lay.part(rr) + (size_t)kk * cs * lay.bins * 2;
+            boff[i] = (v < ROWS * TK / 4 && r0 + rr < R) ? (unsigned)(o * sizeof(float)) : 0xffffffffu;
+        }
+    }
+    // ub: uniform base of this K tile (real parts); the imaginary parts lie im_bytes further.
+    __device__ __forceinline__ void load_fast(const char *ub, unsigned im_bytes, int k0, int K, int tid) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int v = tid + i * NT;
+            int kk;
+            if constexpr (KF) kk = (v % (TK / 4)) * 4;
+            else kk = v / (ROWS / 4);
+            vr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            vi[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (boff[i] != 0xffffffffu && k0 + kk < K) {
+                vr[i] = *reinterpret_cast<const float4 *>(ub + boff[i]);
+                vi[i] = *reinterpret_cast<const float4 *>(ub + im_bytes + boff[i]);
+            }
+        }
+    }
 
     __device__ __forceinline__ void load(const float *base, const FreqLayout &lay, long rs, long cs,
                                          int bin, int r0, int k0, int R, int K, int tid) {
@@ -117,6 +153,17 @@ struct TileLoader {
     }
 };
 
+// Uniform part of the addresses of one operand tile under fast addressing: rows from r0 (row
+// stride rs planes), reduction indices from k0 (stride cs planes), real parts.
+template <bool KF>
+__device__ __forceinline__ const char *tile_base(const float *base, const FreqLayout &lay, long rs, long cs,
+                                                 int bin, int r0, int k0) {
+    size_t o = (size_t)bin * (2u << lay.tsh);
+    if constexpr (KF) o += (size_t)r0 * rs * lay.bins * 2 + lay.part(k0);
+    else o += lay.part(r0) + (size_t)k0 * cs * lay.bins * 2;
+    return reinterpret_cast<const char *>(base + o);
+}
+
 // One workgroup's share of the contraction: workgroup number wg of prm's grid.
 template <int WGM, int WGN, int FM, int FN, int TK, bool AKF, bool BKF, bool VEC, int PD>
 __device__ __forceinline__ void cgemm_bins_body(const GemmParams &prm, const unsigned wg) {
@@ -157,7 +204,27 @@ __device__ __forceinline__ void cgemm_bins_body(const GemmParams &prm, const uns
     TileLoader<TM, TK, SA, AKF, VEC, NT> la[PD];
     TileLoader<TN, TK, SB, BKF, VEC, NT> lb[PD];
     const int nkt = (K + TK - 1) / TK;
+    bool fast = false;
+    if constexpr (VEC) fast = prm.fast != 0;
+    if constexpr (VEC) {
+        if (fast) {
+#pragma unroll
+            for (int d = 0; d < PD; ++d) {
+                la[d].prepare_fast(prm.layA, prm.a_rs, prm.a_cs, m0, M, tid);
+                lb[d].prepare_fast(prm.layB, prm.b_cs, prm.b_rs, n0, N, tid);
+            }
+        }
+    }
     auto issue = [&](auto &xa, auto &xb, int kt) {
+        if constexpr (VEC) {
+            if (fast) {
+                xa.load_fast(tile_base<AKF>(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, kt * TK),
+                             4u << prm.layA.tsh, kt * TK, K, tid);
+                xb.load_fast(tile_base<BKF>(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, kt * TK),
+                             4u << prm.layB.tsh, kt * TK, K, tid);
+                return;
+            }
+        }
         xa.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, kt * TK, M, K, tid);
         // B(k, n): row index of the loader is n, so swap the strides
         xb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, kt * TK, N, K, tid);
@@ -242,6 +309,30 @@ __device__ __forceinline__ void cgemm_bins_body(const GemmParams &prm, const uns
 
     // D layout of the 32x32x2 MFMA: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32.
     const size_t cim = (size_t)1 << prm.layC.tsh;
+    if (fast) {
+        // C(m, n) with n the contiguous plane index and the row stride a whole number of plane
+        // tiles: uniform base per register v (scalar unit), one per-lane byte offset
+        const size_t row = (size_t)prm.c_rs * prm.layC.bins * 2;          // floats per step of m
+        char *cb = reinterpret_cast<char *>(prm.C + (size_t)bin * (2u << prm.layC.tsh) + prm.layC.part(n0) + (size_t)m0 * row);
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int nl = (wn * FN + j) * 32 + lrow, ml = (wm * FM + i) * 32 + 4 * lk;
+                const unsigned lo = (unsigned)((ml * row + prm.layC.part(nl)) * sizeof(float));
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int mv = 8 * (v / 4) + (v % 4);
+                    if (m0 + ml + mv < M && n0 + nl < N) {
+                        char *q = cb + (size_t)mv * row * sizeof(float) + lo;
+                        const float p1 = acc_p1[i][j][v], p2 = acc_p2[i][j][v];
+                        *reinterpret_cast<float *>(q) = p1 - p2;
+                        *reinterpret_cast<float *>(q + cim * sizeof(float)) = acc_p3[i][j][v] - p1 - p2;
+                    }
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -297,7 +388,22 @@ __device__ __forceinline__ void cgemm_quadrant_body(const GemmParams &prm, const
     TileLoader<TQ, TK, SQ, AKF, true, NT> la[PD];
     TileLoader<TQ, TK, SQ, BKF, true, NT> lb[PD];
     const int nkt = (K + TK - 1) / TK;
+    const bool fast = prm.fast != 0;
+    if (fast) {
+#pragma unroll
+        for (int d = 0; d < PD; ++d) {
+            la[d].prepare_fast(prm.layA, prm.a_rs, prm.a_cs, m0, M, tid);
+            lb[d].prepare_fast(prm.layB, prm.b_cs, prm.b_rs, n0, N, tid);
+        }
+    }
     auto issue = [&](auto &xa, auto &xb, int kt) {
+        if (fast) {
+            xa.load_fast(tile_base<AKF>(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, kt * TK),
+                         4u << prm.layA.tsh, kt * TK, K, tid);
+            xb.load_fast(tile_base<BKF>(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, kt * TK),
+                         4u << prm.layB.tsh, kt * TK, K, tid);
+            return;
+        }
         xa.load(prm.A, prm.layA, prm.a_rs, prm.a_cs, bin, m0, kt * TK, M, K, tid);
         xb.load(prm.B, prm.layB, prm.b_cs, prm.b_rs, bin, n0, kt * TK, N, K, tid);
     };
@@ -365,7 +471,10 @@ __device__ __forceinline__ void cgemm_quadrant_body(const GemmParams &prm, const
         }
         const int m = m0 + 8 * wave + 4 * lk + vv;
         if (m < M && n < N) {
-            const size_t idx = prm.layC.index(m * prm.c_rs + n * prm.c_cs, bin, 0);
+            size_t idx;
+            if (fast) idx = (size_t)bin * (2u << prm.layC.tsh) + prm.layC.part(n0) + prm.layC.part(lrow) +
+                            (size_t)m * prm.c_rs * prm.layC.bins * 2;
+            else idx = prm.layC.index(m * prm.c_rs + n * prm.c_cs, bin, 0);
             prm.C[idx] = cr;
             prm.C[idx + cim] = ci;
         }
@@ -454,6 +563,17 @@ static int pick_tile() {
     return 3;
 }
 
+// Fast addressing of an operand (see TileLoader::prepare_fast): one index of the matrix is the
+// contiguous plane index, the other moves `stride` planes per step.  When that stride is a
+// whole number of plane tiles, a step of the strided index adds a constant to the element index,
+// whatever the contiguous index is, so addresses split into a uniform part and a per-lane
+// part.  The per-lane part must fit an unsigned 32-bit byte offset: 64 steps of the strided index.
+static bool fast_addressing(const FreqLayout &lay, long stride, int bins) {
+    const long T = 1L << lay.tsh;
+    if (stride <= 0 || stride % T != 0) return false;
+    return (double)stride * bins * 2 * 4 * 65 < 2147483648.0;
+}
+
 // Kernel parameters of one contraction and the kernel variant it can use.
 struct Prepared {
     GemmParams prm;
@@ -484,6 +604,9 @@ static hipError_t prepare(const GemmOperand &A, const GemmOperand &B, float *C, 
     const bool va = akf ? vec_ok(A.lay, K, A.rs, A.ptr) : (A.rs == 1 && vec_ok(A.lay, M, A.cs, A.ptr));
     const bool vb = bkf ? vec_ok(B.lay, K, B.cs, B.ptr) : (B.cs == 1 && vec_ok(B.lay, N, B.rs, B.ptr));
     out->akf = akf; out->bkf = bkf; out->vec = va && vb;
+    prm.fast = (out->vec && fast_addressing(A.lay, akf ? A.rs : A.cs, bins) &&
+                fast_addressing(B.lay, bkf ? B.cs : B.rs, bins) && C_cs == 1 && fast_addressing(layC, C_rs, bins) &&
+                !getenv("FFTCONV_GEMM_NO_FAST")) ? 1 : 0;
     // Layouts with runs of 4 planes (basis 64) put four bins in every 128-byte line: the
     // bin-group kernel loads whole lines and multiplies the four bins side by side.
     const char *no_bg_env = getenv("FFTCONV_GEMM_NO_BINGROUP");

@@ -15,6 +15,7 @@ struct GemmParams {
     int tiles_m, tiles_n;
     unsigned a_sign, b_sign;   // 0x80000000 to conjugate the operand (flips Im on the way to the MFMA)
     unsigned split_from;       // cgemm_tail_kernel: first workgroup index of the quadrant workgroups
+    int fast;                  // addresses split into a uniform and a per-lane part (fast_addressing())
 };
 
 __device__ __forceinline__ float flip(float v, unsigned sign) {

@@ -40,6 +40,12 @@ struct FreqLayout {
         const long pl = plane & ((1L << tsh) - 1);
         return (size_t)((((pt * bins + bin) * 2 + c) << tsh) + pl);
     }
+    // Offset of plane x relative to plane 0 for a fixed bin and component.  For x = a + b with
+    // no carry out of the low tsh bits of a and b (e.g. a a multiple of the tile, or both below
+    // it with a + b below it too), part(a + b) = part(a) + part(b).
+    __host__ __device__ size_t part(int x) const {
+        return ((size_t)(x >> tsh) * bins * 2 << tsh) + (size_t)(x & ((1 << tsh) - 1));
+    }
     size_t floats(long planes) const {
         const long T = 1L << tsh;
         return (size_t)((planes + T - 1) / T) * T * bins * 2;

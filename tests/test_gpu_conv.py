@@ -224,3 +224,29 @@ def test_saved_buffer_too_small(hd, lib):
     small = torch.empty(need // 8, device="cuda", dtype=torch.float32)
     with pytest.raises(lib.FFTConvError, match="workspace too small"):
         hd.fft_conv_fprop_save(_dev(x), _dev(w), small)
+
+
+@pytest.mark.parametrize("cfg", [dict(S=128, f=64, fo=64, h=27, w=27, kh=5, kw=5),      # basis 28, 64x64 tiles + split tail
+                                 dict(S=70, f=32, fo=96, h=13, w=13, kh=3, kw=3),       # basis 14, ragged M
+                                 dict(S=8, f=64, fo=32, h=8, w=8, kh=3, kw=3)])         # basis 8: 64 planes per tile
+def test_contraction_addressing_paths_agree(hd, cfg, monkeypatch):
+    """The contraction splits its gather / store addresses into a uniform and a per-lane part
+    when every strided index moves in whole plane tiles; the general index arithmetic must
+    give bit-identical results (same loads, same order of summation)."""
+    import torch
+    x, w, gy = synth.conv_inputs(seed=77, **cfg)
+    dx, dw, dgy = (torch.from_numpy(a).cuda() for a in (x, w, gy))
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda")
+
+    def run():
+        y = hd.fft_conv_fprop_save(dx, dw, saved).clone()
+        gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+        return y, gx.clone(), gw.clone(), hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"]).clone()
+    fast = run()
+    monkeypatch.setenv("FFTCONV_GEMM_NO_FAST", "1")
+    general = run()
+    for a, b in zip(fast, general):
+        assert torch.equal(a, b)
+    ref = oracle.conv_fprop(x, w)
+    assert np.max(np.abs(fast[0].cpu().numpy() - ref)) / np.max(np.abs(ref)) <= 1e-4
