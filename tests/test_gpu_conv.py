@@ -31,17 +31,22 @@ def _np(t):
     return t.cpu().numpy().astype(np.float64)
 
 
-def _run_all(hd, cfg, seed, passes=("fprop", "bprop", "accgrad")):
+def _run_all(hd, cfg, seed, passes=("fprop", "bprop", "accgrad"), basis=None):
+    """basis=None: the ordinary entry points (the library's own basis); a number: that Fourier
+    basis through the *_tiled entry points (untiled pipeline when it holds the image)."""
     x, w, gy = synth.conv_inputs(seed=seed, **cfg)
     dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
     errs = {}
     if "fprop" in passes:
-        errs["fprop"] = _relerr(_np(hd.fft_conv_fprop(dx, dw)), oracle.conv_fprop(x, w))
+        got = hd.fft_conv_fprop(dx, dw) if basis is None else hd.fft_conv_fprop_tiled(dx, dw, basis)
+        errs["fprop"] = _relerr(_np(got), oracle.conv_fprop(x, w))
     if "bprop" in passes:
-        errs["bprop"] = _relerr(_np(hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"])),
-                                oracle.conv_bprop(gy, w, cfg["h"], cfg["w"]))
+        got = (hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"]) if basis is None
+               else hd.fft_conv_bprop_tiled(dgy, dw, cfg["h"], cfg["w"], basis))
+        errs["bprop"] = _relerr(_np(got), oracle.conv_bprop(gy, w, cfg["h"], cfg["w"]))
     if "accgrad" in passes:
-        errs["accgrad"] = _relerr(_np(hd.fft_conv_accgrad(dx, dgy)), oracle.conv_accgrad(x, gy))
+        got = hd.fft_conv_accgrad(dx, dgy) if basis is None else hd.fft_conv_accgrad_tiled(dx, dgy, basis)
+        errs["accgrad"] = _relerr(_np(got), oracle.conv_accgrad(x, gy))
     return errs
 
 
@@ -73,16 +78,20 @@ def test_small_shapes(hd, cfg):
         assert e <= TOL, (k, e)
 
 
-def test_config_c1_fprop(hd):
+# The benchmark configurations name their Fourier basis (16, 32, 16); the library by itself
+# takes the smallest basis that holds the image (14, 28, 14).  Both are checked at full size.
+@pytest.mark.parametrize("named", [False, True], ids=["library_basis", "named_basis"])
+def test_config_c1_fprop(hd, named):
     cfg = synth.CONV_CONFIGS["C1"]
-    errs = _run_all(hd, cfg, seed=synth.CONV_SEEDS["C1"], passes=cfg["passes"])
+    errs = _run_all(hd, cfg, seed=synth.CONV_SEEDS["C1"], passes=cfg["passes"], basis=cfg["N"] if named else None)
     assert errs["fprop"] <= TOL
 
 
+@pytest.mark.parametrize("named", [False, True], ids=["library_basis", "named_basis"])
 @pytest.mark.parametrize("name", ["C2", "C3"])
-def test_config_full_tensor(hd, name):
+def test_config_full_tensor(hd, name, named):
     cfg = synth.CONV_CONFIGS[name]
-    errs = _run_all(hd, cfg, seed=synth.CONV_SEEDS[name])
+    errs = _run_all(hd, cfg, seed=synth.CONV_SEEDS[name], basis=cfg["N"] if named else None)
     for k, e in errs.items():
         assert e <= TOL, (name, k, e)
 
@@ -178,14 +187,23 @@ def test_fprop_save_and_backward(hd, cfg):
     assert none is None and _relerr(_np(gw2), 0.5 * ref_gw) <= TOL
 
 
-def test_reuse_at_c2(hd):
+@pytest.mark.parametrize("named", [False, True], ids=["library_basis", "named_basis"])
+def test_reuse_at_c2(hd, named):
+    """The step bench.py times: fprop_save + backward of the headline layer, on the basis the
+    benchmark definition names (32, the launch configuration of `value`) and on the library's."""
     import torch
     cfg = {k: v for k, v in synth.CONV_CONFIGS["C2"].items() if k not in ("passes", "N")}
     x, w, gy = synth.conv_inputs(seed=synth.CONV_SEEDS["C2"], **cfg)
     dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
-    saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
-    y = hd.fft_conv_fprop_save(_dev(x), _dev(w), saved)
-    gx, gw = hd.fft_conv_backward(_dev(gy), saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    if named:
+        n = synth.CONV_CONFIGS["C2"]["N"]
+        saved = torch.empty(hd.saved_bytes_tiled(*dims, n) // 4, device="cuda", dtype=torch.float32)
+        y = hd.fft_conv_fprop_save_tiled(_dev(x), _dev(w), n, saved)
+        gx, gw = hd.fft_conv_backward_tiled(_dev(gy), saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"], n)
+    else:
+        saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda", dtype=torch.float32)
+        y = hd.fft_conv_fprop_save(_dev(x), _dev(w), saved)
+        gx, gw = hd.fft_conv_backward(_dev(gy), saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
     assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
     assert _relerr(_np(gx), oracle.conv_bprop(gy, w, cfg["h"], cfg["w"])) <= TOL
     assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
