@@ -422,6 +422,35 @@ def table4_layers(hd, reps=10):
     return out
 
 
+def weights_ahead(hd, reps=30):
+    """fprop with the weight transform computed ahead (fft_conv_transform_weights once, then
+    fft_conv_fprop_weights) against the ordinary fprop, on the shapes of C2..C4 (timing only)."""
+    import torch
+    from paper_1412_7580_amd import synth
+    gen = torch.Generator(device="cuda").manual_seed(8)
+    out = {}
+    for name in ("C2", "C3", "C4"):
+        c = synth.CONV_CONFIGS[name]
+        mk = lambda *shape: torch.rand(shape, device="cuda", generator=gen) * 2 - 1
+        x, wt = mk(c["S"], c["f"], c["h"], c["w"]), mk(c["fo"], c["f"], c["kh"], c["kw"])
+        y = hd.fft_conv_fprop(x, wt)
+        wf = hd.fft_conv_transform_weights(wt, c["h"], c["w"])
+        us = []
+        for fn in (lambda: hd.fft_conv_fprop(x, wt, y=y),
+                   lambda: hd.fft_conv_fprop_weights(x, wf, c["fo"], c["kh"], c["kw"], y=y)):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            us.append(round((time.perf_counter() - t0) / reps * 1e6, 1))
+        out[name] = {"fprop_us": us[0], "fprop_weights_ahead_us": us[1], "weights_MB": round(wf.numel() * 4 / 1e6, 1)}
+        del x, wt, y, wf
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -603,6 +632,8 @@ def main():
         extra["tiled_layers"] = tiled_layers(hd)
         torch.cuda.empty_cache()
         extra["paper_table4_layers"] = table4_layers(hd)
+        torch.cuda.empty_cache()
+        extra["weights_transformed_ahead"] = weights_ahead(hd)
         torch.cuda.empty_cache()
         extra["fft_sweep_256MiB"] = fft_sweep(hd)
         torch.cuda.empty_cache()

@@ -179,6 +179,27 @@ int fft_conv_backward_tiled(fftconv_handle hd, const float *gy, float *gx, float
                             void *ws, size_t ws_bytes);
 
 /*
+ * Weights transformed ahead of the passes that use them (the second opportunity Section 6
+ * lists and forgoes: precomputing the FFTs of the weight tensors; once per optimiser step in
+ * training, once for all in inference).  fft_conv_transform_weights leaves the transform of
+ * wt[fo,f,kh,kw] for a layer of h x w images (padded by pad_h, pad_w; 0 for none) in the caller's
+ * device buffer wf of at least fftconv_weights_bytes() bytes (contents private; valid for
+ * every minibatch size).  fft_conv_fprop_weights / fft_conv_bprop_weights then equal
+ * fft_conv_fprop(_padded) / fft_conv_bprop(_padded) with one forward transform instead of two.
+ * The transform may run on another handle and stream than the passes (the caller orders
+ * them).  Workspace as for the ordinary passes; a short wf gives FFTCONV_WORKSPACE_TOO_SMALL.
+ */
+size_t fftconv_weights_bytes(int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w);
+int fft_conv_transform_weights(fftconv_handle hd, const float *wt, void *wf, size_t wf_bytes,
+                               int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w);
+int fft_conv_fprop_weights(fftconv_handle hd, const float *x, const void *wf, size_t wf_bytes, float *y,
+                           int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                           void *ws, size_t ws_bytes);
+int fft_conv_bprop_weights(fftconv_handle hd, const float *gy, const void *wf, size_t wf_bytes, float *gx,
+                           int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                           void *ws, size_t ws_bytes);
+
+/*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
  * (Supplement, DFT definition); n is a power of two in 8..128 (256 for the 1-D calls: the
  * sizes of Section 5.3) or one of 12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112 (and 160, 192,

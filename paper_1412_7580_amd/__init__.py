@@ -23,6 +23,7 @@ SYMBOLS = [
     "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled", "fftconv_autotune_basis",
     "fftconv_saved_bytes_tiled", "fftconv_backward_workspace_bytes_tiled",
     "fft_conv_fprop_save_tiled", "fft_conv_backward_tiled",
+    "fftconv_weights_bytes", "fft_conv_transform_weights", "fft_conv_fprop_weights", "fft_conv_bprop_weights",
     "fftconv_padded_workspace_bytes",
     "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
     "fftconv_saved_bytes_padded", "fftconv_backward_workspace_bytes_padded",
@@ -82,6 +83,11 @@ def load_library():
     lib.fftconv_backward_workspace_bytes_tiled.restype = sz
     lib.fft_conv_fprop_save_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz, vp, sz]
     lib.fft_conv_backward_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [f, i, vp, sz, vp, sz]
+    lib.fftconv_weights_bytes.argtypes = [i] * 8
+    lib.fftconv_weights_bytes.restype = sz
+    lib.fft_conv_transform_weights.argtypes = [vp, vp, vp, sz] + [i] * 8
+    lib.fft_conv_fprop_weights.argtypes = [vp, vp, vp, sz, vp] + [i] * 9 + [vp, sz]
+    lib.fft_conv_bprop_weights.argtypes = [vp, vp, vp, sz, vp] + [i] * 9 + [vp, sz]
     lib.fftconv_padded_workspace_bytes.argtypes = [i] * 10
     lib.fftconv_padded_workspace_bytes.restype = sz
     lib.fft_conv_fprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
@@ -350,6 +356,47 @@ class Handle:
                                                  1 if accumulate else 0, *self._ws(saved), *self._ws(ws)),
                "fft_conv_backward_tiled")
         return gx, gw
+
+    # ---- weights transformed ahead --------------------------------------------------------
+    def weights_bytes(self, f, fo, h, w, kh, kw, pad_h=0, pad_w=0) -> int:
+        return int(self._lib.fftconv_weights_bytes(f, fo, h, w, kh, kw, pad_h, pad_w))
+
+    def fft_conv_transform_weights(self, wt, h, w, pad_h=0, pad_w=0, wf=None):
+        """Transform of wt for layers of h x w images; returns the (float32 device) buffer."""
+        import torch
+        fo, f, kh, kw = wt.shape
+        if wf is None:
+            wf = torch.empty(self.weights_bytes(f, fo, h, w, kh, kw, pad_h, pad_w) // 4, device=wt.device,
+                             dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_transform_weights(self._h, _dev_f32(wt, "wt"), *self._ws(wf), f, fo, h, w, kh, kw,
+                                                    pad_h, pad_w), "fft_conv_transform_weights")
+        return wf
+
+    def fft_conv_fprop_weights(self, x, wf, fo, kh, kw, pad_h=0, pad_w=0, y=None, ws=None):
+        import torch
+        S, f, h, w = x.shape
+        if y is None:
+            y = torch.empty((S, fo, h + 2 * pad_h - kh + 1, w + 2 * pad_w - kw + 1), device=x.device,
+                            dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop_weights(self._h, _dev_f32(x, "x"), *self._ws(wf), _dev_f32(y, "y"),
+                                                S, f, fo, h, w, kh, kw, pad_h, pad_w, *self._ws(ws)),
+               "fft_conv_fprop_weights")
+        return y
+
+    def fft_conv_bprop_weights(self, gy, wf, f, h, w, kh, kw, pad_h=0, pad_w=0, gx=None, ws=None):
+        import torch
+        S, fo, oh, ow = gy.shape
+        if oh != h + 2 * pad_h - kh + 1 or ow != w + 2 * pad_w - kw + 1:
+            raise FFTConvError("gy and (h, w, kh, kw, padding) disagree")
+        if gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_bprop_weights(self._h, _dev_f32(gy, "gy"), *self._ws(wf), _dev_f32(gx, "gx"),
+                                                S, f, fo, h, w, kh, kw, pad_h, pad_w, *self._ws(ws)),
+               "fft_conv_bprop_weights")
+        return gx
 
     # ---- zero-padded layers ---------------------------------------------------------------
     def padded_workspace_bytes(self, pass_, S, f, fo, h, w, kh, kw, pad_h, pad_w) -> int:

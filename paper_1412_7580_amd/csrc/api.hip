@@ -304,6 +304,25 @@ static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB
     return FFTCONV_OK;
 }
 
+// fprop / bprop with the weights already in the frequency domain (wf from
+// fft_conv_transform_weights): one forward transform, the contraction, the inverse.
+static int run_pass_weights(fftconv_ctx *c, int pass, const float *opA, const void *wf, size_t wf_bytes, float *out,
+                            int S, int f, int fo, int h, int w, int kh, int kw, int ph, int pw,
+                            void *ws, size_t ws_bytes) {
+    if (!c || !opA || !wf || !out) return FFTCONV_INVALID_ARG;
+    PassPlan p;
+    int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p, -1, ph, pw);
+    if (rc != FFTCONV_OK) return rc;
+    if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
+    if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
+    float *AF = at(ws, p.offA), *CF = at(ws, p.offC);
+    c->nk = 0;
+    hipError_t e = launch_fft2d_r2c(opA, AF, p.planesA, p.hA, p.wA, p.N, true, next_ctx(c), p.viewA ? &p.vA : nullptr);
+    if (e != hipSuccess) return hip_fail(c, e);
+    if ((e = contract_and_invert(c, p, AF, static_cast<const float *>(wf), CF, out, 1.0f, 0)) != hipSuccess) return hip_fail(c, e);
+    return FFTCONV_OK;
+}
+
 // Layout of the buffer that carries the input and weight transforms from fprop to the
 // backward call: [XF | WF], each in the plane-tiled layout of the layer's basis.
 struct SavedPlan {
@@ -721,6 +740,36 @@ int fft_conv_backward_tiled(fftconv_handle hd, const float *gy, float *gx, float
     if (tile_n < 0) return FFTCONV_INVALID_ARG;
     return backward_impl(hd, gy, gx, gw, S, f, fo, h, w, kh, kw, 0, 0, scale, accumulate, saved, saved_bytes, ws,
                          ws_bytes, tile_n);
+}
+
+size_t fftconv_weights_bytes(int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w) {
+    PassPlan p;
+    if (make_plan(FFTCONV_FPROP, 1, f, fo, h, w, kh, kw, &p, -1, pad_h, pad_w) != FFTCONV_OK) return 0;
+    return align_up(p.lay.floats(p.planesB) * sizeof(float), 256);
+}
+
+int fft_conv_transform_weights(fftconv_handle hd, const float *wt, void *wf, size_t wf_bytes,
+                               int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w) {
+    if (!hd || !wt || !wf) return FFTCONV_INVALID_ARG;
+    PassPlan p;
+    int rc = make_plan(FFTCONV_FPROP, 1, f, fo, h, w, kh, kw, &p, -1, pad_h, pad_w);
+    if (rc != FFTCONV_OK) return rc;
+    if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
+    hd->nk = 0;
+    hipError_t e = launch_fft2d_r2c(wt, static_cast<float *>(wf), p.planesB, p.hB, p.wB, p.N, true, next_ctx(hd));
+    return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
+}
+
+int fft_conv_fprop_weights(fftconv_handle hd, const float *x, const void *wf, size_t wf_bytes, float *y,
+                           int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                           void *ws, size_t ws_bytes) {
+    return run_pass_weights(hd, FFTCONV_FPROP, x, wf, wf_bytes, y, S, f, fo, h, w, kh, kw, pad_h, pad_w, ws, ws_bytes);
+}
+
+int fft_conv_bprop_weights(fftconv_handle hd, const float *gy, const void *wf, size_t wf_bytes, float *gx,
+                           int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
+                           void *ws, size_t ws_bytes) {
+    return run_pass_weights(hd, FFTCONV_BPROP, gy, wf, wf_bytes, gx, S, f, fo, h, w, kh, kw, pad_h, pad_w, ws, ws_bytes);
 }
 
 }  // extern "C"

@@ -113,3 +113,37 @@ def test_padded_errors_and_workspace(hd, lib):
     hd.fft_conv_fprop_padded(x, k, 1, 1, ws=ws)
     with pytest.raises(lib.FFTConvError, match="workspace too small"):
         hd.fft_conv_fprop_padded(x, k, 1, 1, ws=ws[: need // 8])
+
+
+@pytest.mark.parametrize("cfg,pad", [(dict(S=5, f=6, fo=7, h=13, w=13, kh=3, kw=3), (0, 0)),       # basis 14
+                                     (dict(S=3, f=4, fo=5, h=27, w=25, kh=5, kw=5), (2, 2)),       # padded: windows
+                                     (dict(S=2, f=3, fo=2, h=150, w=140, kh=7, kw=5), (0, 0)),     # tiled by itself
+                                     (dict(S=2, f=8, fo=8, h=64, w=64, kh=31, kw=31), (0, 0))])    # basis 64
+def test_weights_transformed_ahead(hd, lib, cfg, pad):
+    """fft_conv_transform_weights once, then fprop and bprop for two different minibatches: equal
+    to the ordinary (padded) passes bit for bit (same kernels on the same transforms) and to the
+    oracle within the bound."""
+    import torch
+    ph, pw = pad
+    h, w, kh, kw = cfg["h"], cfg["w"], cfg["kh"], cfg["kw"]
+    big = dict(cfg, h=h + 2 * ph, w=w + 2 * pw)
+    wf = None
+    for S in (cfg["S"], 1):
+        xp, wt, gy = synth.conv_inputs(seed=700 + S, **dict(big, S=S))
+        x = np.ascontiguousarray(xp[:, :, ph:ph + h, pw:pw + w])
+        xpad = np.zeros_like(xp)
+        xpad[:, :, ph:ph + h, pw:pw + w] = x
+        if wf is None:
+            w0 = wt                                           # the weights of the first draw serve both minibatches
+            wf = hd.fft_conv_transform_weights(_dev(w0), h, w, ph, pw)
+            assert wf.numel() * 4 == hd.weights_bytes(cfg["f"], cfg["fo"], h, w, kh, kw, ph, pw) > 0
+        dx, dw, dgy = _dev(x), _dev(w0), _dev(gy)
+        y = hd.fft_conv_fprop_weights(dx, wf, cfg["fo"], kh, kw, ph, pw)
+        gx = hd.fft_conv_bprop_weights(dgy, wf, cfg["f"], h, w, kh, kw, ph, pw)
+        assert torch.equal(y, hd.fft_conv_fprop_padded(dx, dw, ph, pw))
+        assert torch.equal(gx, hd.fft_conv_bprop_padded(dgy, dw, h, w, ph, pw))
+        assert _relerr(_np(y), oracle.conv_fprop(xpad, w0)) <= TOL
+        ref = oracle.conv_bprop(gy, w0, h + 2 * ph, w + 2 * pw)[:, :, ph:ph + h, pw:pw + w]
+        assert _relerr(_np(gx), ref) <= TOL
+    with pytest.raises(lib.FFTConvError, match="workspace too small"):
+        hd.fft_conv_fprop_weights(dx, wf[:-64], cfg["fo"], kh, kw, ph, pw)
