@@ -201,7 +201,7 @@ int fft_conv_bprop_weights(fftconv_handle hd, const float *gy, const void *wf, s
 
 /*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
- * (Supplement, DFT definition); n is a power of two in 8..128 (256 for the 1-D calls: the
+ * (Supplement, DFT definition); n is a power of two in 2..128 (256 for the 1-D calls: the
  * sizes of Section 5.3) or one of 12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112 (and 160, 192,
  * 224 for the 1-D calls): 2^a x {3, 5, 7}, sizes Section 3.2 takes from cuFFT; any other n
  * gives FFTCONV_UNSUPPORTED.  Inputs shorter than n are

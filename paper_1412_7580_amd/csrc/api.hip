@@ -509,9 +509,9 @@ int fft_conv_accgrad_padded(fftconv_handle hd, const float *x, const float *gy, 
                     pad_h, pad_w);
 }
 
-static bool fft_size_ok(int n) { return basis_ok(n); }
+static bool fft_size_ok(int n) { return n == 2 || n == 4 || basis_ok(n); }
 // 1-D transforms go one octave further (the range of Section 5.3 of the paper).
-static bool fft1d_size_ok(int n) { return basis_ok(n) || n == 160 || n == 192 || n == 224 || n == 256; }
+static bool fft1d_size_ok(int n) { return fft_size_ok(n) || n == 160 || n == 192 || n == 224 || n == 256; }
 
 int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in, int n) {
     if (!hd || B < 0 || n_in <= 0 || (B > 0 && (!in || !out))) return FFTCONV_INVALID_ARG;

@@ -60,6 +60,9 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
     if (planes <= 0) return hipSuccess;
     if (view && !conv) return hipErrorInvalidValue;
     switch (N) {
+        // sizes 2 and 4: stand-alone transforms only (Section 5 covers 2 ... 256; no convolution basis)
+        case 2: return conv ? hipErrorInvalidValue : run_fwd2d<2, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
+        case 4: return conv ? hipErrorInvalidValue : run_fwd2d<4, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
         case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
         case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);   // (8,2): 12 % slower
         case 32: return run_fwd2d<16, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);   // (32,1): equal at C2, 3..5 % slower on large grids
@@ -75,6 +78,8 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
     if (view && (!conv || view->oy + h_out > N || view->ox + w_out > N)) return hipErrorInvalidValue;
     const int rows = h_out + (view ? view->oy : 0);   // rows of the transform that are computed
     switch (N) {
+        case 2: return conv ? hipErrorInvalidValue : run_inv2d<2, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 4: return conv ? hipErrorInvalidValue : run_inv2d<4, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 8: return run_inv2d<8, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 16:
             // lane pairs when at most half the rows are kept (3x3 weight gradients: 29 us against
@@ -104,6 +109,8 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st) {
     if (B <= 0) return hipSuccess;
     switch (n) {
+        case 2: return run_fwd1d<2, 1, 1024>(in, out, B, n_in, st);
+        case 4: return run_fwd1d<4, 1, 1024>(in, out, B, n_in, st);
         case 8: return run_fwd1d<4, 2, 512>(in, out, B, n_in, st);
         case 16: return run_fwd1d<4, 4, 512>(in, out, B, n_in, st);
         case 32: return run_fwd1d<8, 4, 256>(in, out, B, n_in, st);
@@ -117,6 +124,8 @@ hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n
 hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st) {
     if (B <= 0) return hipSuccess;
     switch (n) {
+        case 2: return run_inv1d<2, 1, 1024>(in, out, B, n_out, st);
+        case 4: return run_inv1d<4, 1, 1024>(in, out, B, n_out, st);
         case 8: return run_inv1d<4, 2, 512>(in, out, B, n_out, st);
         case 16: return run_inv1d<4, 4, 512>(in, out, B, n_out, st);
         case 32: return run_inv1d<8, 4, 256>(in, out, B, n_out, st);

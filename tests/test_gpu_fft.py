@@ -155,3 +155,23 @@ def test_sweep_full_size(hd, dim, n):
     assert _relerr(got, ref) <= TOL
     err = float((back - dx).abs().max()) / float(dx.abs().max())
     assert err <= TOL
+
+
+@pytest.mark.parametrize("n", [2, 4])
+def test_smallest_sizes(hd, n):
+    """n = 2 and 4, the low end of the range of Section 5: every input length, ragged batches,
+    both dimensions, forward against the oracle and the inverse against the input."""
+    for B in (1, 3, 2051):
+        for n_in in range(1, n + 1):
+            x = synth.normal01(21, n, (B, n_in))
+            X = hd.fft_r2c_1d(_dev(x), n)
+            assert _relerr(_c(X), oracle.dft_r2c_1d(x, n)) <= TOL, (B, n_in)
+            back = hd.fft_c2r_1d(X, n, n_in).cpu().numpy().astype(np.float64)
+            assert np.max(np.abs(back - x)) <= TOL * max(1.0, np.max(np.abs(x))), (B, n_in)
+    for B in (1, 5, 300):
+        for (h_in, w_in) in [(1, 1), (n, n), (1, n), (n, 1), (n - 1, n)]:
+            x = synth.normal01(22, n, (B, h_in, w_in))
+            X = hd.fft_r2c_2d(_dev(x), n)
+            assert _relerr(_c(X), oracle.dft_r2c_2d(x, n)) <= TOL, (B, h_in, w_in)
+            back = hd.fft_c2r_2d(X, n, h_in, w_in).cpu().numpy().astype(np.float64)
+            assert np.max(np.abs(back - x)) <= TOL * max(1.0, np.max(np.abs(x))), (B, h_in, w_in)
