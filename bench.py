@@ -269,8 +269,8 @@ def fft_sweep(hd, max_bytes=1 << 28, reps=3, sizes=None, sizes_1d_only=(256,)):
 
 def graph_replay_c1(hd, reps=200):
     """The smallest configuration is launch-bound (three kernels of a few microseconds): time
-    its fprop eagerly and as a captured HIP graph (caller-supplied workspace, so the call
-    allocates nothing)."""
+    its fprop eagerly, as a captured HIP graph (caller-supplied workspace, so the call
+    allocates nothing) and as the one-launch fused kernel."""
     import torch
     import paper_1412_7580_amd as pkg
     from paper_1412_7580_amd import synth
@@ -296,7 +296,11 @@ def graph_replay_c1(hd, reps=200):
     with torch.cuda.graph(graph):
         call()
     replay = timed(graph.replay)
-    return {"eager_us_per_fprop": round(eager * 1e6, 2), "graph_replay_us_per_fprop": round(replay * 1e6, 2)}
+    # the same fprop as ONE launch (fft_conv_fprop_fused, on weights transformed ahead)
+    wf = hd.fft_conv_transform_weights(t["w"], cfg["h"], cfg["w"])
+    fused = timed(lambda: hd.fft_conv_fprop_fused(t["x"], wf, cfg["fo"], cfg["kh"], cfg["kw"], y=t["y"]))
+    return {"eager_us_per_fprop": round(eager * 1e6, 2), "graph_replay_us_per_fprop": round(replay * 1e6, 2),
+            "fused_one_launch_us_per_fprop": round(fused * 1e6, 2)}
 
 
 def tiled_layers(hd, reps=10):

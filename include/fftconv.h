@@ -200,6 +200,19 @@ int fft_conv_bprop_weights(fftconv_handle hd, const float *gy, const void *wf, s
                            void *ws, size_t ws_bytes);
 
 /*
+ * fprop of a small layer in ONE launch, on weights transformed ahead (wf from
+ * fft_conv_transform_weights with pad 0): for the latency-bound regime, where the three launches
+ * of fft_conv_fprop_weights cost more than the arithmetic (Section 6 plans such an integration
+ * of the matrix product with the transform kernels).  One workgroup carries one sample through
+ * transform, contraction and inverse; it needs no workspace.  Same result as fft_conv_fprop up
+ * to rounding.  Supported when the layer's basis is at most 16 (images up to 16x16, unpadded),
+ * f is a multiple of 4 that divides 32 (64 at basis 8), fo <= 32 (64) and f * fo <= 256:
+ * otherwise FFTCONV_UNSUPPORTED, and the caller uses fft_conv_fprop_weights.
+ */
+int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size_t wf_bytes, float *y,
+                         int S, int f, int fo, int h, int w, int kh, int kw);
+
+/*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
  * (Supplement, DFT definition); n is a power of two in 2..128 (256 for the 1-D calls: the
  * sizes of Section 5.3) or one of 12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112 (and 160, 192,

@@ -372,7 +372,7 @@ const char *fftconv_status_string(int status) {
     switch (status) {
         case FFTCONV_OK: return "ok";
         case FFTCONV_INVALID_ARG: return "invalid argument";
-        case FFTCONV_UNSUPPORTED: return "unsupported Fourier basis size (must be 8..128)";
+        case FFTCONV_UNSUPPORTED: return "unsupported transform size or layer shape for this entry point";
         case FFTCONV_WORKSPACE_TOO_SMALL: return "workspace too small";
         case FFTCONV_HIP_ERROR: return "HIP runtime error";
         default: return "unknown status";
@@ -770,6 +770,20 @@ int fft_conv_bprop_weights(fftconv_handle hd, const float *gy, const void *wf, s
                            int S, int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w,
                            void *ws, size_t ws_bytes) {
     return run_pass_weights(hd, FFTCONV_BPROP, gy, wf, wf_bytes, gx, S, f, fo, h, w, kh, kw, pad_h, pad_w, ws, ws_bytes);
+}
+
+int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size_t wf_bytes, float *y,
+                         int S, int f, int fo, int h, int w, int kh, int kw) {
+    if (!hd || !x || !wf || !y) return FFTCONV_INVALID_ARG;
+    PassPlan p;
+    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
+    if (rc != FFTCONV_OK) return rc;
+    if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
+    if (p.tiled || !fused_fprop_supported(p.N, f, fo, static_cast<const float *>(wf))) return FFTCONV_UNSUPPORTED;
+    hd->nk = 0;
+    const hipError_t e = launch_fused_fprop(x, static_cast<const float *>(wf), y, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd));
+    if (e == hipErrorInvalidValue) return FFTCONV_UNSUPPORTED;   // the layer's planes do not fit the kernel's LDS plan
+    return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
 }  // extern "C"

@@ -266,8 +266,11 @@ struct BinStore {
     }
 };
 
-template <int L, int G, int T, bool CONV, bool OSTAGE>
+// KEEP (with CONV and OSTAGE): stop once the block's spectra stand in LDS, as the image
+// smem[(bin * 2 + c) * T + plane], and leave them there for the caller (after a barrier).
+template <int L, int G, int T, bool CONV, bool OSTAGE, bool KEEP = false>
 __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned block) {
+    static_assert(!KEEP || (CONV && OSTAGE), "KEEP leaves the plane-tiled image in LDS");
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
     constexpr int NA = SplitRegs<L, G>::A;   // registers of split spectrum per lane
     constexpr int NBR = SplitRegs<L, G>::B;
@@ -422,6 +425,7 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
     }
     if constexpr (OSTAGE) {
         __syncthreads();
+        if constexpr (KEEP) return;
         if constexpr (CONV) {
             // whole tile, including the padding planes of a ragged last tile
             unstage_linear<BT>(prm.out + prm.lay.index(p0, 0, 0), smem, (unsigned)T * N * NB * 2, tid,
@@ -472,14 +476,18 @@ struct Inv2dParams {
     PlaneView view;
 };
 
-template <int L, int G, int T, bool CONV, bool ISTAGE>
-__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dParams prm) {
+// PRE (plane-tiled layout only): the block's input already stands in LDS at pre_img, laid out
+// like one tile of the layout ((bin * 2 + c) * T + plane), beyond the first
+// max(T * MPS float2, T * h_out * w_out + 3 floats) of LDS, which this function uses.
+template <int L, int G, int T, bool CONV, bool ISTAGE, bool PRE = false>
+__device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned block, const float *pre_img = nullptr) {
+    static_assert(!PRE || (CONV && !ISTAGE), "a preloaded tile is in the plane-tiled layout and needs no staging");
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
     extern __shared__ float smem[];
     float2 *mid = reinterpret_cast<float2 *>(smem);
 
     const int tid = threadIdx.x;
-    const long p0 = (long)blockIdx.x * T;
+    const long p0 = (long)block * T;
     // the output block assembled in LDS shares the 16-byte phase of its place in global memory
     // (contiguous outputs only; scattered windows keep an aligned image)
     float *sout = smem;
@@ -507,7 +515,7 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
         float cre[L], cim[L];
         if (cp < np) {
             if constexpr (CONV) {
-                const float *base = (ISTAGE ? smem : prm.in + prm.lay.index(p0, 0, 0)) + cp;
+                const float *base = (PRE ? pre_img : ISTAGE ? smem : prm.in + prm.lay.index(p0, 0, 0)) + cp;
                 const int tsh = prm.lay.tsh;
 #pragma unroll
                 for (int m = 0; m < L; ++m) {
@@ -606,6 +614,11 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
         const unsigned total = (unsigned)np * h_out * w_out;
         unstage_linear<BT>(dst, sout, total, tid, true, prm.accumulate != 0);
     }
+}
+
+template <int L, int G, int T, bool CONV, bool ISTAGE>
+__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dParams prm) {
+    fft2d_c2r_body<L, G, T, CONV, ISTAGE>(prm, blockIdx.x);
 }
 
 // ------------------------------------------------------------------ 1-D forward

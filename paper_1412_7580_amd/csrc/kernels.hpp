@@ -106,6 +106,12 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
                             bool conv_layout, float scale, bool accumulate, LaunchCtx st,
                             const PlaneView *view = nullptr);
 
+// One-launch fprop of a small layer (basis N <= 16, f and f' within one plane tile): one
+// workgroup per sample; wf is the weight transform in the layout of basis N.
+bool fused_fprop_supported(int N, int f, int fo, const float *wf);
+hipError_t launch_fused_fprop(const float *x, const float *wf, float *y, int S, int f, int fo, int h, int w,
+                              int kh, int kw, int N, LaunchCtx st);
+
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
 hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);
 

@@ -268,3 +268,38 @@ def test_contraction_addressing_paths_agree(hd, cfg, monkeypatch):
         assert torch.equal(a, b)
     ref = oracle.conv_fprop(x, w)
     assert np.max(np.abs(fast[0].cpu().numpy() - ref)) / np.max(np.abs(ref)) <= 1e-4
+
+
+FUSED = [dict(S=16, f=16, fo=16, h=13, w=13, kh=3, kw=3),      # the smallest benchmark layer (basis 14)
+         dict(S=5, f=4, fo=7, h=16, w=16, kh=5, kw=5),         # basis 16, padded LDS rows, ragged f'
+         dict(S=3, f=32, fo=8, h=12, w=11, kh=2, kw=4),        # basis 12, f fills the plane tile
+         dict(S=7, f=8, fo=3, h=8, w=8, kh=3, kw=3),           # basis 8 (64 planes per tile)
+         dict(S=1, f=8, fo=32, h=14, w=9, kh=1, kw=1)]
+
+
+@pytest.mark.parametrize("cfg", FUSED, ids=lambda c: "S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c))
+def test_fused_fprop(hd, lib, cfg):
+    """The one-launch fprop of small layers against the oracle and against the three-launch path."""
+    import torch
+    x, w, _ = synth.conv_inputs(seed=88, **cfg)
+    dx, dw = _dev(x), _dev(w)
+    wf = hd.fft_conv_transform_weights(dw, cfg["h"], cfg["w"])
+    y = hd.fft_conv_fprop_fused(dx, wf, cfg["fo"], cfg["kh"], cfg["kw"])
+    torch.cuda.synchronize()
+    ref = oracle.conv_fprop(x, w)
+    assert _relerr(_np(y), ref) <= TOL
+    y3 = hd.fft_conv_fprop_weights(dx, wf, cfg["fo"], cfg["kh"], cfg["kw"])
+    assert float((y - y3).abs().max()) <= 2e-5 * float(np.max(np.abs(ref)))
+
+
+def test_fused_fprop_unsupported_shapes(hd, lib):
+    import torch
+    for cfg in (dict(S=2, f=12, fo=8, h=13, w=13, kh=3, kw=3),     # f does not divide the plane tile
+                dict(S=2, f=16, fo=40, h=13, w=13, kh=3, kw=3),    # f' beyond one plane tile
+                dict(S=2, f=32, fo=32, h=13, w=13, kh=3, kw=3),    # more than 256 weight planes
+                dict(S=2, f=16, fo=16, h=27, w=27, kh=5, kw=5)):   # basis 28
+        x = torch.zeros((cfg["S"], cfg["f"], cfg["h"], cfg["w"]), device="cuda")
+        w = torch.zeros((cfg["fo"], cfg["f"], cfg["kh"], cfg["kw"]), device="cuda")
+        wf = hd.fft_conv_transform_weights(w, cfg["h"], cfg["w"])
+        with pytest.raises(lib.FFTConvError, match="unsupported"):
+            hd.fft_conv_fprop_fused(x, wf, cfg["fo"], cfg["kh"], cfg["kw"])
