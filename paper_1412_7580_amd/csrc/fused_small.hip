@@ -43,6 +43,7 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fused_fprop_kernel(FusedPa
         const float *wi = wr + T;
         const float *xr = smem + (bin * 2) * T, *xi = xr + T;
         float yr = 0.f, yi = 0.f;
+#pragma unroll 4
         for (int i = 0; i < f; i += 4) {
             const float4 a = *reinterpret_cast<const float4 *>(wr + i), b = *reinterpret_cast<const float4 *>(wi + i);
             const float4 p = *reinterpret_cast<const float4 *>(xr + i), q = *reinterpret_cast<const float4 *>(xi + i);
