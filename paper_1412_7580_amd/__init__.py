@@ -132,6 +132,7 @@ class Handle:
         self._h = ctypes.c_void_p()
         _check(self._lib.fftconv_create(ctypes.byref(self._h), device), "fftconv_create")
         self.device = device
+        self._stream = 0               # a new handle runs on the null stream
 
     def close(self):
         if self._h:
@@ -147,7 +148,9 @@ class Handle:
     def _sync_stream(self):
         import torch
         s = torch.cuda.current_stream().cuda_stream
-        _check(self._lib.fftconv_set_stream(self._h, ctypes.c_void_p(s)), "fftconv_set_stream")
+        if s != self._stream:          # the handle keeps its stream: tell it only about changes
+            _check(self._lib.fftconv_set_stream(self._h, ctypes.c_void_p(s)), "fftconv_set_stream")
+            self._stream = s
 
     def workspace_bytes(self, pass_, S, f, fo, h, w, kh, kw) -> int:
         return int(self._lib.fftconv_workspace_bytes(pass_, S, f, fo, h, w, kh, kw))
