@@ -2,9 +2,11 @@
 """Benchmark of the frequency-domain convolution hot path on one MI355X.
 
 One step = fprop + bprop + accGrad of the headline layer (S=128, f=f'=64, 27x27 input,
-5x5 kernel, 32x32 Fourier basis), i.e. twelve kernel launches: for each pass the FFT of
-both operands, the per-bin complex contraction and the inverse FFT with crop.  Inputs are
-seeded synthetic fp32 tensors already resident in device memory.
+5x5 kernel, 32x32 Fourier basis) as the two calls fft_conv_fprop_save + fft_conv_backward:
+seven kernel launches (x, w and gy are transformed once each, the two backward contractions
+share a launch, three inverse transforms with crop).  Inputs are seeded synthetic fp32 tensors
+already resident in device memory.  `extra` holds the same step as three independent passes,
+on the library's own Fourier basis, the other configurations, tiled layers, the FFT sweep.
 
 Prints ONE JSON line: effective TFLOP/s (direct-convolution FLOP count over measured time),
 the roofline of the dominant kernel (durations from HIP events recorded by the library on its
