@@ -457,6 +457,26 @@ def weights_ahead(hd, reps=30):
     return out
 
 
+def device_copy_bandwidth(reps=20):
+    """Plain device-to-device copy of 256 MiB and 1 GiB (read + write bytes over time): what the
+    memory system delivers to the simplest kernel, for reading the FFT stages' GB/s against."""
+    import torch
+    out = {}
+    for mib in (256, 1024):
+        a = torch.ones(mib * (1 << 20) // 4, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            b.copy_(a)
+        e1.record(); torch.cuda.synchronize()
+        out[f"{mib}MiB"] = round(2 * a.numel() * 4 / (e0.elapsed_time(e1) / reps) / 1e6, 1)
+        del a, b
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -640,6 +660,8 @@ def main():
         extra["paper_table4_layers"] = table4_layers(hd)
         torch.cuda.empty_cache()
         extra["weights_transformed_ahead"] = weights_ahead(hd)
+        torch.cuda.empty_cache()
+        extra["device_copy_GBps"] = device_copy_bandwidth()
         torch.cuda.empty_cache()
         extra["fft_sweep_256MiB"] = fft_sweep(hd)
         torch.cuda.empty_cache()
