@@ -477,6 +477,41 @@ def device_copy_bandwidth(reps=20):
     return out
 
 
+def conv_sweep_3x3(hd, reps=10):
+    """The workload of the paper's comparison of fbfft against cuFFT inside the convolution
+    (Section 5.4): 3x3 kernels, h = w in {13, 16, 27, 32, 57, 64}, S = f = f' in {16, 32, 64, 128},
+    all three passes (here: fft_conv_fprop_save + fft_conv_backward, library's basis).  The paper
+    reports only speed ratios over its cuFFT path for these; the table is ms per step and
+    effective TFLOP/s on this chip."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    out = {}
+    for hw in (13, 16, 27, 32, 57, 64):
+        row = {}
+        for n in (16, 32, 64, 128):
+            mk = lambda *shape: torch.rand(shape, device="cuda", generator=gen) * 2 - 1
+            x, wt, gy = mk(n, n, hw, hw), mk(n, n, 3, 3), mk(n, n, hw - 2, hw - 2)
+            y, gx, gw = torch.empty_like(gy), torch.empty_like(x), torch.empty_like(wt)
+            saved = torch.empty(hd.saved_bytes(n, n, n, hw, hw, 3, 3) // 4, device="cuda", dtype=torch.float32)
+
+            def step():
+                hd.fft_conv_fprop_save(x, wt, saved, y=y)
+                hd.fft_conv_backward(gy, saved, n, hw, hw, 3, 3, gx=gx, gw=gw)
+            for _ in range(3):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                step()
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / reps
+            fl = 3 * 2.0 * n * n * n * 9 * (hw - 2) ** 2
+            row[f"S=f=f'={n}"] = {"ms": round(sec * 1e3, 4), "effective_TFLOPs": round(fl / sec / 1e12, 2)}
+            del x, wt, gy, y, gx, gw, saved
+        out[f"{hw}x{hw}"] = row
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -660,6 +695,8 @@ def main():
         extra["paper_table4_layers"] = table4_layers(hd)
         torch.cuda.empty_cache()
         extra["weights_transformed_ahead"] = weights_ahead(hd)
+        torch.cuda.empty_cache()
+        extra["paper_section5_conv_sweep_3x3"] = conv_sweep_3x3(hd)
         torch.cuda.empty_cache()
         extra["device_copy_GBps"] = device_copy_bandwidth()
         torch.cuda.empty_cache()
