@@ -62,3 +62,41 @@ def test_graph_replay_equals_eager(hd, lib, cfg):
         torch.cuda.synchronize()
         assert torch.equal(y, ref[0]) and torch.equal(gx, ref[1]) and torch.equal(gw, ref[2]), rep
         _ = (dx * 2).sum().item()       # eager work and a synchronisation between replays
+
+
+def test_graph_replay_of_inference_paths(hd, lib):
+    """fprop on weights transformed ahead, as three launches (caller's workspace) and as the
+    one-launch kernel (no workspace at all): captured once, replayed with changing inputs."""
+    import torch
+    cfg = dict(S=16, f=16, fo=16, h=16, w=16, kh=3, kw=3)       # basis 16: the fused kernel needs > 64 KB of LDS
+    x, w, _ = synth.conv_inputs(seed=601, **cfg)
+    dx, dw = _dev(x), _dev(w)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    wf = hd.fft_conv_transform_weights(dw, cfg["h"], cfg["w"])
+    ws = torch.empty(hd.workspace_bytes(lib.FPROP, *dims) // 4, device="cuda", dtype=torch.float32)
+    y3 = torch.empty((16, 16, 14, 14), device="cuda")
+    y1 = torch.empty_like(y3)
+
+    def step():
+        hd.fft_conv_fprop_weights(dx, wf, cfg["fo"], 3, 3, y=y3, ws=ws)
+        hd.fft_conv_fprop_fused(dx, wf, cfg["fo"], 3, 3, y=y1)
+
+    def eager():
+        step()
+        torch.cuda.synchronize()
+        return y3.clone(), y1.clone()
+
+    ref = eager()                       # warm-up: kernel attributes are set outside the capture
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        if rep == 1:
+            dx.mul_(-1.5)
+            ref = eager()
+        y3.zero_(); y1.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y3, ref[0]) and torch.equal(y1, ref[1]), rep
+        _ = (dx + 1).sum().item()
