@@ -79,13 +79,17 @@ static hipError_t run_fused(const float *x, const float *wf, float *y, int S, in
     fp.wf = wf; fp.f = f; fp.fo = fo;
     fp.x_stride = (long)f * h * w; fp.y_stride = (long)fo * oh * ow;
     const size_t img = (size_t)T * N * NB * 2;           // floats of one LDS image
-    // the first image's place also serves the forward staging and the inverse's transposed
-    // data and output block; each fits because h, w, oh, ow <= N
-    if (lds_fwd > img * sizeof(float) || (size_t)T * iv.MPS * sizeof(float2) > img * sizeof(float) ||
-        ((size_t)T * oh * ow + 3) * sizeof(float) > img * sizeof(float))
-        return hipErrorInvalidValue;
-    fp.img = (int)img;
-    const size_t lds = 2 * img * sizeof(float);
+    // the first region holds, one after the other in time, the forward staging and transposed
+    // data, the spectra X, and the inverse's transposed data and output block; the product's
+    // image lies behind it
+    size_t first = img * sizeof(float);
+    if (lds_fwd > first) first = lds_fwd;
+    if ((size_t)T * iv.MPS * sizeof(float2) > first) first = (size_t)T * iv.MPS * sizeof(float2);
+    if (((size_t)T * oh * ow + 3) * sizeof(float) > first) first = ((size_t)T * oh * ow + 3) * sizeof(float);
+    first = (first + 15) / 16 * 16;
+    fp.img = (int)(first / sizeof(float));
+    const size_t lds = first + img * sizeof(float);
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
     auto k = fused_fprop_kernel<L, G, T>;
     if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
     launch_kernel(k, dim3((unsigned)S), dim3(BT), lds, st, fp);
@@ -105,10 +109,11 @@ hipError_t launch_fused_fprop(const float *x, const float *wf, float *y, int S, 
                               int kh, int kw, int N, LaunchCtx st) {
     if (!fused_fprop_supported(N, f, fo, wf) || h > N || w > N) return hipErrorInvalidValue;
     switch (N) {
-        case 8: return run_fused<8, 1, 64>(x, wf, y, S, f, fo, h, w, kh, kw, st);
-        case 12: return run_fused<12, 1, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
-        case 14: return run_fused<14, 1, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
-        case 16: return run_fused<16, 1, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
+        // lane pairs: twice the lanes for the product stage, whose W gathers set its pace
+        case 8: return run_fused<4, 2, 64>(x, wf, y, S, f, fo, h, w, kh, kw, st);
+        case 12: return run_fused<6, 2, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
+        case 14: return run_fused<7, 2, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
+        case 16: return run_fused<8, 2, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -67,10 +67,45 @@ static int check(const char *what, const float *dev, const double *ref, size_t n
     return rel <= tol ? 0 : 1;
 }
 
-int main(void) {
+/* `check_passes --time`: microseconds per fprop of the smallest benchmark layer (S = f = f' = 16,
+ * 13x13, 3x3) driven from C, where no interpreter stands between two launches: the ordinary call,
+ * the call on weights transformed ahead, and the one-launch kernel. */
+static int time_small_layer(fftconv_handle hd) {
+    const int S = 16, f = 16, fo = 16, h = 13, w = 13, k = 3, o = h - k + 1, reps = 2000;
+    const size_t nx = (size_t)S * f * h * w, nw = (size_t)fo * f * k * k, ny = (size_t)S * fo * o * o;
+    float *x = host_random(nx), *wt = host_random(nw);
+    float *dx = to_device(x, nx), *dw = to_device(wt, nw), *dy;
+    void *ws, *wf;
+    const size_t wsb = fftconv_workspace_bytes(FFTCONV_FPROP, S, f, fo, h, w, k, k);
+    const size_t wfb = fftconv_weights_bytes(f, fo, h, w, k, k, 0, 0);
+    HIP_OK(hipMalloc((void **)&dy, ny * sizeof(float)));
+    HIP_OK(hipMalloc(&ws, wsb));
+    HIP_OK(hipMalloc(&wf, wfb));
+    FC_OK(fft_conv_transform_weights(hd, dw, wf, wfb, f, fo, h, w, k, k, 0, 0));
+    hipEvent_t e0, e1;
+    HIP_OK(hipEventCreate(&e0)); HIP_OK(hipEventCreate(&e1));
+    for (int variant = 0; variant < 3; ++variant) {
+        float ms = 0;
+        for (int r = -50; r < reps; ++r) {          /* 50 untimed calls first */
+            if (r == 0) HIP_OK(hipEventRecord(e0, 0));
+            if (variant == 0) FC_OK(fft_conv_fprop(hd, dx, dw, dy, S, f, fo, h, w, k, k, ws, wsb));
+            else if (variant == 1) FC_OK(fft_conv_fprop_weights(hd, dx, wf, wfb, dy, S, f, fo, h, w, k, k, 0, 0, ws, wsb));
+            else FC_OK(fft_conv_fprop_fused(hd, dx, wf, wfb, dy, S, f, fo, h, w, k, k));
+        }
+        HIP_OK(hipEventRecord(e1, 0));
+        HIP_OK(hipEventSynchronize(e1));
+        HIP_OK(hipEventElapsedTime(&ms, e0, e1));
+        printf("%-34s %.2f us per call\n", variant == 0 ? "fft_conv_fprop" : variant == 1 ? "fft_conv_fprop_weights" : "fft_conv_fprop_fused",
+               ms * 1e3 / reps);
+    }
+    return 0;
+}
+
+int main(int argc, char **argv) {
     int bad = 0;
     fftconv_handle hd;
     FC_OK(fftconv_create(&hd, 0));
+    if (argc > 1 && strcmp(argv[1], "--time") == 0) return time_small_layer(hd);
 
     /* ---- one layer, three passes, ordinary and through a forced tile basis */
     const int S = 3, f = 5, fo = 4, h = 21, w = 18, kh = 3, kw = 5, oh = h - kh + 1, ow = w - kw + 1;
