@@ -206,8 +206,9 @@ int fft_conv_bprop_weights(fftconv_handle hd, const float *gy, const void *wf, s
  * of the matrix product with the transform kernels).  One workgroup carries one sample through
  * transform, contraction and inverse; it needs no workspace.  Same result as fft_conv_fprop up
  * to rounding.  Supported when the layer's basis is at most 16 (images up to 16x16, unpadded),
- * f is a multiple of 4 that divides 32 (64 at basis 8), fo <= 32 (64) and f * fo <= 256:
- * otherwise FFTCONV_UNSUPPORTED, and the caller uses fft_conv_fprop_weights.
+ * f is a multiple of 4 that divides 32 (64 at basis 8), fo <= 32 (64) and
+ * bins x f x fo <= 40000 (bins = N (N/2 + 1) of the layer's basis N; e.g. 16 x 16 planes at
+ * basis 14 or 16): otherwise FFTCONV_UNSUPPORTED, and the caller uses fft_conv_fprop_weights.
  */
 int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size_t wf_bytes, float *y,
                          int S, int f, int fo, int h, int w, int kh, int kw);

@@ -100,9 +100,11 @@ bool fused_fprop_supported(int N, int f, int fo, const float *wf) {
     const int tsh = fft2d_tile_log2(N);
     if (tsh < 5 || N > 16) return false;                // bases 8 .. 16: 32 or 64 planes per tile
     const int T = 1 << tsh;
-    // up to 256 weight planes: beyond that the vector-ALU contraction takes longer than the
-    // launches it saves (32 x 32 planes: 34 us against 20 for the three-launch path)
-    return f <= T && fo <= T && f * fo <= 256 && f % 4 == 0 && T % f == 0 && ((size_t)wf & 15) == 0;
+    // bins x weight planes up to 40000: beyond that the vector-ALU product stage takes longer
+    // than the launches it saves (measured at basis 14: 16 x 16 planes 10.1 us against 14.9 for
+    // the three-launch path, 16 x 32 13.2 against 14.6, 32 x 16 19.3 against 15.9, 32 x 32 31 against 16)
+    return f <= T && fo <= T && (long)N * (N / 2 + 1) * f * fo <= 40000 && f % 4 == 0 && T % f == 0 &&
+           ((size_t)wf & 15) == 0;
 }
 
 hipError_t launch_fused_fprop(const float *x, const float *wf, float *y, int S, int f, int fo, int h, int w,
