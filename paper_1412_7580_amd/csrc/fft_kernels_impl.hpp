@@ -23,6 +23,35 @@ __device__ __forceinline__ unsigned mdiv(unsigned x, MagicDiv md) {
     return (unsigned)(((unsigned long long)x * md.m) >> 32);
 }
 
+// Bank layout of the row-transformed data ("mid") that the 2-D kernels keep in LDS between their
+// two phases, rows of N/2 float2.  With G >= 4 lanes per line, G lanes of a half-wave work on
+// the same column of G rows (forward: consecutive rows; inverse: rows L apart) or on G blocks of
+// L entries of one row; with a row stride of N/2 (a multiple of 16 from N = 64 on) they would
+// all meet on one bank pair.  Measured on the stand-alone 128x128 forward kernel: 80 % of the
+// LDS cycles were bank conflicts.  Three paddings, none for G < 4:
+//   row stride:  G consecutive rows spread evenly over the banks: stride 4 or 12 modulo 16
+//                float2 (rows 8 banks apart), for G = 4 also 8 (16 banks apart);
+//   slot (forward, G = 8): entry s of a row sits at s + s / L, one float2 between blocks;
+//   row block (inverse): row a sits (a / L) * RP float2 further, RP = 32 / G.
+template <int L, int G>
+struct MidLayout {
+    static constexpr int N = L * G, NH = N / 2;
+    static constexpr bool slots = (G == 8);
+    static constexpr int need = NH + (slots ? NH / L : 0);
+    static constexpr int pick() {
+        if (G < 4) return NH;
+        for (int v = need;; ++v)
+            if (v % 16 == 4 || v % 16 == 12 || (G == 4 && v % 16 == 8)) return v;
+    }
+    static constexpr int MRS = pick();                 // row stride, float2
+    static constexpr int RP = (G < 4) ? 0 : 32 / G;    // inverse: extra float2 per block of L rows
+    __host__ __device__ static constexpr int slot(int s) { return slots ? s + s / L : s; }
+    __host__ __device__ static constexpr int row(int a) { return a * MRS + (a / L) * RP; }
+    // float2 per plane for h rows: forward (no row blocks) and inverse
+    static constexpr int fwd_plane(int h) { return h * MRS; }
+    static constexpr int inv_plane(int h) { return h * MRS + (h / L + 1) * RP; }
+};
+
 // Floats by which a global address lies past a 16-byte boundary (0..3).
 __device__ __forceinline__ unsigned misalign4(const float *p) { return (unsigned)(((size_t)p >> 2) & 3); }
 
@@ -271,7 +300,7 @@ struct BinStore {
 template <int L, int G, int T, bool CONV, bool OSTAGE, bool KEEP = false>
 __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned block) {
     static_assert(!KEEP || (CONV && OSTAGE), "KEEP leaves the plane-tiled image in LDS");
-    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
+    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G, MRS = MidLayout<L, G>::MRS;
     constexpr int NA = SplitRegs<L, G>::A;   // registers of split spectrum per lane
     constexpr int NBR = SplitRegs<L, G>::B;
     extern __shared__ float smem[];
@@ -342,17 +371,17 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
         float2 *mp = mid + p * prm.MPS;
         if constexpr (G == 1) {
 #pragma unroll
-            for (int k = 0; k < NH; ++k) mp[ra * NH + k] = make_float2(are[k], aim[k]);
+            for (int k = 0; k < NH; ++k) mp[ra * MRS + k] = make_float2(are[k], aim[k]);
             if (hasb) {
 #pragma unroll
-                for (int k = 0; k < NH; ++k) mp[rb * NH + k] = make_float2(bre[k], bim[k]);
+                for (int k = 0; k < NH; ++k) mp[rb * MRS + k] = make_float2(bre[k], bim[k]);
             }
         } else {
             const int row = (g & 1) ? rb : ra;
             if (!(g & 1) || hasb) {
 #pragma unroll
                 for (int k = 0; k < L; ++k)
-                    mp[row * NH + split_slot<L, G>(g, k)] = make_float2(are[k], aim[k]);
+                    mp[row * MRS + MidLayout<L, G>::slot(split_slot<L, G>(g, k))] = make_float2(are[k], aim[k]);
             }
         }
     }
@@ -367,12 +396,12 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
 
     float re[L], im[L];
     if (col_active) {
-        const float2 *mp = mid + cp * prm.MPS + cc;
+        const float2 *mp = mid + cp * prm.MPS + MidLayout<L, G>::slot(cc);
 #pragma unroll
         for (int m = 0; m < L; ++m) {
             const int r = cg + G * m;
             float2 v = make_float2(0.f, 0.f);
-            if (r < h_in) v = mp[r * NH];
+            if (r < h_in) v = mp[r * MRS];
             re[m] = v.x; im[m] = v.y;
         }
         fft_group<L, G, -1>(re, im, cg);
@@ -483,6 +512,7 @@ template <int L, int G, int T, bool CONV, bool ISTAGE, bool PRE = false>
 __device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned block, const float *pre_img = nullptr) {
     static_assert(!PRE || (CONV && !ISTAGE), "a preloaded tile is in the plane-tiled layout and needs no staging");
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
+    typedef MidLayout<L, G> ML;
     extern __shared__ float smem[];
     float2 *mid = reinterpret_cast<float2 *>(smem);
 
@@ -546,11 +576,12 @@ __device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned 
         }
         if constexpr (ISTAGE) __syncthreads();   // staged input fully consumed; `mid` overlays it
         if (cp < np) {
-            float2 *mp = mid + cp * prm.MPS + cc;
+            // row a = k + L * block: k rows plus `block` whole blocks of L rows
+            const int blk = group_block<G>(cg);
+            float2 *mp = mid + cp * prm.MPS + cc + blk * (L * ML::MRS + ML::RP);
 #pragma unroll
             for (int k = 0; k < L; ++k) {
-                const int a = k + L * group_block<G>(cg);
-                if (a < h_out) mp[a * NH] = make_float2(cre[k], cim[k]);
+                if (k + L * blk < h_out) mp[k * ML::MRS] = make_float2(cre[k], cim[k]);
             }
         }
     }
@@ -564,8 +595,8 @@ __device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned 
     const bool hasb = rb < h_out;
     float re[L], im[L];
     if (active) {
-        const float2 *A = mid + p * prm.MPS + ra * NH;
-        const float2 *B = mid + p * prm.MPS + (hasb ? rb : ra) * NH;
+        const float2 *A = mid + p * prm.MPS + ML::row(ra);
+        const float2 *B = mid + p * prm.MPS + ML::row(hasb ? rb : ra);
 #pragma unroll
         for (int m = 0; m < L; ++m) {
             const int k2 = g + G * m;
@@ -811,7 +842,7 @@ static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in
         prm.RS = up_to_residue(w_in, G);
         prm.IPS = up_to_residue(h_in * prm.RS, (G * rows32) % 32);
     }
-    prm.MPS = (h_in * NH) | 1;
+    prm.MPS = MidLayout<L, G>::fwd_plane(h_in) | 1;
     prm.vecw = (((size_t)in & 15) == 0 && w_in % 4 == 0) ? 4 : ((((size_t)in & 7) == 0 && w_in % 2 == 0) ? 2 : 1);
     prm.div_wv = make_magic((unsigned)(w_in / prm.vecw));
     prm.div_h = make_magic((unsigned)h_in);
@@ -922,7 +953,7 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
         h_out += view->oy; w_out += view->ox;
     }
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_out = h_out; prm.w_out = w_out;
-    prm.MPS = (h_out * NH) | 1;
+    prm.MPS = MidLayout<L, G>::inv_plane(h_out) | 1;
     prm.lay.tsh = fft2d_tile_log2(N);
     prm.lay.bins = fft2d_layout_bins(N);
     prm.scale = scale; prm.accumulate = accumulate ? 1 : 0;

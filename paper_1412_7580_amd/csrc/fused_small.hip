@@ -71,7 +71,7 @@ static hipError_t run_fused(const float *x, const float *wf, float *y, int S, in
     const int oh = h - kh + 1, ow = w - kw + 1;
     Inv2dParams &iv = fp.inv;
     iv.in = nullptr; iv.out = y; iv.planes = fo; iv.h_out = oh; iv.w_out = ow;
-    iv.MPS = (oh * NH) | 1;
+    iv.MPS = MidLayout<L, G>::inv_plane(oh) | 1;
     iv.lay = fp.fwd.lay;
     iv.scale = 1.0f / ((float)N * (float)N); iv.accumulate = 0;
     iv.vec_ok = 0; iv.in_vec_ok = 0; iv.tiled = 0; iv.info_off = 0; iv.win_h = iv.win_w = 0;
