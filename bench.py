@@ -512,6 +512,44 @@ def conv_sweep_3x3(hd, reps=10):
     return out
 
 
+def rectangular_layers(hd, reps=10):
+    """Layers with non-square images (sides up to 32): the three passes on the rectangular basis
+    the ordinary entry points choose, beside the same layer on the square basis of the larger
+    side (named through the *_tiled calls).  us per three passes, kernels only."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    mk = lambda *shape: torch.rand(shape, device="cuda", generator=gen) * 2 - 1
+    out = {}
+    for (S, f, fo, h, w, kh, kw) in ((128, 96, 256, 27, 13, 5, 3), (128, 96, 256, 13, 27, 3, 5),
+                                     (128, 64, 64, 16, 32, 3, 3), (128, 64, 64, 8, 32, 3, 3),
+                                     (128, 64, 64, 32, 8, 3, 3), (128, 64, 64, 20, 24, 3, 3)):
+        x, wt, gy = mk(S, f, h, w), mk(fo, f, kh, kw), mk(S, fo, h - kh + 1, w - kw + 1)
+        y, gx, gw = torch.empty_like(gy), torch.empty_like(x), torch.empty_like(wt)
+        nr, nc, _ = hd.layer_basis(h, w, kh, kw)
+        n = max(nr, nc)
+
+        def timed(step):
+            for _ in range(3):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                step()
+            torch.cuda.synchronize()
+            return round((time.perf_counter() - t0) / reps * 1e6, 1)
+
+        def rect():
+            hd.fft_conv_fprop(x, wt, y=y); hd.fft_conv_bprop(gy, wt, h, w, gx=gx); hd.fft_conv_accgrad(x, gy, gw=gw)
+
+        def square():
+            hd.fft_conv_fprop_tiled(x, wt, n, y=y); hd.fft_conv_bprop_tiled(gy, wt, h, w, n, gx=gx)
+            hd.fft_conv_accgrad_tiled(x, gy, n, gw=gw)
+        out[f"S{S}_f{f}_fo{fo}_{h}x{w}_k{kh}x{kw}"] = {"basis": f"{nr}x{nc}", "us": timed(rect),
+                                                       "square_basis": n, "square_us": timed(square)}
+        del x, wt, gy, y, gx, gw
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -697,6 +735,8 @@ def main():
         extra["weights_transformed_ahead"] = weights_ahead(hd)
         torch.cuda.empty_cache()
         extra["paper_section5_conv_sweep_3x3"] = conv_sweep_3x3(hd)
+        torch.cuda.empty_cache()
+        extra["rectangular_basis"] = rectangular_layers(hd)
         torch.cuda.empty_cache()
         extra["device_copy_GBps"] = device_copy_bandwidth()
         torch.cuda.empty_cache()

@@ -18,11 +18,12 @@
  *    handle (the buffer policy of Section 3.3).
  *  - Every function returns an fftconv_status; arguments are validated before anything
  *    is launched, so on an error other than FFTCONV_HIP_ERROR no device work was issued.
- *  - The Fourier basis is square with N = the smallest power of two >= max(h, w),
- *    at least 8 and at most 128 (the range of the paper's 2-D kernels, Section 5.3).
- *    Layers that would need a larger basis, and layers for which it is clearly cheaper, are
- *    tiled (Section 6): the passes then run on windows of the images with a small basis,
- *    with identical results.
+ *  - The Fourier basis is the smallest supported size that holds the image (8 ... 128: the
+ *    powers of two of the paper's 2-D kernels, Section 5.3, and sizes 2^a x {3, 5, 7} between
+ *    them), square, or rectangular (each side on its own size) when both sides are at most
+ *    32 and differ.  Layers that would need a larger basis, and layers for which it is
+ *    clearly cheaper, are tiled (Section 6): the passes then run on windows of the images
+ *    with a small basis, with identical results.  fftconv_layer_basis() tells which.
  */
 #ifndef FFTCONV_H
 #define FFTCONV_H
@@ -54,6 +55,12 @@ int fftconv_destroy(fftconv_handle h);
 int fftconv_set_stream(fftconv_handle h, void *stream);
 const char *fftconv_status_string(int status);
 
+/* The basis the ordinary (and padded, saved-transform and weights-ahead) entry points use for a
+ * layer: *n_rows x *n_cols (equal unless rectangular).  Returns 0 when the layer runs whole on
+ * that basis, 1 when it is tiled with that basis, and a negative fftconv_status for invalid
+ * or unsupported shapes.  Host only. */
+int fftconv_layer_basis(int h, int w, int kh, int kw, int pad_h, int pad_w, int *n_rows, int *n_cols);
+
 /* Bytes of device scratch one pass needs: the three frequency-domain tensors of Table 1
  * (both operands and the product), Hermitian half, complex fp32, in the library's private
  * bin-major layout.  Returns 0 for invalid or unsupported shapes. */
@@ -64,9 +71,12 @@ size_t fftconv_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int
  *   S minibatch, f input planes, fo output planes (f'), h x w input, kh x kw kernel,
  *   oh = h-kh+1, ow = w-kw+1.  Stride 1, no margin padding (Section 2 excludes strides).
  * Fourier basis: the smallest of 8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64 that holds the
- * image, square (the powers of two of Section 5 and, between them, the sizes 2^a x {3, 5, 7}
- * of the search space of Section 3.4); larger images are tiled (see the tiled passes below).
- * The same basis serves all three passes of a layer.
+ * image (the powers of two of Section 5 and, between them, the sizes 2^a x {3, 5, 7} of the
+ * search space of Section 3.4); larger images are tiled (see the tiled passes below).  The
+ * basis is square, N x N with N chosen for max(h, w), except that an image whose sides both
+ * fit 32 and call for different sizes gets a rectangular basis N_h x N_w, each side the
+ * smallest size that holds it (Section 3.1 only asks that every operand fit the common
+ * basis).  The same basis serves all three passes of a layer.
  * `ws`/`ws_bytes`: optional caller-owned device scratch of at least
  * fftconv_workspace_bytes(); with ws == NULL the handle grows and reuses its own buffer
  * (hipMalloc on first use or growth only).
@@ -205,7 +215,7 @@ int fft_conv_bprop_weights(fftconv_handle hd, const float *gy, const void *wf, s
  * of fft_conv_fprop_weights cost more than the arithmetic (Section 6 plans such an integration
  * of the matrix product with the transform kernels).  One workgroup carries one sample through
  * transform, contraction and inverse; it needs no workspace.  Same result as fft_conv_fprop up
- * to rounding.  Supported when the layer's basis is at most 16 (images up to 16x16, unpadded),
+ * to rounding.  Supported when the layer's basis is square and at most 16 (unpadded images),
  * f is a multiple of 4 that divides 32 (64 at basis 8), fo <= 32 (64) and
  * bins x f x fo <= 40000 (bins = N (N/2 + 1) of the layer's basis N; e.g. 16 x 16 planes at
  * basis 14 or 16): otherwise FFTCONV_UNSUPPORTED, and the caller uses fft_conv_fprop_weights.

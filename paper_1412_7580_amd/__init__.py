@@ -19,7 +19,7 @@ SYMBOLS = [
     "fft_r2c_1d", "fft_c2r_1d", "fft_r2c_2d", "fft_c2r_2d",
     "fftconv_set_profiling", "fftconv_last_kernel_ms",
     "fftconv_saved_bytes", "fftconv_backward_workspace_bytes", "fft_conv_fprop_save", "fft_conv_backward",
-    "fftconv_tiled_workspace_bytes", "fftconv_tile_basis",
+    "fftconv_tiled_workspace_bytes", "fftconv_tile_basis", "fftconv_layer_basis",
     "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled", "fftconv_autotune_basis",
     "fftconv_saved_bytes_tiled", "fftconv_backward_workspace_bytes_tiled",
     "fft_conv_fprop_save_tiled", "fft_conv_backward_tiled",
@@ -74,6 +74,8 @@ def load_library():
     lib.fftconv_tiled_workspace_bytes.argtypes = [i] * 9
     lib.fftconv_tiled_workspace_bytes.restype = sz
     lib.fftconv_tile_basis.argtypes = [i] * 5
+    lib.fftconv_layer_basis.argtypes = [i] * 6 + [ctypes.POINTER(ctypes.c_int)] * 2
+    lib.fftconv_layer_basis.restype = i
     lib.fft_conv_fprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
     lib.fft_conv_bprop_tiled.argtypes = [vp, vp, vp, vp] + [i] * 8 + [vp, sz]
     lib.fft_conv_accgrad_tiled.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i, i, vp, sz]
@@ -257,6 +259,14 @@ class Handle:
 
     def tile_basis(self, h, w, kh, kw, tile_n) -> int:
         return int(self._lib.fftconv_tile_basis(h, w, kh, kw, tile_n))
+
+    def layer_basis(self, h, w, kh, kw, pad_h=0, pad_w=0):
+        """(rows, columns, tiled) of the basis the ordinary entry points use for a layer."""
+        nr, nc = ctypes.c_int(0), ctypes.c_int(0)
+        rc = int(self._lib.fftconv_layer_basis(h, w, kh, kw, pad_h, pad_w, ctypes.byref(nr), ctypes.byref(nc)))
+        if rc < 0:
+            _check(-rc, "fftconv_layer_basis")
+        return nr.value, nc.value, bool(rc)
 
     def fft_conv_fprop_tiled(self, x, wt, tile_n, y=None, ws=None):
         import torch

@@ -10,8 +10,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfftconv.so")
 SOURCES = ["api.hip", "fft_kernels.hip", "fft_kernels_mixed_small.hip", "fft_kernels_mixed_large.hip", "fft1d_mixed.hip",
-           "fused_small.hip", "cgemm_kernels.hip", "cgemm_bingroup.hip"]
-HEADERS = ["fft_core.hpp", "fft_kernels_impl.hpp", "kernels.hpp", "gemm_params.hpp", os.path.join("..", "..", "include", "fftconv.h")]
+           "fft_rect_fwd.hip", "fft_rect_inv.hip", "fused_small.hip", "cgemm_kernels.hip", "cgemm_bingroup.hip"]
+HEADERS = ["fft_core.hpp", "fft_kernels_impl.hpp", "fft_rect_impl.hpp", "kernels.hpp", "gemm_params.hpp", os.path.join("..", "..", "include", "fftconv.h")]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -41,7 +41,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         subprocess.check_call(cmd)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB]
     if verbose:

@@ -47,6 +47,8 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct PassPlan {
     int N, bins;
+    bool rect;          // rectangular basis Nr x Nc (untiled, unpadded layers only); N = the larger side
+    int Nr, Nc;
     long planesA, planesB, planesC;
     int hA, wA, hB, wB, hC, wC;
     bool conjA, conjB;
@@ -116,10 +118,16 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
     if (whole) { tiled = false; N = tile_n; }
     if (tiled && tile_n < 0) tile_n = 0;
     if (N > 128) { tiled = true; if (tile_n < 0) tile_n = 0; }
+    // each side on the smallest basis that holds it, where the rectangular kernels exist
+    int nr = N, nc = N;
+    if (!tiled && !whole) {
+        nr = basis_size(h, 1); nc = basis_size(1, w);
+        if (nr == nc || !fft2d_rect_supported(nr, nc)) nr = nc = N;
+    }
     if (!tiled && !whole) {
         double cost = 0;
         const int tn = pick_tile_basis(hp, wp, kh, kw, &cost);
-        if (tn && tn < N && cost < 0.8 * N * (N / 2 + 1) * basis_weight(N)) { tiled = true; tile_n = tn; }
+        if (tn && tn < N && cost < 0.8 * nr * (nc / 2 + 1) * basis_weight(N)) { tiled = true; tile_n = tn; }
     }
     if (tiled && tile_n == 0) tile_n = pick_tile_basis(hp, wp, kh, kw);
     if (tiled && tile_n == 0) return FFTCONV_UNSUPPORTED;   // kernel larger than every basis
@@ -129,6 +137,12 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
     p->N = N;
     p->bins = fft2d_layout_bins(N);
     p->lay.tsh = fft2d_tile_log2(N);
+    p->rect = false; p->Nr = p->Nc = N;
+    if (!tiled && !whole && nr != nc) {
+        p->rect = true; p->Nr = nr; p->Nc = nc;
+        p->bins = fft2d_rect_layout_bins(nr, nc);
+        p->lay.tsh = fft2d_rect_tile_log2(nr, nc);
+    }
     p->lay.bins = p->bins;
     p->conjA = p->conjB = false;
     p->tiled = tiled;
@@ -243,6 +257,16 @@ static LaunchCtx next_ctx(fftconv_ctx *c) {
 
 static float *at(void *base, size_t off) { return reinterpret_cast<float *>(static_cast<char *>(base) + off); }
 
+// One operand's forward transform into the plane-tiled layout of the plan's basis.
+static hipError_t transform(const PassPlan &p, const float *in, float *out, long planes, int h, int w, LaunchCtx lc,
+                            const PlaneView *view = nullptr) {
+    if (p.rect) {
+        const FwdOperand op{in, out, planes, h, w, nullptr};
+        return launch_fft2d_r2c_rect(&op, 1, p.Nr, p.Nc, lc);
+    }
+    return launch_fft2d_r2c(in, out, planes, h, w, p.N, true, lc, view);
+}
+
 // Forward transforms of both operands of a pass.  For the bases up to 32 they share one launch
 // (two short kernels would queue behind each other's ramp-up and tail; measured 14 us of 204
 // per step on the 32-basis layer).  For basis 64 and up the transform is ALU-bound and a shared
@@ -252,15 +276,19 @@ static float *at(void *base, size_t off) { return reinterpret_cast<float *>(stat
 static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a, float *AF,
                                const float *b, float *BF) {
     const PlaneView *va = p.viewA ? &p.vA : nullptr, *vb = p.viewB ? &p.vB : nullptr;
+    if (p.rect) {
+        FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, nullptr}, {b, BF, p.planesB, p.hB, p.wB, nullptr}};
+        return launch_fft2d_r2c_rect(ops, 2, p.Nr, p.Nc, next_ctx(c));
+    }
     if (p.lay.tsh >= 4) {
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, va}, {b, BF, p.planesB, p.hB, p.wB, vb}};
         return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c));
     }
     // one event pair around both launches: start from the first, stop from the second
     LaunchCtx lc = next_ctx(c);
-    hipError_t e = launch_fft2d_r2c(a, AF, p.planesA, p.hA, p.wA, p.N, true, LaunchCtx{lc.stream, lc.start, nullptr}, va);
+    hipError_t e = transform(p, a, AF, p.planesA, p.hA, p.wA, LaunchCtx{lc.stream, lc.start, nullptr}, va);
     if (e != hipSuccess) return e;
-    return launch_fft2d_r2c(b, BF, p.planesB, p.hB, p.wB, p.N, true, LaunchCtx{lc.stream, nullptr, lc.stop}, vb);
+    return transform(p, b, BF, p.planesB, p.hB, p.wB, LaunchCtx{lc.stream, nullptr, lc.stop}, vb);
 }
 
 // The contraction of one pass as the kernels see it.
@@ -275,7 +303,8 @@ static GemmProblem gemm_problem(const PassPlan &p, const float *AF, const float 
 
 // Inverse transform + crop of one pass's product (1/N^2 folded into the output scale).
 static hipError_t invert(fftconv_ctx *c, const PassPlan &p, const float *CF, float *out, float scale, int accumulate) {
-    const float s = scale / ((float)p.N * (float)p.N);
+    const float s = scale / ((float)p.Nr * (float)p.Nc);
+    if (p.rect) return launch_fft2d_c2r_rect(CF, out, p.planesC, p.Nr, p.Nc, p.hC, p.wC, s, accumulate != 0, next_ctx(c));
     return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c),
                             p.viewC ? &p.vC : nullptr);
 }
@@ -317,7 +346,7 @@ static int run_pass_weights(fftconv_ctx *c, int pass, const float *opA, const vo
     if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     float *AF = at(ws, p.offA), *CF = at(ws, p.offC);
     c->nk = 0;
-    hipError_t e = launch_fft2d_r2c(opA, AF, p.planesA, p.hA, p.wA, p.N, true, next_ctx(c), p.viewA ? &p.vA : nullptr);
+    hipError_t e = transform(p, opA, AF, p.planesA, p.hA, p.wA, next_ctx(c), p.viewA ? &p.vA : nullptr);
     if (e != hipSuccess) return hip_fail(c, e);
     if ((e = contract_and_invert(c, p, AF, static_cast<const float *>(wf), CF, out, 1.0f, 0)) != hipSuccess) return hip_fail(c, e);
     return FFTCONV_OK;
@@ -405,6 +434,15 @@ size_t fftconv_tiled_workspace_bytes(int pass, int S, int f, int fo, int h, int 
     PassPlan p;
     if (tile_n < 0 || make_plan(pass, S, f, fo, h, w, kh, kw, &p, tile_n) != FFTCONV_OK) return 0;
     return p.total;
+}
+
+int fftconv_layer_basis(int h, int w, int kh, int kw, int pad_h, int pad_w, int *n_rows, int *n_cols) {
+    PassPlan p;
+    const int rc = make_plan(FFTCONV_FPROP, 1, 1, 1, h, w, kh, kw, &p, -1, pad_h, pad_w);
+    if (rc != FFTCONV_OK) return -rc;
+    if (n_rows) *n_rows = p.Nr;
+    if (n_cols) *n_cols = p.Nc;
+    return p.tiled ? 1 : 0;
 }
 
 int fftconv_tile_basis(int h, int w, int kh, int kw, int tile_n) {
@@ -664,7 +702,7 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
     hd->nk = 0;
     hipError_t e;
     if (!pb.tiled) {
-        if ((e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+        if ((e = transform(pb, gy, GYF, pb.planesA, pb.hA, pb.wA, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
     } else {
         // gy cut twice: overlapping windows for bprop, disjoint tiles for accGrad
         if (gx && gw && pb.lay.tsh >= 4) {   // small bases: both in one launch, as for the two operands of a pass
@@ -756,7 +794,7 @@ int fft_conv_transform_weights(fftconv_handle hd, const float *wt, void *wf, siz
     if (rc != FFTCONV_OK) return rc;
     if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
     hd->nk = 0;
-    hipError_t e = launch_fft2d_r2c(wt, static_cast<float *>(wf), p.planesB, p.hB, p.wB, p.N, true, next_ctx(hd));
+    hipError_t e = transform(p, wt, static_cast<float *>(wf), p.planesB, p.hB, p.wB, next_ctx(hd));
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
@@ -779,7 +817,7 @@ int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size
     int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
     if (rc != FFTCONV_OK) return rc;
     if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
-    if (p.tiled || !fused_fprop_supported(p.N, f, fo, static_cast<const float *>(wf))) return FFTCONV_UNSUPPORTED;
+    if (p.tiled || p.rect || !fused_fprop_supported(p.N, f, fo, static_cast<const float *>(wf))) return FFTCONV_UNSUPPORTED;
     hd->nk = 0;
     const hipError_t e = launch_fused_fprop(x, static_cast<const float *>(wf), y, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd));
     if (e == hipErrorInvalidValue) return FFTCONV_UNSUPPORTED;   // the layer's planes do not fit the kernel's LDS plan

@@ -75,11 +75,6 @@ int fft2d_tile_log2(int N);
 // odd factor have, are never written by the transforms nor read by the inverse; the
 // contraction multiplies whatever they hold into the padding bins of its output.
 int fft2d_layout_bins(int N);
-// Bins per plane tile of the layout for basis N: N * (N/2 + 1) rounded up to a multiple of 8, so
-// that the contraction can always cut the bins into equal chunks per XCD.  The padding bins
-// (bases 12, 20 and 28 have some) are never written by the transforms nor read by the inverse;
-// the contraction multiplies whatever they hold into padding bins of its output.
-int fft2d_layout_bins(int N);
 
 // 2-D R2C of `planes` planes [h_in x w_in] zero-padded to N x N.
 //   conv layout: out = FreqLayout buffer (tile = fft2d_tile_log2(N)).
@@ -97,6 +92,16 @@ struct FwdOperand {
     const PlaneView *view = nullptr;
 };
 hipError_t launch_fft2d_r2c_multi(const FwdOperand *ops, int nops, int N, LaunchCtx st);
+
+// The same on a rectangular basis nr x nc (nr rows, nc columns; both at most 32 and different),
+// plane-tiled layout only, whole planes only (no windows).  The layout then has
+// bin = k1 * (nc/2+1) + k2 with the tile and bin count given by these functions.
+bool fft2d_rect_supported(int nr, int nc);
+int fft2d_rect_tile_log2(int nr, int nc);
+int fft2d_rect_layout_bins(int nr, int nc);
+hipError_t launch_fft2d_r2c_rect(const FwdOperand *ops, int nops, int nr, int nc, LaunchCtx st);   // nops 1 or 2
+hipError_t launch_fft2d_c2r_rect(const float *in, float *out, long planes, int nr, int nc, int h_out, int w_out,
+                                 float scale, bool accumulate, LaunchCtx st);
 
 // 2-D C2R + crop.  out[planes][h_out][w_out] = scale * real inverse (the caller folds 1/N^2
 // into `scale`), added to the previous contents when accumulate is set.

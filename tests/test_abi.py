@@ -57,6 +57,32 @@ def test_host_only_calls():
     assert lib.fftconv_tile_basis(20, 20, 9, 9, 8) == 0
 
 
+def test_layer_basis_on_the_host():
+    """Which basis the ordinary entry points take: square for square images, one size per side
+    for other images whose sides both fit 32, tiles beyond the largest basis."""
+    import ctypes
+    import paper_1412_7580_amd as pkg
+    lib = pkg.load_library()
+
+    def basis(h, w, kh, kw, ph=0, pw=0):
+        nr, nc = ctypes.c_int(-1), ctypes.c_int(-1)
+        rc = lib.fftconv_layer_basis(h, w, kh, kw, ph, pw, ctypes.byref(nr), ctypes.byref(nc))
+        return rc, nr.value, nc.value
+
+    assert basis(13, 13, 3, 3) == (0, 14, 14)
+    assert basis(27, 27, 5, 5) == (0, 28, 28)
+    assert basis(27, 13, 5, 3) == (0, 28, 14)
+    assert basis(8, 32, 3, 3) == (0, 8, 32)
+    assert basis(40, 30, 9, 9) == (0, 40, 40)            # a side beyond 32: square
+    assert basis(13, 27, 3, 3, 1, 1)[0] == 1             # margin padding: windows on a square basis
+    rc, nr, nc = basis(200, 200, 3, 3)
+    assert rc == 1 and nr == nc == lib.fftconv_tile_basis(200, 200, 3, 3, 0)
+    assert basis(4, 4, 5, 5)[0] == -1                    # kernel larger than the image
+    assert lib.fftconv_layer_basis(13, 13, 3, 3, 0, 0, None, None) == 0
+    # 28 x 14 basis: 28 * 8 = 224 bins
+    assert lib.fftconv_workspace_bytes(0, 16, 16, 16, 27, 13, 5, 3) == 3 * 256 * 224 * 2 * 4
+
+
 def test_no_oracle_in_product():
     """The product package must not reach into the oracle."""
     pkg_dir = os.path.join(ROOT, "paper_1412_7580_amd")

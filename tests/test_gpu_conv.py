@@ -274,7 +274,7 @@ FUSED = [dict(S=16, f=16, fo=16, h=13, w=13, kh=3, kw=3),      # the smallest be
          dict(S=5, f=4, fo=7, h=16, w=16, kh=5, kw=5),         # basis 16, padded LDS rows, ragged f'
          dict(S=3, f=32, fo=8, h=12, w=11, kh=2, kw=4),        # basis 12, f fills the plane tile
          dict(S=7, f=8, fo=3, h=8, w=8, kh=3, kw=3),           # basis 8 (64 planes per tile)
-         dict(S=1, f=8, fo=32, h=14, w=9, kh=1, kw=1)]
+         dict(S=1, f=8, fo=32, h=14, w=13, kh=1, kw=1)]  # non-square image on a square basis
 
 
 @pytest.mark.parametrize("cfg", FUSED, ids=lambda c: "S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c))
@@ -297,7 +297,8 @@ def test_fused_fprop_unsupported_shapes(hd, lib):
     for cfg in (dict(S=2, f=12, fo=8, h=13, w=13, kh=3, kw=3),     # f does not divide the plane tile
                 dict(S=2, f=16, fo=40, h=13, w=13, kh=3, kw=3),    # f' beyond one plane tile
                 dict(S=2, f=32, fo=32, h=13, w=13, kh=3, kw=3),    # more than 256 weight planes
-                dict(S=2, f=16, fo=16, h=27, w=27, kh=5, kw=5)):   # basis 28
+                dict(S=2, f=16, fo=16, h=27, w=27, kh=5, kw=5),    # basis 28
+                dict(S=1, f=8, fo=32, h=14, w=9, kh=1, kw=1)):     # rectangular basis 14 x 12
         x = torch.zeros((cfg["S"], cfg["f"], cfg["h"], cfg["w"]), device="cuda")
         w = torch.zeros((cfg["fo"], cfg["f"], cfg["kh"], cfg["kw"]), device="cuda")
         wf = hd.fft_conv_transform_weights(w, cfg["h"], cfg["w"])

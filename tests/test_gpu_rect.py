@@ -1,0 +1,104 @@
+"""Layers on a rectangular Fourier basis (each side of the image on the smallest supported size
+that holds it, sides up to 32) against the time-domain oracle (GPU, C ABI).
+
+Every ordered pair of different sides is exercised through the three ordinary passes; the
+transform-reuse pair, the weights-ahead calls and scale/accumulate through a few.  Bound:
+max|err| / max|ref| <= 1e-4 over each output tensor."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1412_7580_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+SIDES = (8, 12, 14, 16, 20, 24, 28, 32)
+PAIRS = [(a, b) for a in SIDES for b in SIDES if a != b]
+
+
+@pytest.fixture(scope="module")
+def hd(lib):
+    h = lib.Handle(0)
+    yield h
+    h.close()
+
+
+def _relerr(got, ref):
+    return float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def _np(t):
+    return t.cpu().numpy().astype(np.float64)
+
+
+def _image_for(n, rng):
+    """An image side whose smallest basis is n."""
+    lo = {8: 3, 12: 9, 14: 13, 16: 15, 20: 17, 24: 21, 28: 25, 32: 29}[n]
+    return int(rng.integers(lo, n + 1))
+
+
+@pytest.mark.parametrize("nr,nc", PAIRS)
+def test_three_passes(hd, nr, nc):
+    rng = np.random.default_rng(nr * 100 + nc)
+    h, w = _image_for(nr, rng), _image_for(nc, rng)
+    kh, kw = int(rng.integers(1, min(h, 7) + 1)), int(rng.integers(1, min(w, 7) + 1))
+    assert hd.layer_basis(h, w, kh, kw) == (nr, nc, False)
+    # plane counts beyond one tile of the layout, with a ragged last tile
+    S, f, fo = int(rng.integers(1, 6)), int(rng.integers(1, 12)), int(rng.integers(1, 12))
+    cfg = dict(S=S, f=f, fo=fo, h=h, w=w, kh=kh, kw=kw)
+    x, wt, gy = synth.conv_inputs(seed=nr * 64 + nc, **cfg)
+    dx, dw, dgy = _dev(x), _dev(wt), _dev(gy)
+    got = (hd.fft_conv_fprop(dx, dw), hd.fft_conv_bprop(dgy, dw, h, w), hd.fft_conv_accgrad(dx, dgy))
+    ref = (oracle.conv_fprop(x, wt), oracle.conv_bprop(gy, wt, h, w), oracle.conv_accgrad(x, gy))
+    for name, g, r in zip(("fprop", "bprop", "accgrad"), got, ref):
+        assert g.shape == r.shape
+        err = _relerr(_np(g), r)
+        assert err <= TOL, f"{name} {cfg} basis {nr}x{nc}: {err:.2e}"
+
+
+@pytest.mark.parametrize("h,w,kh,kw", [(27, 13, 5, 3), (13, 27, 3, 5), (8, 32, 3, 3), (30, 10, 7, 2), (16, 12, 16, 12),
+                                       (20, 15, 1, 1)])
+def test_reuse_and_weights_ahead(hd, h, w, kh, kw):
+    import torch
+    cfg = dict(S=19, f=20, fo=36, h=h, w=w, kh=kh, kw=kw)
+    nr, nc, tiled = hd.layer_basis(h, w, kh, kw)
+    assert nr != nc and not tiled
+    x, wt, gy = synth.conv_inputs(seed=h * 40 + w, **cfg)
+    dx, dw, dgy = _dev(x), _dev(wt), _dev(gy)
+    ref = (oracle.conv_fprop(x, wt), oracle.conv_bprop(gy, wt, h, w), oracle.conv_accgrad(x, gy))
+
+    nsaved = hd.saved_bytes(cfg["S"], cfg["f"], cfg["fo"], h, w, kh, kw)
+    saved = torch.empty((nsaved + 3) // 4, dtype=torch.float32, device="cuda")
+    y = hd.fft_conv_fprop_save(dx, dw, saved)
+    gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], h, w, kh, kw)
+    for name, g, r in zip(("fprop_save", "backward gx", "backward gw"), (y, gx, gw), ref):
+        err = _relerr(_np(g), r)
+        assert err <= TOL, f"{name} {cfg}: {err:.2e}"
+
+    wf = hd.fft_conv_transform_weights(dw, h, w)
+    yw = hd.fft_conv_fprop_weights(dx, wf, cfg["fo"], kh, kw)
+    gxw = hd.fft_conv_bprop_weights(dgy, wf, cfg["f"], h, w, kh, kw)
+    for name, g, r in zip(("fprop_weights", "bprop_weights"), (yw, gxw), ref[:2]):
+        err = _relerr(_np(g), r)
+        assert err <= TOL, f"{name} {cfg}: {err:.2e}"
+
+    # scale and accumulate of the weight gradient
+    gw0 = torch.full_like(gw, 0.5)
+    hd.fft_conv_accgrad(dx, dgy, gw=gw0, scale=0.25, accumulate=True)
+    err = _relerr(_np(gw0), 0.5 + 0.25 * ref[2])
+    assert err <= TOL, f"accumulate {cfg}: {err:.2e}"
+
+
+def test_square_images_keep_the_square_basis(hd):
+    assert hd.layer_basis(13, 13, 3, 3) == (14, 14, False)
+    assert hd.layer_basis(27, 27, 5, 5) == (28, 28, False)
+    # one side beyond 32: a square basis (of the larger side, or of the tiles)
+    for h, w, k in ((40, 12, 3), (40, 30, 9), (33, 8, 1), (100, 20, 5)):
+        nr, nc, _ = hd.layer_basis(h, w, k, k)
+        assert nr == nc
+    assert hd.layer_basis(40, 30, 9, 9) == (40, 40, False)
