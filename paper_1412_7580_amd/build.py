@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfftconv.so")
 SOURCES = ["api.hip", "fft_kernels.hip", "fft_kernels_mixed_small.hip", "fft_kernels_mixed_large.hip", "fft1d_mixed.hip",
-           "fft_rect_fwd.hip", "fft_rect_inv.hip", "fused_small.hip", "cgemm_kernels.hip", "cgemm_bingroup.hip"]
+           "fft_kernels_natural.hip", "fft_rect_fwd.hip", "fft_rect_inv.hip", "fused_small.hip", "cgemm_kernels.hip", "cgemm_bingroup.hip"]
 HEADERS = ["fft_core.hpp", "fft_kernels_impl.hpp", "fft_rect_impl.hpp", "kernels.hpp", "gemm_params.hpp", os.path.join("..", "..", "include", "fftconv.h")]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",

@@ -59,6 +59,10 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
                             bool conv, LaunchCtx st, const PlaneView *view) {
     if (planes <= 0) return hipSuccess;
     if (view && !conv) return hipErrorInvalidValue;
+    if (!conv) {
+        const hipError_t e = launch_fft2d_r2c_natural(in, out, planes, h_in, w_in, N, st);
+        if (e != hipErrorNotSupported) return e;
+    }
     switch (N) {
         // sizes 2 and 4: stand-alone transforms only (Section 5 covers 2 ... 256; no convolution basis)
         case 2: return conv ? hipErrorInvalidValue : run_fwd2d<2, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
@@ -77,6 +81,10 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
     if (planes <= 0) return hipSuccess;
     if (view && (!conv || view->oy + h_out > N || view->ox + w_out > N)) return hipErrorInvalidValue;
     const int rows = h_out + (view ? view->oy : 0);   // rows of the transform that are computed
+    if (!conv) {
+        const hipError_t e = launch_fft2d_c2r_natural(in, out, planes, N, h_out, w_out, scale, accumulate, st);
+        if (e != hipErrorNotSupported) return e;
+    }
     switch (N) {
         case 2: return conv ? hipErrorInvalidValue : run_inv2d<2, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 4: return conv ? hipErrorInvalidValue : run_inv2d<4, 1, 64>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);

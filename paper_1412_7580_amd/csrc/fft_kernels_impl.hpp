@@ -873,7 +873,8 @@ static inline size_t with_origin_table(size_t lds, int T, int *info_off) {
     return at + (size_t)T * 16;
 }
 
-template <int L, int G, int T>
+// CONV_TOO = false: only the natural-layout kernel is instantiated (conv must be false).
+template <int L, int G, int T, bool CONV_TOO = true>
 static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, int w_in,
                             bool conv, LaunchCtx st, const PlaneView *view) {
     constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
@@ -895,7 +896,11 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
         launch_kernel(k, dim3(grid), dim3(BT), lds, st, prm);
         return hipGetLastError();
     };
-    if (conv) return go(fft2d_r2c_kernel<L, G, T, true, false>);
+    if constexpr (CONV_TOO) {
+        if (conv) return go(fft2d_r2c_kernel<L, G, T, true, false>);
+    } else {
+        if (conv) return hipErrorInvalidValue;
+    }
     return go(fft2d_r2c_kernel<L, G, T, false, true>);
 }
 
@@ -935,7 +940,7 @@ static hipError_t run_fwd2d_multi(const FwdOperand *ops, int nops, LaunchCtx st)
     return hipGetLastError();
 }
 
-template <int L, int G, int T>
+template <int L, int G, int T, bool CONV_TOO = true>
 static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out, int w_out,
                             bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view) {
     constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
@@ -978,7 +983,11 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
         launch_kernel(k, dim3(grid), dim3(BT), lds, st, prm);
         return hipGetLastError();
     };
-    if (conv) return istage ? go(fft2d_c2r_kernel<L, G, T, true, true>) : go(fft2d_c2r_kernel<L, G, T, true, false>);
+    if constexpr (CONV_TOO) {
+        if (conv) return istage ? go(fft2d_c2r_kernel<L, G, T, true, true>) : go(fft2d_c2r_kernel<L, G, T, true, false>);
+    } else {
+        if (conv) return hipErrorInvalidValue;
+    }
     return go(fft2d_c2r_kernel<L, G, T, false, true>);
 }
 
@@ -1024,6 +1033,11 @@ hipError_t launch_fft2d_r2c_mixed(const float *in, float *out, long planes, int 
 hipError_t launch_fft2d_r2c_multi_mixed(const FwdOperand *ops, int nops, int N, LaunchCtx st);
 hipError_t launch_fft2d_c2r_mixed(const float *in, float *out, long planes, int N, int h_out, int w_out,
                                   bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view);
+// Natural-layout choices that differ from the convolution path's (fft_kernels_natural.hip);
+// hipErrorNotSupported for the sizes without one.
+hipError_t launch_fft2d_r2c_natural(const float *in, float *out, long planes, int h_in, int w_in, int N, LaunchCtx st);
+hipError_t launch_fft2d_c2r_natural(const float *in, float *out, long planes, int N, int h_out, int w_out,
+                                    float scale, bool accumulate, LaunchCtx st);
 hipError_t launch_fft1d_r2c_mixed(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
 hipError_t launch_fft1d_c2r_mixed(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);
 
