@@ -258,6 +258,92 @@ __device__ __forceinline__ void fft_group(float (&re)[L], float (&im)[L], int g)
     }
 }
 
+// The per-lane twiddles of the cross-lane steps of a line spread over G lanes, as a table for
+// kernels that keep it in LDS: entry (step s, register k, lane g) is the factor lane g applies
+// to register k before step s (1 for the lanes that keep their value), for DIR = +1; the
+// other direction uses the conjugate.  Step s pairs lanes that differ in bit log2(G)-1-s of g;
+// the exponent collects the bits already used (see fft_group).  One 8-byte LDS read replaces
+// the selects among compile-time constants (up to four constants moved into registers and
+// three selects per component), a third of the vector instructions of the eight-lane kernels.
+template <int G> constexpr int kGroupSteps = G == 8 ? 3 : G == 4 ? 2 : 1;
+// Lines of four or eight lanes read the table; lane pairs keep the immediates (one select).
+template <int G> constexpr bool kLdsTwiddles = G >= 4;
+template <int L, int G> constexpr int kGroupTwiddleFloats = kLdsTwiddles<G> ? kGroupSteps<G> * L * G * 2 : 0;
+
+template <int L, int G>
+struct GroupTwiddles {
+    float v[kGroupSteps<G> * L * G * 2];
+    constexpr GroupTwiddles() : v{} {
+        constexpr int S = kGroupSteps<G>;
+        for (int s = 0; s < S; ++s)
+            for (int k = 0; k < L; ++k)
+                for (int g = 0; g < G; ++g) {
+                    const bool on = ((g >> (S - 1 - s)) & 1) != 0;
+                    int e = k;
+                    for (int t = 0; t < s; ++t) e += ((g >> (S - 1 - t)) & 1) * (L << t);
+                    const cplx_d w = on ? unit_root(e, (2 << s) * L) : cplx_d{1.0, 0.0};
+                    v[((s * L + k) * G + g) * 2 + 0] = (float)w.re;
+                    v[((s * L + k) * G + g) * 2 + 1] = (float)w.im;
+                }
+    }
+};
+template <int L, int G> __device__ const GroupTwiddles<L, G> kGroupTwiddles{};
+
+// Copy the table to LDS (all threads of the workgroup; a barrier must follow before use).
+template <int L, int G, int BT>
+__device__ __forceinline__ void load_group_twiddles(float *dst, int tid) {
+    if constexpr (kLdsTwiddles<G>) {
+        for (int i = tid; i < kGroupTwiddleFloats<L, G>; i += BT) dst[i] = kGroupTwiddles<L, G>.v[i];
+    }
+}
+
+// fft_group<L, G, DIR> for G = 4 or 8 with the twiddles read from the LDS copy of the table; tw
+// points at this lane's entry of (step 0, register 0).
+template <int L, int G, int DIR>
+__device__ __forceinline__ void fft_group_lds(float (&re)[L], float (&im)[L], int g, const float2 *tw) {
+    static_assert(G == 4 || G == 8, "four or eight lanes per line");
+    fft_leaf<L, DIR>(re, im);
+    constexpr float D = (float)DIR;
+    auto twiddle = [&](const float2 w, float &xr, float &xi) {
+        const float tr = w.x * xr - D * w.y * xi;
+        const float ti = w.x * xi + D * w.y * xr;
+        xr = tr; xi = ti;
+    };
+    if constexpr (G == 8) {
+        const float s1 = (g & 4) ? -1.0f : 1.0f, s2 = (g & 2) ? -1.0f : 1.0f, s3 = (g & 1) ? -1.0f : 1.0f;
+        static_for<0, L>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            float xr = re[k], xi = im[k];
+            twiddle(tw[(0 * L + k) * 8], xr, xi);
+            float yr = lane_xor4(xr) + s1 * xr, yi = lane_xor4(xi) + s1 * xi;
+            twiddle(tw[(1 * L + k) * 8], yr, yi);
+            float zr = lane_xor2(yr) + s2 * yr, zi = lane_xor2(yi) + s2 * yi;
+            twiddle(tw[(2 * L + k) * 8], zr, zi);
+            re[k] = lane_xor1(zr) + s3 * zr;
+            im[k] = lane_xor1(zi) + s3 * zi;
+        });
+    } else {
+        const float s1 = (g & 2) ? -1.0f : 1.0f, s2 = (g & 1) ? -1.0f : 1.0f;
+        static_for<0, L>([&](auto kk) {
+            constexpr int k = decltype(kk)::value;
+            float xr = re[k], xi = im[k];
+            twiddle(tw[(0 * L + k) * 4], xr, xi);
+            float yr = lane_xor2(xr) + s1 * xr, yi = lane_xor2(xi) + s1 * xi;
+            twiddle(tw[(1 * L + k) * 4], yr, yi);
+            re[k] = lane_xor1(yr) + s2 * yr;
+            im[k] = lane_xor1(yi) + s2 * yi;
+        });
+    }
+}
+
+// The line transform as the kernels call it: lines of four or eight lanes take their twiddles
+// from the table at `tw` in LDS, the others have them as immediates.
+template <int L, int G, int DIR>
+__device__ __forceinline__ void fft_lines(float (&re)[L], float (&im)[L], int g, const float *tw) {
+    if constexpr (kLdsTwiddles<G>) fft_group_lds<L, G, DIR>(re, im, g, reinterpret_cast<const float2 *>(tw) + g);
+    else fft_group<L, G, DIR>(re, im, g);
+}
+
 // Number of registers of split spectrum a lane keeps (see split_two_real).
 template <int L, int G> struct SplitRegs { static constexpr int A = (G == 1) ? L / 2 : L, B = (G == 1) ? L / 2 : 1; };
 

@@ -273,6 +273,7 @@ struct Fwd2dParams {
     int out_vec_ok;   // output base and every block start are 16-byte aligned
     int tiled;        // planes are windows of images (view); origin table at LDS float info_off
     int info_off;
+    int tw_off;       // lines of four or eight lanes: twiddle table at LDS float tw_off
     PlaneView view;
 };
 
@@ -313,6 +314,7 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
     const long left = prm.planes - p0;
     const int np = left < T ? (int)left : T;
 
+    load_group_twiddles<L, G, BT>(smem + prm.tw_off, tid);   // used after the next barrier
     // ---- stage the contiguous block of np planes into LDS (coalesced reads)
     bool windows = false;
     if constexpr (CONV) windows = prm.tiled != 0;   // only the plane-tiled layout is used with views
@@ -363,7 +365,7 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
             re[m] = in ? pa[j] : 0.0f;
             im[m] = (in && hasb) ? pb[j] : 0.0f;
         }
-        fft_group<L, G, -1>(re, im, g);
+        fft_lines<L, G, -1>(re, im, g, smem + prm.tw_off);
         split_two_real<L, G>(re, im, g, are, aim, bre, bim);
     }
     __syncthreads();   // every lane has read its rows; the staging area may be overwritten
@@ -404,7 +406,7 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
             if (r < h_in) v = mp[r * MRS];
             re[m] = v.x; im[m] = v.y;
         }
-        fft_group<L, G, -1>(re, im, cg);
+        fft_lines<L, G, -1>(re, im, cg, smem + prm.tw_off);
     }
 
     // Results go either straight to global memory or, when OSTAGE, into an LDS image of the
@@ -501,6 +503,7 @@ struct Inv2dParams {
     int tiled;        // outputs are windows of images (view); origin table at LDS float info_off
     int info_off;
     int win_h, win_w; // tiled: size of the window taken at (view.oy, view.ox) of the h_out x w_out block
+    int tw_off;       // lines of four or eight lanes: twiddle table at LDS float tw_off
     MagicDiv div_w, div_h;
     PlaneView view;
 };
@@ -533,6 +536,10 @@ __device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned 
         int cg, cp, cc;
         if constexpr (CONV) { cg = tid % G; cp = (tid / G) % T; cc = tid / (G * T); }
         else { cg = tid % G; cc = (tid / G) % NH; cp = tid / (G * NH); }
+        if constexpr (kLdsTwiddles<G>) {
+            load_group_twiddles<L, G, BT>(smem + prm.tw_off, tid);
+            if constexpr (!ISTAGE) __syncthreads();   // (the staging below ends with a barrier)
+        }
         if constexpr (ISTAGE) {
             if constexpr (CONV)   // whole tile (its padding planes are simply not used)
                 stage_linear<BT>(smem, prm.in + prm.lay.index(p0, 0, 0), (unsigned)T * N * NB * 2, tid,
@@ -572,7 +579,7 @@ __device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned 
                     cre[m] = v.x; cim[m] = v.y;
                 }
             }
-            fft_group<L, G, +1>(cre, cim, cg);
+            fft_lines<L, G, +1>(cre, cim, cg, smem + prm.tw_off);
         }
         if constexpr (ISTAGE) __syncthreads();   // staged input fully consumed; `mid` overlays it
         if (cp < np) {
@@ -611,7 +618,7 @@ __device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned 
             else { xr = a.x + b.y; xi = b.x - a.y; }
             re[m] = xr; im[m] = xi;
         }
-        fft_group<L, G, +1>(re, im, g);
+        fft_lines<L, G, +1>(re, im, g, smem + prm.tw_off);
     }
     __syncthreads();   // all reads of `mid` done; reuse the area as the output block
     if (active) {
@@ -660,6 +667,7 @@ struct Fwd1dParams {
     int n_in, RS;
     MagicDiv div_n;
     int linear, vec_ok, out_vec_ok;
+    int tw_off;       // lines of four or eight lanes: twiddle table at LDS float tw_off
 };
 
 template <int L, int G, int TB>
@@ -676,6 +684,7 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) 
     const long left = prm.B - b0;
     const int nb = left < TB ? (int)left : TB;
     const int n_in = prm.n_in;
+    load_group_twiddles<L, G, BT>(smem + prm.tw_off, tid);   // used after the next barrier
     {
         const float *src = prm.in + b0 * n_in;
         const unsigned total = (unsigned)nb * n_in;
@@ -718,7 +727,7 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_r2c_kernel(Fwd1dParams prm) 
             re[m] = in ? va : 0.f;
             im[m] = (in && hasb) ? vb : 0.f;
         }
-        fft_group<L, G, -1>(re, im, g);
+        fft_lines<L, G, -1>(re, im, g, smem + prm.tw_off);
         split_two_real<L, G>(re, im, g, are, aim, bre, bim);
     }
     __syncthreads();
@@ -761,6 +770,7 @@ struct Inv1dParams {
     int n_out;
     float scale;
     int in_vec_ok, out_vec_ok;
+    int tw_off;       // lines of four or eight lanes: twiddle table at LDS float tw_off
 };
 
 template <int L, int G, int TB>
@@ -775,6 +785,7 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_c2r_kernel(Inv1dParams prm) 
     const long left = prm.B - b0;
     const int nb = left < TB ? (int)left : TB;
     const int n_out = prm.n_out;
+    load_group_twiddles<L, G, BT>(smem + prm.tw_off, tid);   // used after the next barrier
     {
         const float *src = prm.in + b0 * NB * 2;
         const unsigned total = (unsigned)nb * NB * 2;
@@ -799,7 +810,7 @@ __global__ void __launch_bounds__(TB / 2 * G) fft1d_c2r_kernel(Inv1dParams prm) 
             re[m] = a.x - b.y;
             im[m] = a.y + b.x;
         }
-        fft_group<L, G, +1>(re, im, g);
+        fft_lines<L, G, +1>(re, im, g, smem + prm.tw_off);
     }
     __syncthreads();
     if (active) {
@@ -853,7 +864,7 @@ static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in
     prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)T * N * (NH + 1) * 2) % 4 == 0) ? 1 : 0;
     const size_t a = ((size_t)T * prm.IPS + N) * sizeof(float), b = (size_t)T * prm.MPS * sizeof(float2);
     *lds = a > b ? a : b;
-    prm.tiled = 0; prm.info_off = 0; prm.view = PlaneView{};
+    prm.tiled = 0; prm.info_off = 0; prm.tw_off = 0; prm.view = PlaneView{};
     if (view) {   // gathered windows: scalar loads, padded image, origin table behind everything else
         prm.tiled = 1; prm.view = *view;
         prm.linear = 0;
@@ -863,6 +874,17 @@ static Fwd2dParams make_fwd2d(const float *in, float *out, long planes, int h_in
         prm.div_wv = make_magic((unsigned)(w_in / prm.vecw));
     }
     return prm;
+}
+
+// LDS bytes of a launch whose lines of four or eight lanes keep their twiddle table behind `lds` bytes of
+// other data; *tw_off receives the table's offset in floats.
+template <int L, int G>
+static inline size_t with_twiddle_table(size_t lds, int *tw_off) {
+    *tw_off = 0;
+    if constexpr (!kLdsTwiddles<G>) return lds;
+    const size_t at = (lds + 7) / 8 * 8;
+    *tw_off = (int)(at / sizeof(float));
+    return at + kGroupTwiddleFloats<L, G> * sizeof(float);
 }
 
 // LDS bytes of a launch whose blocks keep an origin table of T planes behind `lds` bytes of
@@ -888,6 +910,7 @@ static hipError_t run_fwd2d(const float *in, float *out, long planes, int h_in, 
         const size_t c = (size_t)T * N * (NH + 1) * 2 * sizeof(float);
         if (c > lds) lds = c;
     }
+    lds = with_twiddle_table<L, G>(lds, &prm.tw_off);
     if (prm.tiled) lds = with_origin_table(lds, T, &prm.info_off);
     const unsigned grid = (unsigned)((planes + T - 1) / T);
     hipError_t e;
@@ -924,7 +947,12 @@ static hipError_t run_fwd2d_multi(const FwdOperand *ops, int nops, LaunchCtx st)
     }
     m.first[3] = blocks;
     for (int o = nops; o < 3; ++o) m.first[o] = blocks;   // unused operands own no blocks
-    {   // one origin table position for all operands, behind the largest footprint
+    {   // one twiddle table position for all operands, behind the largest footprint
+        int tw_off = 0;
+        lds = with_twiddle_table<L, G>(lds, &tw_off);
+        for (int o = 0; o < 3; ++o) m.op[o].tw_off = tw_off;
+    }
+    {   // one origin table position for all operands, behind everything else
         int info_off = 0;
         bool any = false;
         for (int o = 0; o < nops; ++o) any = any || m.op[o].tiled;
@@ -975,6 +1003,7 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
         const size_t c = (size_t)T * N * (NH + 1) * sizeof(float2);
         if (c > lds) lds = c;
     }
+    lds = with_twiddle_table<L, G>(lds, &prm.tw_off);
     if (prm.tiled) lds = with_origin_table(lds, T, &prm.info_off);
     const unsigned grid = (unsigned)((planes + T - 1) / T);
     hipError_t e;
@@ -1001,7 +1030,7 @@ static hipError_t run_fwd1d(const float *in, float *out, long B, int n_in, Launc
     prm.vec_ok = (((size_t)in & 15) == 0 && ((size_t)TB * n_in) % 4 == 0) ? 1 : 0;
     prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)TB * NB * 2) % 4 == 0) ? 1 : 0;
     const size_t a = ((size_t)TB * prm.RS + N) * sizeof(float), b = (size_t)TB * NB * sizeof(float2);
-    const size_t lds = a > b ? a : b;
+    const size_t lds = with_twiddle_table<L, G>(a > b ? a : b, &prm.tw_off);
     auto k = fft1d_r2c_kernel<L, G, TB>;
     hipError_t e;
     if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;
@@ -1017,7 +1046,7 @@ static hipError_t run_inv1d(const float *in, float *out, long B, int n_out, Laun
     prm.in_vec_ok = (((size_t)in & 15) == 0 && ((size_t)TB * NB * 2) % 4 == 0) ? 1 : 0;
     prm.out_vec_ok = (((size_t)out & 15) == 0 && ((size_t)TB * n_out) % 4 == 0) ? 1 : 0;
     const size_t a = (size_t)TB * NB * sizeof(float2), b = (size_t)TB * n_out * sizeof(float);
-    const size_t lds = a > b ? a : b;
+    const size_t lds = with_twiddle_table<L, G>(a > b ? a : b, &prm.tw_off);
     auto k = fft1d_c2r_kernel<L, G, TB>;
     hipError_t e;
     if ((e = allow_big_lds((const void *)k, lds)) != hipSuccess) return e;

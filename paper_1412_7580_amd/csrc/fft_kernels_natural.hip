@@ -7,7 +7,8 @@
 //   forward  14: 5.36 -> 5.97   16: 5.31 -> 5.74   20: 5.56 -> 5.73   24: 5.31 -> 5.77   28: 5.32 -> 5.52
 //            32: 5.03 -> 5.44   56: 4.37 -> 4.75   64: 4.01 -> 4.70
 //   inverse   8: 5.57 -> 5.98   12: 4.48 -> 5.96   16: 5.43 -> 5.73   24: 4.95 -> 5.51   28: 4.70 -> 5.42
-//            32: 5.23 -> 5.54   56: 4.83 -> 5.00   64: 4.65 -> 5.03
+//            32: 5.23 -> 5.54   56: 4.83 -> 5.00   64: 4.65 -> 5.03 (eight lanes per line since
+//            their twiddles come from the LDS table: 4.76 with four lanes -> 4.92)
 #include "fft_kernels_impl.hpp"
 
 namespace fc {
@@ -37,7 +38,7 @@ hipError_t launch_fft2d_c2r_natural(const float *in, float *out, long planes, in
         case 28: return run_inv2d<7, 4, 8, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
         case 32: return run_inv2d<8, 4, 8, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
         case 56: return run_inv2d<14, 4, 1, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
-        case 64: return run_inv2d<16, 4, 1, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
+        case 64: return run_inv2d<8, 8, 1, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
         default: return hipErrorNotSupported;
     }
 }

@@ -74,7 +74,7 @@ static hipError_t run_fused(const float *x, const float *wf, float *y, int S, in
     iv.MPS = MidLayout<L, G>::inv_plane(oh) | 1;
     iv.lay = fp.fwd.lay;
     iv.scale = 1.0f / ((float)N * (float)N); iv.accumulate = 0;
-    iv.vec_ok = 0; iv.in_vec_ok = 0; iv.tiled = 0; iv.info_off = 0; iv.win_h = iv.win_w = 0;
+    iv.vec_ok = 0; iv.in_vec_ok = 0; iv.tiled = 0; iv.info_off = 0; iv.tw_off = 0; iv.win_h = iv.win_w = 0;
     iv.div_w = iv.div_h = MagicDiv{0}; iv.view = PlaneView{};
     fp.wf = wf; fp.f = f; fp.fo = fo;
     fp.x_stride = (long)f * h * w; fp.y_stride = (long)fo * oh * ow;
