@@ -113,17 +113,22 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
 
 // Lanes per line of the 1-D kernels: more lanes with shorter register FFTs measured faster at
 // every size (fewer registers per lane, more loads in flight), e.g. n = 64: (8,8) 5.3 TB/s against
-// (32,2) 4.8; n = 256: (32,8) 4.2 against (64,4) 2.7; (2,4) at n = 8 and (4,8) at n = 32 lost.
+// (32,2) 4.8; n = 256: (32,8) 4.2 against (64,4) 2.7; (2,4) at n = 8 lost.  Signals per workgroup
+// (third argument): smaller workgroups overlap their load, transform and store phases better;
+// same process, TB/s R2C / C2R: n = 16 512 -> 256 signals 5.49 / 5.65 -> 5.96 / 5.80; n = 32 (8,4) 256 ->
+// (4,8) 128 (eight lanes since the cross-lane twiddles come from LDS) 5.32 / 5.47 -> 5.86 / 5.84; n = 64
+// 128 -> 32 5.37 / 5.42 -> 5.61 / 5.56; n = 128 128 -> 64 4.57..5.01 / 4.59..4.88 -> 5.14..5.18 / 5.06..5.17;
+// n = 256 keeps 64 (32: 4.04 against 4.08).
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st) {
     if (B <= 0) return hipSuccess;
     switch (n) {
         case 2: return run_fwd1d<2, 1, 1024>(in, out, B, n_in, st);
         case 4: return run_fwd1d<4, 1, 1024>(in, out, B, n_in, st);
         case 8: return run_fwd1d<4, 2, 512>(in, out, B, n_in, st);
-        case 16: return run_fwd1d<4, 4, 512>(in, out, B, n_in, st);
-        case 32: return run_fwd1d<8, 4, 256>(in, out, B, n_in, st);
-        case 64: return run_fwd1d<8, 8, 128>(in, out, B, n_in, st);
-        case 128: return run_fwd1d<16, 8, 128>(in, out, B, n_in, st);
+        case 16: return run_fwd1d<4, 4, 256>(in, out, B, n_in, st);
+        case 32: return run_fwd1d<4, 8, 128>(in, out, B, n_in, st);
+        case 64: return run_fwd1d<8, 8, 32>(in, out, B, n_in, st);
+        case 128: return run_fwd1d<16, 8, 64>(in, out, B, n_in, st);
         case 256: return run_fwd1d<32, 8, 64>(in, out, B, n_in, st);
         default: return launch_fft1d_r2c_mixed(in, out, B, n_in, n, st);
     }
@@ -135,10 +140,10 @@ hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_ou
         case 2: return run_inv1d<2, 1, 1024>(in, out, B, n_out, st);
         case 4: return run_inv1d<4, 1, 1024>(in, out, B, n_out, st);
         case 8: return run_inv1d<4, 2, 512>(in, out, B, n_out, st);
-        case 16: return run_inv1d<4, 4, 512>(in, out, B, n_out, st);
-        case 32: return run_inv1d<8, 4, 256>(in, out, B, n_out, st);
-        case 64: return run_inv1d<8, 8, 128>(in, out, B, n_out, st);
-        case 128: return run_inv1d<16, 8, 128>(in, out, B, n_out, st);
+        case 16: return run_inv1d<4, 4, 256>(in, out, B, n_out, st);
+        case 32: return run_inv1d<4, 8, 128>(in, out, B, n_out, st);
+        case 64: return run_inv1d<8, 8, 32>(in, out, B, n_out, st);
+        case 128: return run_inv1d<16, 8, 64>(in, out, B, n_out, st);
         case 256: return run_inv1d<32, 8, 64>(in, out, B, n_out, st);
         default: return launch_fft1d_c2r_mixed(in, out, B, n, n_out, st);
     }
