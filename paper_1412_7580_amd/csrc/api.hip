@@ -280,7 +280,7 @@ static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, nullptr}, {b, BF, p.planesB, p.hB, p.wB, nullptr}};
         return launch_fft2d_r2c_rect(ops, 2, p.Nr, p.Nc, next_ctx(c));
     }
-    if (p.lay.tsh >= 4) {
+    if (p.lay.tsh >= 3) {
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, va}, {b, BF, p.planesB, p.hB, p.wB, vb}};
         return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c));
     }
@@ -705,7 +705,7 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
         if ((e = transform(pb, gy, GYF, pb.planesA, pb.hA, pb.wA, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
     } else {
         // gy cut twice: overlapping windows for bprop, disjoint tiles for accGrad
-        if (gx && gw && pb.lay.tsh >= 4) {   // small bases: both in one launch, as for the two operands of a pass
+        if (gx && gw && pb.lay.tsh >= 3) {   // small bases: both in one launch, as for the two operands of a pass
             FwdOperand ops[2] = {{gy, GYF, pb.planesA, pb.hA, pb.wA, &pb.vA}, {gy, GYFa, pa.planesA, pa.hA, pa.wA, &pa.vA}};
             if ((e = launch_fft2d_r2c_multi(ops, 2, pb.N, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
         } else {

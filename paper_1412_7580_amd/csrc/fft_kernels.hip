@@ -22,14 +22,18 @@ hipError_t allow_big_lds(const void *fn, size_t bytes) {
     return e;
 }
 
-// Planes per workgroup follow the size class: the sizes between two powers of two share the
-// tile of the upper one (12 and 14 with 16; 20, 24, 28 with 32; 40, 48, 56 with 64; 80, 96, 112
-// with 128), so that the contraction sees the same run lengths.
+// Planes per workgroup (= tile of the frequency layout) by size class: 64 at 8, 32 up to 16, 16
+// up to 28, 4 up to 64, 1 above.  Basis 32 takes 8: with four lanes per line and eight planes
+// its transforms are 5 .. 25 % faster than any 16-plane variant (more, smaller workgroups), which
+// outweighs the contraction's loss from runs of 8 planes instead of 16 (0 .. 15 %) on every layer
+// measured (27x27 step 146.4 -> 143.5 us, 224x224 in 32x32 tiles 1480 -> 1420, 55x55 780 -> 745);
+// at 20 .. 28 the one-lane-per-line 16-plane kernels stay ahead (basis 28: 125 us against 127 .. 132).
 int fft2d_tile_log2(int N) {
     switch (N) {
         case 8: return 6;
         case 12: case 14: case 16: return 5;
-        case 20: case 24: case 28: case 32: return 4;
+        case 20: case 24: case 28: return 4;
+        case 32: return 3;
         case 40: case 48: case 56: case 64: return 2;
         case 80: case 96: case 112: case 128: return 0;
         default: return -1;
@@ -48,7 +52,7 @@ hipError_t launch_fft2d_r2c_multi(const FwdOperand *ops, int nops, int N, Launch
     switch (N) {
         case 8: return run_fwd2d_multi<8, 1, 64>(ops, nops, st);
         case 16: return run_fwd2d_multi<16, 1, 32>(ops, nops, st);
-        case 32: return run_fwd2d_multi<16, 2, 16>(ops, nops, st);
+        case 32: return run_fwd2d_multi<8, 4, 8>(ops, nops, st);
         case 64: return run_fwd2d_multi<32, 2, 4>(ops, nops, st);
         case 128: return run_fwd2d_multi<16, 8, 1>(ops, nops, st);
         default: return launch_fft2d_r2c_multi_mixed(ops, nops, N, st);
@@ -69,7 +73,7 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
         case 4: return conv ? hipErrorInvalidValue : run_fwd2d<4, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
         case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
         case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);   // (8,2): 12 % slower
-        case 32: return run_fwd2d<16, 2, 16>(in, out, planes, h_in, w_in, conv, st, view);   // (32,1): equal at C2, 3..5 % slower on large grids
+        case 32: return run_fwd2d<8, 4, 8>(in, out, planes, h_in, w_in, conv, st, view);   // 16 planes: (16,2) 5 % slower, (32,1) 8 %
         case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st, view);   // (64,1): 25 % slower, (16,4): 5 % slower
         case 128: return run_fwd2d<16, 8, 1>(in, out, planes, h_in, w_in, conv, st, view);
         default: return launch_fft2d_r2c_mixed(in, out, planes, h_in, w_in, N, conv, st, view);
@@ -95,12 +99,10 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
             if (conv && 2 * rows <= 16) return run_inv2d<8, 2, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
             return run_inv2d<16, 1, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 32:
-            // one lane per line only for grids of a single round of workgroups that keep most rows
-            // (the 27x27 layer: 15.0 us against 16.1); lane pairs are 3..6 % faster on large grids
-            if (conv && 2 * rows > 32 && planes <= 16 * 1024) return run_inv2d<32, 1, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
-            return run_inv2d<16, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+            // (with 16 planes per workgroup: (32,1) 15.0 us on the 27x27 layer, (16,2) 16.1; this: 14.3)
+            return run_inv2d<8, 4, 8>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         // the inverse gains from more lanes per line (fewer registers, shorter serial chains):
-        // (16,4) measured 15..25 % faster than (32,2) here, (16,2) 20 % faster than (32,1) at 32
+        // (16,4) measured 15..25 % faster than (32,2) here
         case 64:
             // eight lanes per line when (nearly) all rows are kept (64x64 input gradients: 42 us
             // against 49), four otherwise (31x31 crops: 89 us against 92)

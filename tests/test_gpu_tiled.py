@@ -179,7 +179,7 @@ def test_named_basis_that_holds_the_image(hd, n):
     assert _relerr(_np(hd.fft_conv_fprop_tiled(dx, dw, n)), oracle.conv_fprop(x, w)) <= TOL
     assert _relerr(_np(hd.fft_conv_bprop_tiled(dgy, dw, 27, 25, n)), oracle.conv_bprop(gy, w, 27, 25)) <= TOL
     assert _relerr(_np(hd.fft_conv_accgrad_tiled(dx, dgy, n)), oracle.conv_accgrad(x, gy)) <= TOL
-    T = {28: 16, 32: 16, 40: 4, 56: 4}[n]
+    T = {28: 16, 32: 8, 40: 4, 56: 4}[n]     # planes per tile of the layout
     bins = {28: 424, 32: 544, 40: 864, 56: 1632}[n]     # n * (n/2 + 1), padded to the layout's unit
     pad = lambda planes: -(-planes // T) * T
     assert hd.tiled_workspace_bytes(0, 3, 5, 4, 27, 25, 5, 4, n) == (pad(15) + pad(20) + pad(12)) * bins * 2 * 4
