@@ -33,15 +33,15 @@ STAGES = ("fft", "contraction", "ifft")   # kernels of one pass, in launch order
 # and the table are in profiles/c2_hbm_traffic.md.  Keyed by workload, then "pass.stage".
 MEASURED_TRAFFIC_BYTES = {
     "C2": {   # keys: the launches of the fprop_save + backward step (paired or separate contractions)
-        "fprop.fft": (1.201e4 * 2.0 + 5.222e4) * 1024,
-        "fprop.contraction": (2.625e4 * 2.0 + 3.482e4) * 1024,
-        "fprop.ifft": (1.754e4 * 2.0 + 1.693e4) * 1024,
-        "backward.fft": (8.607e3 * 2.0 + 3.482e4) * 1024,
+        "fprop.fft": (1.205e4 * 2.0 + 5.225e4) * 1024,
+        "fprop.contraction": (2.625e4 * 2.0 + 3.483e4) * 1024,
+        "fprop.ifft": (1.748e4 * 2.0 + 1.693e4) * 1024,
+        "backward.fft": (8.610e3 * 2.0 + 3.487e4) * 1024,
         "bprop.contraction": (2.617e4 * 2.0 + 3.482e4) * 1024,
-        "backward.contraction": (5.571e4 * 2.0 + 5.222e4) * 1024,
-        "bprop.ifft": (1.754e4 * 2.0 + 2.333e4) * 1024,
+        "backward.contraction": (5.572e4 * 2.0 + 5.313e4) * 1024,
+        "bprop.ifft": (1.748e4 * 2.0 + 2.333e4) * 1024,
         "accgrad.contraction": (3.489e4 * 2.0 + 1.741e4) * 1024,
-        "accgrad.ifft": (8.810e3 * 2.0 + 4.00e2) * 1024,
+        "accgrad.ifft": (8.778e3 * 2.0 + 4.00e2) * 1024,
     },
 }
 
