@@ -107,7 +107,7 @@ def run_step(hd, t, cfg, passes, reuse=False, basis=None):
             hd.fft_conv_accgrad_tiled(t["x"], t["gy"], basis, gw=t["gw"])
 
 
-BASES = (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128)
+BASES = (8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128)
 
 
 def library_basis(cfg):

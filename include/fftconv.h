@@ -19,7 +19,7 @@
  *  - Every function returns an fftconv_status; arguments are validated before anything
  *    is launched, so on an error other than FFTCONV_HIP_ERROR no device work was issued.
  *  - The Fourier basis is the smallest supported size that holds the image (8 ... 128: the
- *    powers of two of the paper's 2-D kernels, Section 5.3, and sizes 2^a x {3, 5, 7} between
+ *    powers of two of the paper's 2-D kernels, Section 5.3, and sizes 2^a x {3, 5, 7, 9} between
  *    them), square, or rectangular (each side on its own size) when both sides are at most
  *    32 and differ.  Layers that would need a larger basis, and layers for which it is
  *    clearly cheaper, are tiled (Section 6): the passes then run on windows of the images
@@ -70,9 +70,9 @@ size_t fftconv_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int
  * The three passes (Section 2; pipeline of Table 1; clipping sizes of Section 3.1).
  *   S minibatch, f input planes, fo output planes (f'), h x w input, kh x kw kernel,
  *   oh = h-kh+1, ow = w-kw+1.  Stride 1, no margin padding (Section 2 excludes strides).
- * Fourier basis: the smallest of 8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64 that holds the
- * image (the powers of two of Section 5 and, between them, the sizes 2^a x {3, 5, 7} of the
- * search space of Section 3.4); larger images are tiled (see the tiled passes below).  The
+ * Fourier basis: the smallest of 8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64 that
+ * holds the image (the powers of two of Section 5 and, between them, sizes 2^a x {3, 5, 7, 9} of
+ * the search space of Section 3.4); larger images are tiled (see the tiled passes below).  The
  * basis is square, N x N with N chosen for max(h, w), except that an image whose sides both
  * fit 32 and call for different sizes gets a rectangular basis N_h x N_w, each side the
  * smallest size that holds it (Section 3.1 only asks that every operand fit the common
@@ -107,7 +107,7 @@ int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *
  * tile_n = d + kh - 1 (columns alike): fprop and bprop by overlapping input windows, accGrad
  * by summing the per-tile correlations, the tile index joining the minibatch index in the
  * reduction.  Results equal those of the untiled calls up to rounding.  tile_n is one of the
- * bases 8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128, at least max(kh, kw); 0
+ * bases 8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128, at least max(kh, kw); 0
  * lets the library choose (the basis with the lowest estimated cost: tiles x bins per tile x a
  * measured per-basis factor).  A tile_n that holds the whole image (tile_n >= max(h, w)) runs
  * the untiled pipeline at that basis: this is how a caller names the Fourier basis of a layer.
@@ -226,8 +226,8 @@ int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size
 /*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
  * (Supplement, DFT definition); n is a power of two in 2..128 (256 for the 1-D calls: the
- * sizes of Section 5.3) or one of 12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112 (and 160, 192,
- * 224 for the 1-D calls): 2^a x {3, 5, 7}, sizes Section 3.2 takes from cuFFT; any other n
+ * sizes of Section 5.3) or one of 10, 12, 14, 18, 20, 24, 28, 36, 40, 48, 56, 80, 96, 112 (and
+ * 160, 192, 224 for the 1-D calls): 2^a x {3, 5, 7, 9}, sizes Section 3.2 takes from cuFFT; any other n
  * gives FFTCONV_UNSUPPORTED.  Inputs shorter than n are
  * zero-padded implicitly while loading (the clipping of Section 5.1), no padded copy is
  * made.  Complex data are interleaved (re,im) fp32; only the Hermitian half

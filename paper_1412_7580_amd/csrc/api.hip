@@ -28,10 +28,11 @@ struct fftconv_ctx {
     char last_hip_error[256];
 };
 
-// Fourier bases of the 2-D transforms: the powers of two 8 ... 128 (Section 5 of the paper) and
-// the sizes 2^a * {3, 5, 7} between them (the search space of Section 3.4 restricted to one odd
-// factor).
-static const int kBases[] = {8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128};
+// Fourier bases of the 2-D transforms: the powers of two 8 ... 128 (Section 5 of the paper) and,
+// between them, sizes 2^a * {3, 5, 7, 9} from the search space of Section 3.4: one odd factor
+// everywhere, and 10, 18 and 36, which close the widest gaps of that ladder below 40 (the
+// sizes with a factor 15 measured slower than the next power of two and are left out).
+static const int kBases[] = {8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128};
 static bool basis_ok(int n) {
     for (int b : kBases) if (b == n) return true;
     return false;

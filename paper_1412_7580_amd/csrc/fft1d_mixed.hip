@@ -1,4 +1,4 @@
-// 1-D transforms of the sizes with one odd factor 3, 5 or 7: 12 ... 224.  Eight lanes per line
+// 1-D transforms of the sizes with an odd factor 3, 5, 7 or 9: 10 ... 224.  Eight lanes per line
 // from 40 on (and at 24), as for the powers of two (more lanes with shorter register transforms
 // measured faster at every size there).  Signals per workgroup from a sweep of the base choice
 // against a half, a quarter and another lane split, same process (e.g. n = 96: 128 -> 64 signals
@@ -10,7 +10,10 @@ namespace fc {
 
 hipError_t launch_fft1d_r2c_mixed(const float *in, float *out, long B, int n_in, int n, LaunchCtx st) {
     switch (n) {
+        case 10: return run_fwd1d<5, 2, 256>(in, out, B, n_in, st);
         case 12: return run_fwd1d<3, 4, 128>(in, out, B, n_in, st);
+        case 18: return run_fwd1d<9, 2, 256>(in, out, B, n_in, st);
+        case 36: return run_fwd1d<9, 4, 128>(in, out, B, n_in, st);
         case 14: return run_fwd1d<7, 2, 256>(in, out, B, n_in, st);
         case 20: return run_fwd1d<5, 4, 128>(in, out, B, n_in, st);
         case 24: return run_fwd1d<3, 8, 128>(in, out, B, n_in, st);
@@ -30,7 +33,10 @@ hipError_t launch_fft1d_r2c_mixed(const float *in, float *out, long B, int n_in,
 
 hipError_t launch_fft1d_c2r_mixed(const float *in, float *out, long B, int n, int n_out, LaunchCtx st) {
     switch (n) {
+        case 10: return run_inv1d<5, 2, 256>(in, out, B, n_out, st);
         case 12: return run_inv1d<3, 4, 128>(in, out, B, n_out, st);
+        case 18: return run_inv1d<9, 2, 256>(in, out, B, n_out, st);
+        case 36: return run_inv1d<9, 4, 128>(in, out, B, n_out, st);
         case 14: return run_inv1d<7, 2, 256>(in, out, B, n_out, st);
         case 20: return run_inv1d<5, 4, 128>(in, out, B, n_out, st);
         case 24: return run_inv1d<3, 8, 128>(in, out, B, n_out, st);

@@ -31,10 +31,10 @@ hipError_t allow_big_lds(const void *fn, size_t bytes) {
 int fft2d_tile_log2(int N) {
     switch (N) {
         case 8: return 6;
-        case 12: case 14: case 16: return 5;
-        case 20: case 24: case 28: return 4;
+        case 10: case 12: case 14: case 16: return 5;
+        case 18: case 20: case 24: case 28: return 4;
         case 32: return 3;
-        case 40: case 48: case 56: case 64: return 2;
+        case 36: case 40: case 48: case 56: case 64: return 2;
         case 80: case 96: case 112: case 128: return 0;
         default: return -1;
     }

@@ -1,4 +1,4 @@
-// 2-D transforms of the sizes 12, 14, 20, 24 and 28 (one odd factor 3, 5 or 7 in the
+// 2-D transforms of the sizes 10, 12, 14, 18, 20, 24 and 28 (an odd factor 3, 5, 7 or 9 in the
 // per-lane part of the line, see fft_core.hpp), the small half of the bases Section 3.2 of the
 // fbfft paper reaches through cuFFT.
 #include "fft_kernels_impl.hpp"
@@ -12,7 +12,9 @@ namespace fc {
 
 hipError_t launch_fft2d_r2c_multi_small(const FwdOperand *ops, int nops, int N, LaunchCtx st) {
     switch (N) {
+        case 10: return run_fwd2d_multi<10, 1, 32>(ops, nops, st);
         case 12: return run_fwd2d_multi<12, 1, 32>(ops, nops, st);
+        case 18: return run_fwd2d_multi<18, 1, 16>(ops, nops, st);   // (9,2): 12.8 -> 15.3 us on an 18x18 layer
         case 14: return run_fwd2d_multi<14, 1, 32>(ops, nops, st);
         case 20: {
             // one lane per line on grids of a few rounds of workgroups (18x18 layer: 13.7 us against
@@ -31,7 +33,9 @@ hipError_t launch_fft2d_r2c_multi_small(const FwdOperand *ops, int nops, int N, 
 hipError_t launch_fft2d_r2c_small(const float *in, float *out, long planes, int h_in, int w_in, int N,
                                   bool conv, LaunchCtx st, const PlaneView *view) {
     switch (N) {
+        case 10: return run_fwd2d<10, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
         case 12: return run_fwd2d<12, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
+        case 18: return run_fwd2d<18, 1, 16>(in, out, planes, h_in, w_in, conv, st, view);
         case 14: return run_fwd2d<14, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);
         // (the natural layout, whose batches are large, keeps lane pairs: 4.9 against 4.7 TB/s at 28)
         case 20:
@@ -50,7 +54,9 @@ hipError_t launch_fft2d_r2c_small(const float *in, float *out, long planes, int 
 hipError_t launch_fft2d_c2r_small(const float *in, float *out, long planes, int N, int h_out, int w_out,
                                   bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view) {
     switch (N) {
+        case 10: return run_inv2d<5, 2, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 12: return run_inv2d<3, 4, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        case 18: return run_inv2d<9, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 14: return run_inv2d<7, 2, 32>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 20:
             if (!conv) return run_inv2d<10, 2, 16>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);

@@ -18,6 +18,8 @@ namespace fc {
 // Returns hipErrorNotSupported for the sizes that keep the convolution path's choice.
 hipError_t launch_fft2d_r2c_natural(const float *in, float *out, long planes, int h_in, int w_in, int N, LaunchCtx st) {
     switch (N) {
+        case 10: return run_fwd2d<5, 2, 32, false>(in, out, planes, h_in, w_in, false, st, nullptr);
+        case 18: return run_fwd2d<9, 2, 8, false>(in, out, planes, h_in, w_in, false, st, nullptr);
         case 14: return run_fwd2d<7, 2, 16, false>(in, out, planes, h_in, w_in, false, st, nullptr);
         case 16: return run_fwd2d<8, 2, 4, false>(in, out, planes, h_in, w_in, false, st, nullptr);
         case 20: return run_fwd2d<10, 2, 8, false>(in, out, planes, h_in, w_in, false, st, nullptr);
@@ -34,6 +36,7 @@ hipError_t launch_fft2d_r2c_natural(const float *in, float *out, long planes, in
 hipError_t launch_fft2d_c2r_natural(const float *in, float *out, long planes, int N, int h_out, int w_out,
                                     float scale, bool accumulate, LaunchCtx st) {
     switch (N) {
+        case 18: return run_inv2d<9, 2, 8, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
         case 8: return run_inv2d<4, 2, 64, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
         case 12: return run_inv2d<6, 2, 32, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);
         case 16: return run_inv2d<8, 2, 16, false>(in, out, planes, h_out, w_out, false, scale, accumulate, st, nullptr);

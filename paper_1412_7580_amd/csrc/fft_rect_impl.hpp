@@ -14,7 +14,7 @@ template <int LH, int GH, int LW, int GW>
 struct RectShape {
     static constexpr int NR = LH * GH, NC = LW * GW, RH = NR / 2, CH = NC / 2, NB = CH + 1;
     // planes per workgroup = tile of the layout: as for the square basis of the larger side
-    static constexpr int T = (NR >= 20 || NC >= 20) ? 16 : 32;
+    static constexpr int T = (NR >= 18 || NC >= 18) ? 16 : 32;
     static constexpr int ROW_LANES = T * GW * RH;   // (lane in line, plane, row pair)
     static constexpr int COL_LANES = T * GH * CH;   // (lane in line, plane, column slot)
     static constexpr int BT = ROW_LANES > COL_LANES ? ROW_LANES : COL_LANES;
@@ -272,7 +272,7 @@ __global__ void __launch_bounds__((RectShape<LH, GH, LW, GW>::BT)) fft2d_c2r_rec
 }
 
 // Tile and bin count of the plane-tiled layout of a rectangular basis.
-inline int rect_tile_log2(int nr, int nc) { return (nr >= 20 || nc >= 20) ? 4 : 5; }
+inline int rect_tile_log2(int nr, int nc) { return (nr >= 18 || nc >= 18) ? 4 : 5; }
 inline int rect_layout_bins(int nr, int nc) { return (nr * (nc / 2 + 1) + 7) / 8 * 8; }
 
 template <int LH, int GH, int LW, int GW>
@@ -349,14 +349,14 @@ static bool rect_dispatch(int nr, int nc, F &&f) {
         constexpr int NR = decltype(R)::value;
         switch (nc) {
 #define RECT_COL(NC_) case NC_: if constexpr (NR != NC_) { f(R, std::integral_constant<int, NC_>{}); return true; } return false;
-            RECT_COL(8) RECT_COL(12) RECT_COL(14) RECT_COL(16) RECT_COL(20) RECT_COL(24) RECT_COL(28) RECT_COL(32)
+            RECT_COL(8) RECT_COL(10) RECT_COL(12) RECT_COL(14) RECT_COL(16) RECT_COL(18) RECT_COL(20) RECT_COL(24) RECT_COL(28) RECT_COL(32)
 #undef RECT_COL
             default: return false;
         }
     };
     switch (nr) {
 #define RECT_ROW(NR_) case NR_: return cols(std::integral_constant<int, NR_>{});
-        RECT_ROW(8) RECT_ROW(12) RECT_ROW(14) RECT_ROW(16) RECT_ROW(20) RECT_ROW(24) RECT_ROW(28) RECT_ROW(32)
+        RECT_ROW(8) RECT_ROW(10) RECT_ROW(12) RECT_ROW(14) RECT_ROW(16) RECT_ROW(18) RECT_ROW(20) RECT_ROW(24) RECT_ROW(28) RECT_ROW(32)
 #undef RECT_ROW
         default: return false;
     }

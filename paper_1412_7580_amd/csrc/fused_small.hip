@@ -113,6 +113,7 @@ hipError_t launch_fused_fprop(const float *x, const float *wf, float *y, int S, 
     switch (N) {
         // lane pairs: twice the lanes for the product stage, whose W gathers set its pace
         case 8: return run_fused<4, 2, 64>(x, wf, y, S, f, fo, h, w, kh, kw, st);
+        case 10: return run_fused<5, 2, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
         case 12: return run_fused<6, 2, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
         case 14: return run_fused<7, 2, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);
         case 16: return run_fused<8, 2, 32>(x, wf, y, S, f, fo, h, w, kh, kw, st);

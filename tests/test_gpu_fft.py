@@ -11,7 +11,7 @@ from paper_1412_7580_amd import synth
 pytestmark = pytest.mark.gpu
 TOL = 1e-5
 POW2 = [8, 16, 32, 64, 128]                            # the sizes of Section 5 of the paper
-MIXED = [12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112]   # 2^a * {3, 5, 7}: the bases of Section 3.2
+MIXED = [10, 12, 14, 18, 20, 24, 28, 36, 40, 48, 56, 80, 96, 112]   # 2^a * {3, 5, 7, 9}: bases of Section 3.2
 SIZES = sorted(POW2 + MIXED)
 SIZES_1D = SIZES + [160, 192, 224, 256]   # the 1-D calls go one octave further (Section 5.3)
 
@@ -119,7 +119,7 @@ def test_argument_errors(hd, lib):
     import torch
     x = torch.zeros((4, 20), device="cuda")
     with pytest.raises(lib.FFTConvError, match="unsupported"):
-        hd.fft_r2c_1d(x, 36)            # 2^2 * 3^2: two odd factors
+        hd.fft_r2c_1d(x, 44)            # 2^2 * 11: no such size
     with pytest.raises(lib.FFTConvError, match="invalid"):
         hd.fft_r2c_1d(x, 16)            # n_in > n
     with pytest.raises(lib.FFTConvError, match="unsupported"):

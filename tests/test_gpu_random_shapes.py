@@ -46,7 +46,7 @@ def _draw(case):
     mode = ("ordinary", "tiled", "padded")[case % 3]
     cfg = dict(S=S, f=f, fo=fo, h=h, w=w, kh=kh, kw=kw)
     if mode == "tiled":
-        bases = [n for n in (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64) if n >= max(kh, kw)]
+        bases = [n for n in (8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64) if n >= max(kh, kw)]
         return cfg, mode, (int(rng.choice(bases + [0])),)
     if mode == "padded":
         return cfg, mode, (int(rng.integers(0, 4)), int(rng.integers(0, 4)))

@@ -12,7 +12,7 @@ from paper_1412_7580_amd import synth
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
-SIDES = (8, 12, 14, 16, 20, 24, 28, 32)
+SIDES = (8, 10, 12, 14, 16, 18, 20, 24, 28, 32)
 PAIRS = [(a, b) for a in SIDES for b in SIDES if a != b]
 
 
@@ -38,7 +38,7 @@ def _np(t):
 
 def _image_for(n, rng):
     """An image side whose smallest basis is n."""
-    lo = {8: 3, 12: 9, 14: 13, 16: 15, 20: 17, 24: 21, 28: 25, 32: 29}[n]
+    lo = {8: 3, 10: 9, 12: 11, 14: 13, 16: 15, 18: 17, 20: 19, 24: 21, 28: 25, 32: 29}[n]
     return int(rng.integers(lo, n + 1))
 
 

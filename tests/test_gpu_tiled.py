@@ -145,16 +145,17 @@ def test_tiled_workspace_and_errors(hd, lib):
     assert _relerr(_np(y), oracle.conv_fprop(x, w)) <= TOL
     with pytest.raises(lib.FFTConvError, match="workspace too small"):
         hd.fft_conv_fprop_tiled(dx, dw, 8, ws=ws[: need // 4 - 64])
-    for bad in (-1, 18, 256):
+    for bad in (-1, 22, 256):
         with pytest.raises(lib.FFTConvError, match="invalid argument"):
             hd.fft_conv_fprop_tiled(dx, dw, bad)
     big_k = torch.zeros((1, 1, 9, 9), device="cuda")
     with pytest.raises(lib.FFTConvError, match="invalid argument"):      # basis smaller than the kernel
         hd.fft_conv_fprop_tiled(torch.zeros((1, 1, 20, 20), device="cuda"), big_k, 8)
     assert hd.tile_basis(20, 20, 3, 3, 16) == 16
-    assert hd.tile_basis(200, 200, 5, 5, 0) in (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128)
+    assert hd.tile_basis(200, 200, 5, 5, 0) in (8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128)
     assert hd.tile_basis(20, 20, 3, 3, 12) == 12
-    assert hd.tile_basis(20, 20, 3, 3, 18) == 0
+    assert hd.tile_basis(20, 20, 3, 3, 18) == 18
+    assert hd.tile_basis(20, 20, 3, 3, 22) == 0
 
 
 def test_tiled_is_deterministic(hd):
@@ -166,7 +167,7 @@ def test_tiled_is_deterministic(hd):
     assert bool((a == b).all())
 
 
-BASES = (8, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64, 80, 96, 112, 128)
+BASES = (8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128)
 
 
 @pytest.mark.parametrize("n", [28, 32, 40, 56])
@@ -183,6 +184,31 @@ def test_named_basis_that_holds_the_image(hd, n):
     bins = {28: 424, 32: 544, 40: 864, 56: 1632}[n]     # n * (n/2 + 1), padded to the layout's unit
     pad = lambda planes: -(-planes // T) * T
     assert hd.tiled_workspace_bytes(0, 3, 5, 4, 27, 25, 5, 4, n) == (pad(15) + pad(20) + pad(12)) * bins * 2 * 4
+
+
+@pytest.mark.parametrize("n", [10, 18, 36])
+def test_bases_with_a_factor_nine_or_ten(hd, n):
+    """The sizes 10 = 2 x 5, 18 = 2 x 9 and 36 = 4 x 9: the ordinary calls take them for images
+    that fit, and the three passes agree with the oracle, whole and as a tile basis."""
+    cfg = dict(S=5, f=6, fo=9, h=n, w=n - 1, kh=3, kw=2)
+    assert hd.layer_basis(n, n, 3, 3) == (n, n, False)
+    x, w, gy = synth.conv_inputs(seed=330 + n, **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    ref = (oracle.conv_fprop(x, w), oracle.conv_bprop(gy, w, cfg["h"], cfg["w"]), oracle.conv_accgrad(x, gy))
+    got = (hd.fft_conv_fprop_tiled(dx, dw, n), hd.fft_conv_bprop_tiled(dgy, dw, cfg["h"], cfg["w"], n),
+           hd.fft_conv_accgrad_tiled(dx, dgy, n))
+    for g, r in zip(got, ref):
+        assert _relerr(_np(g), r) <= TOL
+    # a larger image cut into tiles of this basis
+    big = dict(S=2, f=3, fo=4, h=3 * n + 1, w=2 * n + 5, kh=3, kw=3)
+    x, w, gy = synth.conv_inputs(seed=340 + n, **big)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    assert hd.tile_basis(big["h"], big["w"], 3, 3, n) == n
+    ref = (oracle.conv_fprop(x, w), oracle.conv_bprop(gy, w, big["h"], big["w"]), oracle.conv_accgrad(x, gy))
+    got = (hd.fft_conv_fprop_tiled(dx, dw, n), hd.fft_conv_bprop_tiled(dgy, dw, big["h"], big["w"], n),
+           hd.fft_conv_accgrad_tiled(dx, dgy, n))
+    for g, r in zip(got, ref):
+        assert _relerr(_np(g), r) <= TOL
 
 
 def test_autotune_basis(hd):

@@ -7,7 +7,7 @@ import pytest
 import oracle
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
-SIZES = [8, 12, 14, 16, 20, 28, 32, 56, 64, 96, 128]   # powers of two and sizes with a factor 3, 5 or 7
+SIZES = [8, 10, 12, 14, 16, 18, 20, 28, 32, 36, 56, 64, 96, 128]   # powers of two and sizes with a factor 3, 5, 7 or 9
 
 
 def test_closed_forms_from_fixture():
