@@ -743,7 +743,7 @@ def main():
         extra["fft_sweep_256MiB"] = fft_sweep(hd)
         torch.cuda.empty_cache()
         # the sizes with an odd factor (not part of the benchmark definition's sweep)
-        extra["fft_sweep_mixed_sizes_256MiB"] = fft_sweep(hd, sizes=(12, 14, 20, 24, 28, 40, 48, 56, 80, 96, 112),
+        extra["fft_sweep_mixed_sizes_256MiB"] = fft_sweep(hd, sizes=(10, 12, 14, 18, 20, 24, 28, 36, 40, 48, 56, 80, 96, 112),
                                                           sizes_1d_only=(160, 192, 224))
         out["extra"] = extra
     print(json.dumps(out))
