@@ -3,8 +3,8 @@
 
 One step = fprop + bprop + accGrad of the headline layer (S=128, f=f'=64, 27x27 input,
 5x5 kernel, 32x32 Fourier basis) as the two calls fft_conv_fprop_save + fft_conv_backward:
-seven kernel launches (x, w and gy are transformed once each, the two backward contractions
-share a launch, three inverse transforms with crop).  Inputs are seeded synthetic fp32 tensors
+six kernel launches (x, w and gy are transformed once each, the two backward contractions
+share a launch and so do the inverse transforms of the two gradients).  Inputs are seeded synthetic fp32 tensors
 already resident in device memory.  `extra` holds the same step as three independent passes,
 on the library's own Fourier basis, the other configurations, tiled layers, the FFT sweep.
 
@@ -42,6 +42,7 @@ MEASURED_TRAFFIC_BYTES = {
         "bprop.ifft": (1.748e4 * 2.0 + 2.333e4) * 1024,
         "accgrad.contraction": (3.489e4 * 2.0 + 1.741e4) * 1024,
         "accgrad.ifft": (8.778e3 * 2.0 + 4.00e2) * 1024,
+        "backward.ifft": (2.619e4 * 2.0 + 2.373e4) * 1024,
     },
 }
 
@@ -163,8 +164,10 @@ def profile_stages(hd, t, cfg, passes, steps, basis=None):
 
 FPROP_KERNELS = ("fprop.fft", "fprop.contraction", "fprop.ifft")
 # fft_conv_backward: five launches, or four when both contractions go out as one launch
+# (and three when the two inverse transforms share a launch as well)
 BACKWARD_KERNELS = {5: ("backward.fft", "bprop.contraction", "bprop.ifft", "accgrad.contraction", "accgrad.ifft"),
-                    4: ("backward.fft", "backward.contraction", "bprop.ifft", "accgrad.ifft")}
+                    4: ("backward.fft", "backward.contraction", "bprop.ifft", "accgrad.ifft"),
+                    3: ("backward.fft", "backward.contraction", "backward.ifft")}
 
 
 def profile_reuse_step(hd, t, cfg, steps, basis=None):
@@ -638,6 +641,8 @@ def main():
             elif k == "backward.contraction":
                 mb, ma = models["bprop"]["contraction"], models["accgrad"]["contraction"]
                 model = {"bytes": mb["bytes"] + ma["bytes"], "flops": mb["flops"] + ma["flops"]}
+            elif k == "backward.ifft":
+                model = {"bytes": models["bprop"]["ifft"]["bytes"] + models["accgrad"]["ifft"]["bytes"]}
             else:
                 model = models[p][s_]
             kernels[k] = entry(ms, model)

@@ -310,6 +310,23 @@ static hipError_t invert(fftconv_ctx *c, const PassPlan &p, const float *CF, flo
                             p.viewC ? &p.vC : nullptr);
 }
 
+// The two inverse transforms of the backward pass (gx from plan pb, gw from plan pa): one
+// launch where the basis has one inverse kernel for every operand, else one after the other.
+static hipError_t invert_pair(fftconv_ctx *c, const PassPlan &pb, const float *GXF, float *gx, const PassPlan &pa,
+                              const float *GWF, float *gw, float scale, int accumulate) {
+    if (!pb.rect && !pa.rect && pb.N == pa.N) {
+        const float sb = 1.0f / ((float)pb.N * (float)pb.N), sa = scale / ((float)pa.N * (float)pa.N);
+        const InvOperand ops[2] = {{GXF, gx, pb.planesC, pb.hC, pb.wC, sb, false, pb.viewC ? &pb.vC : nullptr},
+                                   {GWF, gw, pa.planesC, pa.hC, pa.wC, sa, accumulate != 0, pa.viewC ? &pa.vC : nullptr}};
+        const int nk = c->nk;
+        const hipError_t e = launch_fft2d_c2r_pair(ops, pb.N, next_ctx(c));
+        if (e != hipErrorNotSupported) return e;
+        c->nk = nk;   // nothing was launched: give the event pair back
+    }
+    if (hipError_t e = invert(c, pb, GXF, gx, 1.0f, 0); e != hipSuccess) return e;
+    return invert(c, pa, GWF, gw, scale, accumulate);
+}
+
 // Contraction + inverse transform of one pass, operands already in the frequency domain.
 static hipError_t contract_and_invert(fftconv_ctx *c, const PassPlan &p, const float *AF, const float *BF,
                                       float *CF, float *out, float scale, int accumulate) {
@@ -725,8 +742,7 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
             // (the one with the longer reduction first: its workgroups run longest)
             const bool a_first = pa.K >= pb.K;
             if ((e = launch_cgemm_pair(a_first ? qa : qb, a_first ? qb : qa, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
-            if ((e = invert(hd, pb, GXF, gx, 1.0f, 0)) != hipSuccess) return hip_fail(hd, e);
-            if ((e = invert(hd, pa, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
+            if ((e = invert_pair(hd, pb, GXF, gx, pa, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
             return FFTCONV_OK;
         }
     }

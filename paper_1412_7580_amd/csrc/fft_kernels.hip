@@ -113,6 +113,17 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
     }
 }
 
+hipError_t launch_fft2d_c2r_pair(const InvOperand *ops, int N, LaunchCtx st) {
+    for (int o = 0; o < 2; ++o) {
+        const int rows = ops[o].h_out + (ops[o].view ? ops[o].view->oy : 0), cols = ops[o].w_out + (ops[o].view ? ops[o].view->ox : 0);
+        if (ops[o].planes <= 0 || rows > N || cols > N) return hipErrorNotSupported;
+    }
+    switch (N) {
+        case 32: return run_inv2d_pair<8, 4, 8>(ops, st);
+        default: return launch_fft2d_c2r_pair_mixed(ops, N, st);
+    }
+}
+
 // Lanes per line of the 1-D kernels: more lanes with shorter register FFTs measured faster at
 // every size (fewer registers per lane, more loads in flight), e.g. n = 64: (8,8) 5.3 TB/s against
 // (32,2) 4.8; n = 256: (32,8) 4.2 against (64,4) 2.7; (2,4) at n = 8 lost.  Signals per workgroup

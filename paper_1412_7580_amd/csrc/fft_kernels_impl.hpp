@@ -659,6 +659,22 @@ __global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_kernel(Inv2dPara
     fft2d_c2r_body<L, G, T, CONV, ISTAGE>(prm, blockIdx.x);
 }
 
+
+// Two inverse transforms (plane-tiled layout, both staged through LDS) in ONE launch: the blocks
+// of operand o are [first[o], first[o+1]).  For the two products of fft_conv_backward (gx and gw),
+// whose grids are short: one ramp-up and one tail instead of two.
+struct InvPairParams {
+    Inv2dParams op[2];
+    unsigned first[3];
+};
+
+template <int L, int G, int T>
+__global__ void __launch_bounds__(T *(L * G / 2) * G) fft2d_c2r_pair_kernel(InvPairParams m) {
+    const unsigned b = blockIdx.x;
+    const int o = b >= m.first[1];
+    fft2d_c2r_body<L, G, T, true, true>(m.op[o], b - m.first[o]);
+}
+
 // ------------------------------------------------------------------ 1-D forward
 struct Fwd1dParams {
     const float *in;
@@ -968,10 +984,12 @@ static hipError_t run_fwd2d_multi(const FwdOperand *ops, int nops, LaunchCtx st)
     return hipGetLastError();
 }
 
-template <int L, int G, int T, bool CONV_TOO = true>
-static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out, int w_out,
-                            bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view) {
-    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+// Parameters and LDS bytes of one inverse launch; *istage_out tells whether the plane-tiled input
+// is staged through LDS (always for the natural layout).
+template <int L, int G, int T>
+static Inv2dParams make_inv2d(const float *in, float *out, long planes, int h_out, int w_out, bool conv, float scale,
+                              bool accumulate, const PlaneView *view, size_t *lds_out, bool *istage_out) {
+    constexpr int N = L * G, NH = N / 2;
     Inv2dParams prm;
     prm.tiled = 0; prm.info_off = 0; prm.win_h = prm.win_w = 0; prm.view = PlaneView{};
     prm.div_w = prm.div_h = MagicDiv{0};
@@ -1003,6 +1021,18 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
         const size_t c = (size_t)T * N * (NH + 1) * sizeof(float2);
         if (c > lds) lds = c;
     }
+    *lds_out = lds;
+    *istage_out = istage;
+    return prm;
+}
+
+template <int L, int G, int T, bool CONV_TOO = true>
+static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out, int w_out,
+                            bool conv, float scale, bool accumulate, LaunchCtx st, const PlaneView *view) {
+    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+    size_t lds;
+    bool istage;
+    Inv2dParams prm = make_inv2d<L, G, T>(in, out, planes, h_out, w_out, conv, scale, accumulate, view, &lds, &istage);
     lds = with_twiddle_table<L, G>(lds, &prm.tw_off);
     if (prm.tiled) lds = with_origin_table(lds, T, &prm.info_off);
     const unsigned grid = (unsigned)((planes + T - 1) / T);
@@ -1018,6 +1048,39 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
         if (conv) return hipErrorInvalidValue;
     }
     return go(fft2d_c2r_kernel<L, G, T, false, true>);
+}
+
+// Two operands in one launch; for (L, G, T) with T <= 16, where the plane-tiled input is always
+// staged, so that both operands run the same kernel variant.
+template <int L, int G, int T>
+static hipError_t run_inv2d_pair(const InvOperand *ops, LaunchCtx st) {
+    static_assert(T <= 16, "the shared launch needs the staged variant for every operand");
+    constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
+    InvPairParams m;
+    size_t lds = 0;
+    unsigned blocks = 0;
+    bool any_tiled = false;
+    for (int o = 0; o < 2; ++o) {
+        size_t l;
+        bool istage;
+        m.first[o] = blocks;
+        m.op[o] = make_inv2d<L, G, T>(ops[o].in, ops[o].out, ops[o].planes, ops[o].h_out, ops[o].w_out, true,
+                                      ops[o].scale, ops[o].accumulate, ops[o].view, &l, &istage);
+        if (!istage) return hipErrorInvalidValue;
+        if (l > lds) lds = l;
+        any_tiled = any_tiled || m.op[o].tiled;
+        blocks += (unsigned)((ops[o].planes + T - 1) / T);
+    }
+    m.first[2] = blocks;
+    int tw_off = 0, info_off = 0;
+    lds = with_twiddle_table<L, G>(lds, &tw_off);
+    if (any_tiled) lds = with_origin_table(lds, T, &info_off);
+    for (int o = 0; o < 2; ++o) { m.op[o].tw_off = tw_off; m.op[o].info_off = info_off; }
+    if (blocks == 0) return hipSuccess;
+    auto k = fft2d_c2r_pair_kernel<L, G, T>;
+    if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
+    launch_kernel(k, dim3(blocks), dim3(BT), lds, st, m);
+    return hipGetLastError();
 }
 
 template <int L, int G, int TB>
@@ -1067,6 +1130,7 @@ hipError_t launch_fft2d_c2r_mixed(const float *in, float *out, long planes, int 
 hipError_t launch_fft2d_r2c_natural(const float *in, float *out, long planes, int h_in, int w_in, int N, LaunchCtx st);
 hipError_t launch_fft2d_c2r_natural(const float *in, float *out, long planes, int N, int h_out, int w_out,
                                     float scale, bool accumulate, LaunchCtx st);
+hipError_t launch_fft2d_c2r_pair_mixed(const InvOperand *ops, int N, LaunchCtx st);
 hipError_t launch_fft1d_r2c_mixed(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
 hipError_t launch_fft1d_c2r_mixed(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);
 

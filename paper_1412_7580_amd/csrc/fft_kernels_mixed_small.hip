@@ -72,4 +72,14 @@ hipError_t launch_fft2d_c2r_small(const float *in, float *out, long planes, int 
     }
 }
 
+// The bases whose inverse kernel does not depend on the operand (same choices as above).
+hipError_t launch_fft2d_c2r_pair_small(const InvOperand *ops, int N, LaunchCtx st) {
+    switch (N) {
+        case 18: return run_inv2d_pair<9, 2, 16>(ops, st);
+        case 20: return run_inv2d_pair<20, 1, 16>(ops, st);
+        case 24: return run_inv2d_pair<6, 4, 16>(ops, st);
+        default: return hipErrorNotSupported;
+    }
+}
+
 }  // namespace fc

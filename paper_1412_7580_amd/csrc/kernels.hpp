@@ -111,6 +111,20 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
                             bool conv_layout, float scale, bool accumulate, LaunchCtx st,
                             const PlaneView *view = nullptr);
 
+// Two inverse transforms of the plane-tiled layout in ONE launch (the two products of the
+// backward pass).  hipErrorNotSupported for the bases whose inverse kernel depends on the
+// operand (how many rows are kept): the caller then launches them one after the other.
+struct InvOperand {
+    const float *in;
+    float *out;
+    long planes;
+    int h_out, w_out;
+    float scale;
+    bool accumulate;
+    const PlaneView *view = nullptr;
+};
+hipError_t launch_fft2d_c2r_pair(const InvOperand *ops, int N, LaunchCtx st);
+
 // One-launch fprop of a small layer (basis N <= 16, f and f' within one plane tile): one
 // workgroup per sample; wf is the weight transform in the layout of basis N.
 bool fused_fprop_supported(int N, int f, int fo, const float *wf);
