@@ -58,15 +58,10 @@ hipError_t launch_fft2d_c2r_mixed(const float *in, float *out, long planes, int 
 
 hipError_t launch_fft2d_c2r_pair_small(const InvOperand *ops, int N, LaunchCtx st);
 
-// The bases whose inverse kernel does not depend on the operand (same choices as above).
+// (From 36 on the backward pass never pairs its products: the contractions of those bases go out
+// as separate launches, each followed by its inverse transform.)
 hipError_t launch_fft2d_c2r_pair_mixed(const InvOperand *ops, int N, LaunchCtx st) {
-    switch (N) {
-        case 36: return run_inv2d_pair<9, 4, 4>(ops, st);
-        case 40: return run_inv2d_pair<10, 4, 4>(ops, st);
-        case 48: return run_inv2d_pair<12, 4, 4>(ops, st);
-        case 56: return run_inv2d_pair<14, 4, 4>(ops, st);
-        default: return launch_fft2d_c2r_pair_small(ops, N, st);
-    }
+    return launch_fft2d_c2r_pair_small(ops, N, st);
 }
 
 }  // namespace fc
