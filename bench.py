@@ -304,8 +304,15 @@ def graph_replay_c1(hd, reps=200):
     # the same fprop as ONE launch (fft_conv_fprop_fused, on weights transformed ahead)
     wf = hd.fft_conv_transform_weights(t["w"], cfg["h"], cfg["w"])
     fused = timed(lambda: hd.fft_conv_fprop_fused(t["x"], wf, cfg["fo"], cfg["kh"], cfg["kw"], y=t["y"]))
+    # and the layer's bprop: ordinary call against the one-launch kernel
+    gy = torch.empty_like(t["y"]).uniform_(-1, 1)
+    gx = torch.empty_like(t["x"])
+    dims = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    bprop = timed(lambda: hd.fft_conv_bprop(gy, t["w"], cfg["h"], cfg["w"], gx=gx))
+    bfused = timed(lambda: hd.fft_conv_bprop_fused(gy, wf, *dims, gx=gx))
     return {"eager_us_per_fprop": round(eager * 1e6, 2), "graph_replay_us_per_fprop": round(replay * 1e6, 2),
-            "fused_one_launch_us_per_fprop": round(fused * 1e6, 2)}
+            "fused_one_launch_us_per_fprop": round(fused * 1e6, 2),
+            "eager_us_per_bprop": round(bprop * 1e6, 2), "fused_one_launch_us_per_bprop": round(bfused * 1e6, 2)}
 
 
 def tiled_layers(hd, reps=10):

@@ -224,6 +224,16 @@ int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size
                          int S, int f, int fo, int h, int w, int kh, int kw);
 
 /*
+ * bprop of a small layer in ONE launch, the counterpart of fft_conv_fprop_fused (same weights
+ * buffer wf, same support rule with the same f and fo, same error behaviour): one workgroup
+ * carries one sample's fo gradient planes gy through transform, product GX_i = sum_j GY_j . W_ji
+ * and inverse with crop to h x w.  gy [S, fo, h-kh+1, w-kw+1] (device, read only), gx
+ * [S, f, h, w] (device, overwritten).  Same result as fft_conv_bprop up to rounding.
+ */
+int fft_conv_bprop_fused(fftconv_handle hd, const float *gy, const void *wf, size_t wf_bytes, float *gx,
+                         int S, int f, int fo, int h, int w, int kh, int kw);
+
+/*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)
  * (Supplement, DFT definition); n is a power of two in 2..128 (256 for the 1-D calls: the
  * sizes of Section 5.3) or one of 10, 12, 14, 18, 20, 24, 28, 36, 40, 48, 56, 80, 96, 112 (and

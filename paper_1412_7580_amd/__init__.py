@@ -24,7 +24,7 @@ SYMBOLS = [
     "fftconv_saved_bytes_tiled", "fftconv_backward_workspace_bytes_tiled",
     "fft_conv_fprop_save_tiled", "fft_conv_backward_tiled",
     "fftconv_weights_bytes", "fft_conv_transform_weights", "fft_conv_fprop_weights", "fft_conv_bprop_weights",
-    "fft_conv_fprop_fused",
+    "fft_conv_fprop_fused", "fft_conv_bprop_fused",
     "fftconv_padded_workspace_bytes",
     "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
     "fftconv_saved_bytes_padded", "fftconv_backward_workspace_bytes_padded",
@@ -92,6 +92,7 @@ def load_library():
     lib.fft_conv_fprop_weights.argtypes = [vp, vp, vp, sz, vp] + [i] * 9 + [vp, sz]
     lib.fft_conv_bprop_weights.argtypes = [vp, vp, vp, sz, vp] + [i] * 9 + [vp, sz]
     lib.fft_conv_fprop_fused.argtypes = [vp, vp, vp, sz, vp] + [i] * 7
+    lib.fft_conv_bprop_fused.argtypes = [vp, vp, vp, sz, vp] + [i] * 7
     lib.fftconv_padded_workspace_bytes.argtypes = [i] * 10
     lib.fftconv_padded_workspace_bytes.restype = sz
     lib.fft_conv_fprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
@@ -410,6 +411,19 @@ class Handle:
         _check(self._lib.fft_conv_fprop_fused(self._h, _dev_f32(x, "x"), *self._ws(wf), _dev_f32(y, "y"),
                                               S, f, fo, h, w, kh, kw), "fft_conv_fprop_fused")
         return y
+
+    def fft_conv_bprop_fused(self, gy, wf, f, h, w, kh, kw, gx=None):
+        """One-launch bprop of a small layer; raises FFTConvError("unsupported ...") for others."""
+        import torch
+        S, fo, oh, ow = gy.shape
+        if oh != h - kh + 1 or ow != w - kw + 1:
+            raise FFTConvError("gy and (h, w, kh, kw) disagree")
+        if gx is None:
+            gx = torch.empty((S, f, h, w), device=gy.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_bprop_fused(self._h, _dev_f32(gy, "gy"), *self._ws(wf), _dev_f32(gx, "gx"),
+                                              S, f, fo, h, w, kh, kw), "fft_conv_bprop_fused")
+        return gx
 
     def fft_conv_bprop_weights(self, gy, wf, f, h, w, kh, kw, pad_h=0, pad_w=0, gx=None, ws=None):
         import torch

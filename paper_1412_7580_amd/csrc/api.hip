@@ -841,4 +841,18 @@ int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
+int fft_conv_bprop_fused(fftconv_handle hd, const float *gy, const void *wf, size_t wf_bytes, float *gx,
+                         int S, int f, int fo, int h, int w, int kh, int kw) {
+    if (!hd || !gy || !wf || !gx) return FFTCONV_INVALID_ARG;
+    PassPlan p;
+    int rc = make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &p);
+    if (rc != FFTCONV_OK) return rc;
+    if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
+    if (p.tiled || p.rect || !fused_bprop_supported(p.N, f, fo, static_cast<const float *>(wf))) return FFTCONV_UNSUPPORTED;
+    hd->nk = 0;
+    const hipError_t e = launch_fused_bprop(gy, static_cast<const float *>(wf), gx, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd));
+    if (e == hipErrorInvalidValue) return FFTCONV_UNSUPPORTED;   // the layer's planes do not fit the kernel's LDS plan
+    return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
+}
+
 }  // extern "C"

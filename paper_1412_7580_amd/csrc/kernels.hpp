@@ -131,6 +131,11 @@ bool fused_fprop_supported(int N, int f, int fo, const float *wf);
 hipError_t launch_fused_fprop(const float *x, const float *wf, float *y, int S, int f, int fo, int h, int w,
                               int kh, int kw, int N, LaunchCtx st);
 
+// bprop likewise (GX_i = sum_j GY_j . W_ji): one workgroup per sample, same support rule.
+bool fused_bprop_supported(int N, int f, int fo, const float *wf);
+hipError_t launch_fused_bprop(const float *gy, const float *wf, float *gx, int S, int f, int fo, int h, int w,
+                              int kh, int kw, int N, LaunchCtx st);
+
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
 hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);
 

@@ -292,6 +292,27 @@ def test_fused_fprop(hd, lib, cfg):
     assert float((y - y3).abs().max()) <= 2e-5 * float(np.max(np.abs(ref)))
 
 
+@pytest.mark.parametrize("cfg", FUSED, ids=lambda c: "S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c))
+def test_fused_bprop(hd, lib, cfg):
+    """The one-launch bprop of small layers against the oracle and against the three-launch path."""
+    import torch
+    _, w, gy = synth.conv_inputs(seed=89, **cfg)
+    dgy, dw = _dev(gy), _dev(w)
+    wf = hd.fft_conv_transform_weights(dw, cfg["h"], cfg["w"])
+    args = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+    gx = hd.fft_conv_bprop_fused(dgy, wf, *args)
+    torch.cuda.synchronize()
+    ref = oracle.conv_bprop(gy, w, cfg["h"], cfg["w"])
+    assert gx.shape == ref.shape
+    assert _relerr(_np(gx), ref) <= TOL
+    gx3 = hd.fft_conv_bprop_weights(dgy, wf, *args)
+    assert float((gx - gx3).abs().max()) <= 2e-5 * float(np.max(np.abs(ref)))
+    # a second call into the same output (stale LDS or output contents must not matter)
+    gx.fill_(7.0)
+    hd.fft_conv_bprop_fused(dgy, wf, *args, gx=gx)
+    assert _relerr(_np(gx), ref) <= TOL
+
+
 def test_fused_fprop_unsupported_shapes(hd, lib):
     import torch
     for cfg in (dict(S=2, f=12, fo=8, h=13, w=13, kh=3, kw=3),     # f does not divide the plane tile
@@ -304,3 +325,6 @@ def test_fused_fprop_unsupported_shapes(hd, lib):
         wf = hd.fft_conv_transform_weights(w, cfg["h"], cfg["w"])
         with pytest.raises(lib.FFTConvError, match="unsupported"):
             hd.fft_conv_fprop_fused(x, wf, cfg["fo"], cfg["kh"], cfg["kw"])
+        gy = torch.zeros((cfg["S"], cfg["fo"], cfg["h"] - cfg["kh"] + 1, cfg["w"] - cfg["kw"] + 1), device="cuda")
+        with pytest.raises(lib.FFTConvError, match="unsupported"):
+            hd.fft_conv_bprop_fused(gy, wf, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
