@@ -66,7 +66,8 @@ def test_graph_replay_equals_eager(hd, lib, cfg):
 
 def test_graph_replay_of_inference_paths(hd, lib):
     """fprop on weights transformed ahead, as three launches (caller's workspace) and as the
-    one-launch kernel (no workspace at all): captured once, replayed with changing inputs."""
+    one-launch kernel (no workspace at all), and the one-launch bprop: captured once, replayed
+    with changing inputs."""
     import torch
     cfg = dict(S=16, f=16, fo=16, h=16, w=16, kh=3, kw=3)       # basis 16: the fused kernel needs > 64 KB of LDS
     x, w, _ = synth.conv_inputs(seed=601, **cfg)
@@ -76,15 +77,17 @@ def test_graph_replay_of_inference_paths(hd, lib):
     ws = torch.empty(hd.workspace_bytes(lib.FPROP, *dims) // 4, device="cuda", dtype=torch.float32)
     y3 = torch.empty((16, 16, 14, 14), device="cuda")
     y1 = torch.empty_like(y3)
+    gx1 = torch.empty_like(dx)          # the one-launch bprop, fed with the fused fprop's output
 
     def step():
         hd.fft_conv_fprop_weights(dx, wf, cfg["fo"], 3, 3, y=y3, ws=ws)
         hd.fft_conv_fprop_fused(dx, wf, cfg["fo"], 3, 3, y=y1)
+        hd.fft_conv_bprop_fused(y1, wf, cfg["f"], 16, 16, 3, 3, gx=gx1)
 
     def eager():
         step()
         torch.cuda.synchronize()
-        return y3.clone(), y1.clone()
+        return y3.clone(), y1.clone(), gx1.clone()
 
     ref = eager()                       # warm-up: kernel attributes are set outside the capture
     graph = torch.cuda.CUDAGraph()
@@ -94,9 +97,9 @@ def test_graph_replay_of_inference_paths(hd, lib):
         if rep == 1:
             dx.mul_(-1.5)
             ref = eager()
-        y3.zero_(); y1.zero_()
+        y3.zero_(); y1.zero_(); gx1.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert torch.equal(y3, ref[0]) and torch.equal(y1, ref[1]), rep
+        assert torch.equal(y3, ref[0]) and torch.equal(y1, ref[1]) and torch.equal(gx1, ref[2]), rep
         _ = (dx + 1).sum().item()
