@@ -169,6 +169,38 @@ int main(int argc, char **argv) {
         free(xp); free(ryp);
     }
 
+    /* ---- which basis the layer above ran on: 21 x 18 calls for a rectangular 24 x 18 */
+    {
+        int nr = 0, nc = 0;
+        const int tiled = fftconv_layer_basis(h, w, kh, kw, 0, 0, &nr, &nc);
+        if (tiled != 0 || nr != 24 || nc != 18) { printf("layer basis %d x %d (tiled %d)  FAIL\n", nr, nc, tiled); ++bad; }
+    }
+
+    /* ---- a small layer on weights transformed ahead: fprop and bprop as one launch each */
+    {
+        const int S2 = 2, f2 = 8, fo2 = 8, h2 = 13, k2 = 3, o2 = h2 - k2 + 1;
+        const size_t nx2 = (size_t)S2 * f2 * h2 * h2, nw2 = (size_t)fo2 * f2 * k2 * k2, ny2 = (size_t)S2 * fo2 * o2 * o2;
+        float *x2 = host_random(nx2), *w2 = host_random(nw2), *g2 = host_random(ny2);
+        double *x2d = widen(x2, nx2), *w2d = widen(w2, nw2), *g2d = widen(g2, ny2);
+        double *ry2 = (double *)malloc(ny2 * sizeof(double)), *rgx2 = (double *)malloc(nx2 * sizeof(double));
+        oracle_conv_fprop(x2d, w2d, ry2, S2, f2, fo2, h2, h2, k2, k2, NULL, 0);
+        oracle_conv_bprop(g2d, w2d, rgx2, S2, f2, fo2, h2, h2, k2, k2, NULL, 0);
+        float *dx2 = to_device(x2, nx2), *dw2 = to_device(w2, nw2), *dg2 = to_device(g2, ny2), *dy2, *dgx2;
+        HIP_OK(hipMalloc((void **)&dy2, ny2 * sizeof(float)));
+        HIP_OK(hipMalloc((void **)&dgx2, nx2 * sizeof(float)));
+        const size_t wb = fftconv_weights_bytes(f2, fo2, h2, h2, k2, k2, 0, 0);
+        void *wf;
+        HIP_OK(hipMalloc(&wf, wb));
+        FC_OK(fft_conv_transform_weights(hd, dw2, wf, wb, f2, fo2, h2, h2, k2, k2, 0, 0));
+        FC_OK(fft_conv_fprop_fused(hd, dx2, wf, wb, dy2, S2, f2, fo2, h2, h2, k2, k2));
+        bad += check("fft_conv_fprop_fused", dy2, ry2, ny2, 1e-4);
+        FC_OK(fft_conv_bprop_fused(hd, dg2, wf, wb, dgx2, S2, f2, fo2, h2, h2, k2, k2));
+        bad += check("fft_conv_bprop_fused", dgx2, rgx2, nx2, 1e-4);
+        HIP_OK(hipFree(dx2)); HIP_OK(hipFree(dw2)); HIP_OK(hipFree(dg2)); HIP_OK(hipFree(dy2)); HIP_OK(hipFree(dgx2));
+        HIP_OK(hipFree(wf));
+        free(x2); free(w2); free(g2); free(x2d); free(w2d); free(g2d); free(ry2); free(rgx2);
+    }
+
     /* ---- a batch of 1-D transforms: 1000 signals of 61 samples, n = 64 */
     {
         const long B = 1000; const int n_in = 61, n = 64, nb = n / 2 + 1;

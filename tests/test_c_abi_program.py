@@ -1,6 +1,6 @@
 """The library driven from plain C: tests/c_abi/check_passes.c includes include/fftconv.h as C99,
 links libfftconv.so and the C oracle, and checks the passes, a tiled and a padded fprop, the
-transform-reuse pair and a 1-D transform on device buffers it allocates with the HIP runtime."""
+transform-reuse pair, the one-launch passes of a small layer and a 1-D transform on device buffers it allocates with the HIP runtime."""
 import importlib.util
 import os
 import subprocess
@@ -35,4 +35,4 @@ def test_plain_c_caller_matches_oracle():
     print(run.stdout, run.stderr)
     assert run.returncode == 0, run.stdout + run.stderr
     assert "all checks passed" in run.stdout
-    assert run.stdout.count("  ok\n") == 9
+    assert run.stdout.count("  ok\n") == 11
