@@ -107,8 +107,8 @@ int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *
  * tile_n = d + kh - 1 (columns alike): fprop and bprop by overlapping input windows, accGrad
  * by summing the per-tile correlations, the tile index joining the minibatch index in the
  * reduction.  Results equal those of the untiled calls up to rounding.  tile_n is one of the
- * bases 8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128, at least max(kh, kw); 0
- * lets the library choose (the basis with the lowest estimated cost: tiles x bins per tile x a
+ * bases 8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128, at least
+ * max(kh, kw); 0 lets the library choose (the basis with the lowest estimated cost: tiles x bins per tile x a
  * measured per-basis factor).  A tile_n that holds the whole image (tile_n >= max(h, w)) runs
  * the untiled pipeline at that basis: this is how a caller names the Fourier basis of a layer.
  * The entry points above tile by themselves, with the library's choice, when max(h, w) > 128
@@ -139,7 +139,10 @@ int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, f
  * operands (device, read only); y, gx, gw (device) are overwritten and hold the chosen basis's
  * results on return.  Uses the handle's own workspace, which grows to the largest candidate's
  * need.  Synchronous: returns after the last run has finished.  Errors as for the passes;
- * reps <= 0 or a NULL pointer other than ms_out gives FFTCONV_INVALID_ARG.
+ * reps <= 0 or a NULL pointer other than ms_out gives FFTCONV_INVALID_ARG.  The candidates are
+ * the square bases; for a non-square image whose sides both fit 32 the ordinary entry points
+ * use a rectangular basis (see fftconv_layer_basis), which is not among them and is usually
+ * the faster choice there.
  */
 int fftconv_autotune_basis(fftconv_handle hd, const float *x, const float *wt, const float *gy,
                            float *y, float *gx, float *gw, int S, int f, int fo, int h, int w, int kh, int kw,
