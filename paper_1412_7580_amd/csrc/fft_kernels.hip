@@ -102,12 +102,10 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
             // (with 16 planes per workgroup: (32,1) 15.0 us on the 27x27 layer, (16,2) 16.1; this: 14.3)
             return run_inv2d<8, 4, 8>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         // the inverse gains from more lanes per line (fewer registers, shorter serial chains):
-        // (16,4) measured 15..25 % faster than (32,2) here
-        case 64:
-            // eight lanes per line when (nearly) all rows are kept (64x64 input gradients: 42 us
-            // against 49), four otherwise (31x31 crops: 89 us against 92)
-            if (conv && 4 * rows > 3 * 64) return run_inv2d<8, 8, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
-            return run_inv2d<16, 4, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
+        // eight per line since their cross-lane twiddles come from the LDS table (31x31 crops of the
+        // 64-basis layer: 85 us with (16,4), 74 with (8,8); 34x34 outputs 29.4 -> 24.8; before the table
+        // (16,4) was ahead whenever at most three quarters of the rows were kept)
+        case 64: return run_inv2d<8, 8, 4>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         case 128: return run_inv2d<16, 8, 1>(in, out, planes, h_out, w_out, conv, scale, accumulate, st, view);
         default: return launch_fft2d_c2r_mixed(in, out, planes, N, h_out, w_out, conv, scale, accumulate, st, view);
     }
