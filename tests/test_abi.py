@@ -83,6 +83,35 @@ def test_layer_basis_on_the_host():
     assert lib.fftconv_workspace_bytes(0, 16, 16, 16, 27, 13, 5, 3) == 3 * 256 * 224 * 2 * 4
 
 
+def test_every_basis_is_accepted_by_name():
+    """The nineteen Fourier bases: each can be named for an image it holds, sizes between them
+    cannot, and the workspace of a named basis is three tensors of its bin count."""
+    import paper_1412_7580_amd as pkg
+    lib = pkg.load_library()
+    bases = (8, 10, 12, 14, 16, 18, 20, 24, 28, 32, 36, 40, 48, 56, 64, 80, 96, 112, 128)
+    tile = {8: 64, 10: 32, 12: 32, 14: 32, 16: 32, 18: 16, 20: 16, 24: 16, 28: 16, 32: 8, 36: 4, 40: 4, 48: 4, 56: 4,
+            64: 4, 80: 1, 96: 1, 112: 1, 128: 1}
+    for n in range(6, 130):
+        got = lib.fftconv_tile_basis(n, n, 3, 3, n)
+        assert got == (n if n in bases else 0), n
+    for n in bases:
+        unit = 32 if tile[n] == 4 else 8
+        bins = -(-(n * (n // 2 + 1)) // unit) * unit
+        planes = 64                                    # a multiple of every tile
+        assert lib.fftconv_tiled_workspace_bytes(0, 8, 8, 8, n, n, 3, 3, n) == 3 * planes * bins * 2 * 4, n
+    # an image takes the smallest basis that holds it
+    import ctypes
+    nr, nc = ctypes.c_int(), ctypes.c_int()
+    untiled = 0
+    for side in range(5, 129):
+        tiled = lib.fftconv_layer_basis(side, side, 5, 5, 0, 0, ctypes.byref(nr), ctypes.byref(nc))
+        assert tiled in (0, 1) and nr.value == nc.value and nr.value in bases
+        if not tiled:                                   # (where tiles are estimated cheaper, any basis may come)
+            untiled += 1
+            assert nr.value == min(b for b in bases if b >= side), side
+    assert untiled >= 50
+
+
 def test_no_oracle_in_product():
     """The product package must not reach into the oracle."""
     pkg_dir = os.path.join(ROOT, "paper_1412_7580_amd")
