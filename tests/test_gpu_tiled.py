@@ -211,6 +211,34 @@ def test_bases_with_a_factor_nine_or_ten(hd, n):
         assert _relerr(_np(g), r) <= TOL
 
 
+@pytest.mark.parametrize("n", [18, 20, 24, 32])
+@pytest.mark.parametrize("tiled", [False, True])
+def test_backward_with_shared_launches(hd, n, tiled):
+    """fft_conv_backward on the bases where both contractions and both inverse transforms share
+    a launch (three launches in all): whole images and windows, with scale and accumulate on
+    the weight gradients."""
+    import torch
+    h, w = (n - 1, n - 3) if not tiled else (2 * n + 3, n + 9)
+    cfg = dict(S=4, f=8, fo=12, h=h, w=w, kh=3, kw=4)
+    x, wt, gy = synth.conv_inputs(seed=350 + n, **cfg)
+    dx, dw, dgy = _dev(x), _dev(wt), _dev(gy)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], h, w, cfg["kh"], cfg["kw"])
+    saved = torch.empty(hd.saved_bytes_tiled(*dims, n) // 4, device="cuda")
+    hd.fft_conv_fprop_save_tiled(dx, dw, n, saved)
+    gw = torch.full((12, 8, 3, 4), 0.25, device="cuda")
+    hd.set_profiling(True)
+    gx, _ = hd.fft_conv_backward_tiled(dgy, saved, cfg["f"], h, w, cfg["kh"], cfg["kw"], n, gw=gw, scale=-0.5,
+                                       accumulate=True)
+    launches = len(hd.last_kernel_ms())
+    hd.set_profiling(False)
+    assert launches == 3
+    assert _relerr(_np(gx), oracle.conv_bprop(gy, wt, h, w)) <= TOL
+    assert _relerr(_np(gw), 0.25 - 0.5 * oracle.conv_accgrad(x, gy)) <= TOL
+    # the same through separate passes
+    gx2 = hd.fft_conv_bprop_tiled(dgy, dw, h, w, n)
+    assert float((gx - gx2).abs().max()) <= 2e-5 * float(gx2.abs().max())
+
+
 def test_autotune_basis(hd):
     """The measured choice is one of the candidate bases, and the outputs left behind are the
     chosen basis's results (checked against the oracle and against the tiled calls)."""
