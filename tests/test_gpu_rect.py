@@ -94,6 +94,25 @@ def test_reuse_and_weights_ahead(hd, h, w, kh, kw):
     assert err <= TOL, f"accumulate {cfg}: {err:.2e}"
 
 
+def test_backward_with_paired_contractions(hd):
+    """On a rectangular basis the two backward contractions still share a launch (the layout is
+    the contraction's own); the inverse transforms stay separate: four launches."""
+    import torch
+    cfg = dict(S=8, f=8, fo=12, h=27, w=13, kh=5, kw=3)
+    x, wt, gy = synth.conv_inputs(seed=77, **cfg)
+    dx, dw, dgy = _dev(x), _dev(wt), _dev(gy)
+    dims = (cfg["S"], cfg["f"], cfg["fo"], 27, 13, 5, 3)
+    saved = torch.empty((hd.saved_bytes(*dims) + 3) // 4, dtype=torch.float32, device="cuda")
+    hd.fft_conv_fprop_save(dx, dw, saved)
+    hd.set_profiling(True)
+    gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], 27, 13, 5, 3)
+    launches = len(hd.last_kernel_ms())
+    hd.set_profiling(False)
+    assert launches == 4
+    assert _relerr(_np(gx), oracle.conv_bprop(gy, wt, 27, 13)) <= TOL
+    assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
+
+
 def test_square_images_keep_the_square_basis(hd):
     assert hd.layer_basis(13, 13, 3, 3) == (14, 14, False)
     assert hd.layer_basis(27, 27, 5, 5) == (28, 28, False)
