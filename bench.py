@@ -575,6 +575,9 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the FFT sweep")
     ap.add_argument("--tiled-only", action="store_true",
                     help="only time the tiled layers of the extra block and print them (for profiling runs)")
+    ap.add_argument("--rect-only", action="store_true",
+                    help="only time the non-square layers of the extra block (rectangular against square "
+                         "basis) and print them (for profiling runs)")
     ap.add_argument("--sweep-only", default=None, metavar="SIZES",
                     help="only run the stand-alone FFT sweep at these comma-separated sizes and print it "
                          "(for profiling runs)")
@@ -604,6 +607,9 @@ def main():
     hd = pkg.Handle(0)
     if args.tiled_only:
         print(json.dumps({"tiled_layers": tiled_layers(hd)}))
+        return
+    if args.rect_only:
+        print(json.dumps({"rectangular_basis": rectangular_layers(hd)}))
         return
     if args.sweep_only:
         sizes = tuple(int(v) for v in args.sweep_only.split(","))
