@@ -988,7 +988,8 @@ static hipError_t run_fwd2d_multi(const FwdOperand *ops, int nops, LaunchCtx st)
 // is staged through LDS (always for the natural layout).
 template <int L, int G, int T>
 static Inv2dParams make_inv2d(const float *in, float *out, long planes, int h_out, int w_out, bool conv, float scale,
-                              bool accumulate, const PlaneView *view, size_t *lds_out, bool *istage_out) {
+                              bool accumulate, const PlaneView *view, size_t *lds_out, bool *istage_out,
+                              bool force_stage = false) {
     constexpr int N = L * G, NH = N / 2;
     Inv2dParams prm;
     prm.tiled = 0; prm.info_off = 0; prm.win_h = prm.win_w = 0; prm.view = PlaneView{};
@@ -1016,7 +1017,7 @@ static Inv2dParams make_inv2d(const float *in, float *out, long planes, int h_ou
     // Stage the block's (contiguous) input through LDS with 16-byte loads: always for the
     // natural layout; for the plane-tiled layout it measured faster except for the small
     // bases (32 or 64 planes per workgroup) when most of the output is kept.
-    const bool istage = !conv || T <= 16 || 2 * h_out <= N;
+    const bool istage = force_stage || !conv || T <= 16 || 2 * h_out <= N;
     if (istage) {
         const size_t c = (size_t)T * N * (NH + 1) * sizeof(float2);
         if (c > lds) lds = c;
@@ -1050,11 +1051,10 @@ static hipError_t run_inv2d(const float *in, float *out, long planes, int h_out,
     return go(fft2d_c2r_kernel<L, G, T, false, true>);
 }
 
-// Two operands in one launch; for (L, G, T) with T <= 16, where the plane-tiled input is always
-// staged, so that both operands run the same kernel variant.
+// Two operands in one launch; both run the variant that stages the plane-tiled input through
+// LDS (the only one for T <= 16).
 template <int L, int G, int T>
 static hipError_t run_inv2d_pair(const InvOperand *ops, LaunchCtx st) {
-    static_assert(T <= 16, "the shared launch needs the staged variant for every operand");
     constexpr int N = L * G, NH = N / 2, BT = T * NH * G;
     InvPairParams m;
     size_t lds = 0;
@@ -1065,8 +1065,7 @@ static hipError_t run_inv2d_pair(const InvOperand *ops, LaunchCtx st) {
         bool istage;
         m.first[o] = blocks;
         m.op[o] = make_inv2d<L, G, T>(ops[o].in, ops[o].out, ops[o].planes, ops[o].h_out, ops[o].w_out, true,
-                                      ops[o].scale, ops[o].accumulate, ops[o].view, &l, &istage);
-        if (!istage) return hipErrorInvalidValue;
+                                      ops[o].scale, ops[o].accumulate, ops[o].view, &l, &istage, true);
         if (l > lds) lds = l;
         any_tiled = any_tiled || m.op[o].tiled;
         blocks += (unsigned)((ops[o].planes + T - 1) / T);

@@ -72,15 +72,21 @@ hipError_t launch_fft2d_c2r_small(const float *in, float *out, long planes, int 
     }
 }
 
-// The bases whose inverse kernel does not depend on the operand (same choices as above).
+// One inverse kernel for both products of the backward pass.  Where the separate launches would
+// pick different kernels by the rows kept (28), the choice for the larger operand serves both.
 // Measured on 64-channel layers, fft_conv_backward in us, two launches -> one: basis 18 44.6 -> 40.4,
-// 20 49.8 -> 44.4, 24 59.5 -> 55.4.  At 28 the two operands want different kernels, and one kernel
-// for both ((7,4), the weight gradients' choice) measured 23.7 us against 13.4 + 6.7.
+// 20 49.8 -> 44.4, 24 59.5 -> 55.4; the 27x27 layer at basis 28: inverse transforms 13.7 + 6.9 -> 16.0 with
+// (28,1) for both (23.7 with (7,4), the weight gradients' own choice); 13x13 with 384 channels at
+// basis 14: 21.5 + 26.1 -> 42.0.
 hipError_t launch_fft2d_c2r_pair_small(const InvOperand *ops, int N, LaunchCtx st) {
     switch (N) {
+        case 10: return run_inv2d_pair<5, 2, 32>(ops, st);
+        case 12: return run_inv2d_pair<3, 4, 32>(ops, st);
+        case 14: return run_inv2d_pair<7, 2, 32>(ops, st);
         case 18: return run_inv2d_pair<9, 2, 16>(ops, st);
         case 20: return run_inv2d_pair<20, 1, 16>(ops, st);
         case 24: return run_inv2d_pair<6, 4, 16>(ops, st);
+        case 28: return run_inv2d_pair<28, 1, 16>(ops, st);
         default: return hipErrorNotSupported;
     }
 }

@@ -112,8 +112,8 @@ hipError_t launch_fft2d_c2r(const float *in, float *out, long planes, int N, int
                             const PlaneView *view = nullptr);
 
 // Two inverse transforms of the plane-tiled layout in ONE launch (the two products of the
-// backward pass).  hipErrorNotSupported for the bases whose inverse kernel depends on the
-// operand (how many rows are kept): the caller then launches them one after the other.
+// backward pass), for the bases up to 32.  hipErrorNotSupported for the others: the caller then
+// launches them one after the other.
 struct InvOperand {
     const float *in;
     float *out;

@@ -211,7 +211,7 @@ def test_bases_with_a_factor_nine_or_ten(hd, n):
         assert _relerr(_np(g), r) <= TOL
 
 
-@pytest.mark.parametrize("n", [18, 20, 24, 32])
+@pytest.mark.parametrize("n", [10, 12, 14, 16, 18, 20, 24, 28, 32])
 @pytest.mark.parametrize("tiled", [False, True])
 def test_backward_with_shared_launches(hd, n, tiled):
     """fft_conv_backward on the bases where both contractions and both inverse transforms share
