@@ -314,6 +314,15 @@ static hipError_t invert(fftconv_ctx *c, const PassPlan &p, const float *CF, flo
 // launch where the basis has one inverse kernel for every operand, else one after the other.
 static hipError_t invert_pair(fftconv_ctx *c, const PassPlan &pb, const float *GXF, float *gx, const PassPlan &pa,
                               const float *GWF, float *gw, float scale, int accumulate) {
+    if (pb.rect && pa.rect && pb.Nr == pa.Nr && pb.Nc == pa.Nc) {
+        const float sb = 1.0f / ((float)pb.Nr * (float)pb.Nc), sa = scale * sb;
+        const InvOperand ops[2] = {{GXF, gx, pb.planesC, pb.hC, pb.wC, sb, false, nullptr},
+                                   {GWF, gw, pa.planesC, pa.hC, pa.wC, sa, accumulate != 0, nullptr}};
+        const int nk = c->nk;
+        const hipError_t e = launch_fft2d_c2r_rect_pair(ops, pb.Nr, pb.Nc, next_ctx(c));
+        if (e != hipErrorNotSupported) return e;
+        c->nk = nk;
+    }
     if (!pb.rect && !pa.rect && pb.N == pa.N) {
         const float sb = 1.0f / ((float)pb.N * (float)pb.N), sa = scale / ((float)pa.N * (float)pa.N);
         const InvOperand ops[2] = {{GXF, gx, pb.planesC, pb.hC, pb.wC, sb, false, pb.viewC ? &pb.vC : nullptr},

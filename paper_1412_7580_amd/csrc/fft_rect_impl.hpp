@@ -186,14 +186,14 @@ struct RectInvParams {
 };
 
 template <int LH, int GH, int LW, int GW>
-__global__ void __launch_bounds__((RectShape<LH, GH, LW, GW>::BT)) fft2d_c2r_rect_kernel(RectInvParams prm) {
+__device__ __forceinline__ void fft2d_c2r_rect_body(const RectInvParams &prm, unsigned block) {
     typedef RectShape<LH, GH, LW, GW> S;
     constexpr int NC = S::NC, CH = S::CH, NB = S::NB, T = S::T, BT = S::BT, MRS = S::MRS;
     extern __shared__ float smem[];
     float2 *mid = reinterpret_cast<float2 *>(smem);
 
     const int tid = threadIdx.x;
-    const long p0 = (long)blockIdx.x * T;
+    const long p0 = (long)block * T;
     const int h_out = prm.h_out, w_out = prm.w_out;
     float *sout = smem + misalign4(prm.out + p0 * (long)h_out * w_out);
     const long left = prm.planes - p0;
@@ -271,6 +271,25 @@ __global__ void __launch_bounds__((RectShape<LH, GH, LW, GW>::BT)) fft2d_c2r_rec
                        prm.accumulate != 0);
 }
 
+template <int LH, int GH, int LW, int GW>
+__global__ void __launch_bounds__((RectShape<LH, GH, LW, GW>::BT)) fft2d_c2r_rect_kernel(RectInvParams prm) {
+    fft2d_c2r_rect_body<LH, GH, LW, GW>(prm, blockIdx.x);
+}
+
+// The inverse transforms of the two products of the backward pass in one launch: the blocks of
+// operand o are [first[o], first[o+1]).
+struct RectInvPair {
+    RectInvParams op[2];
+    unsigned first[3];
+};
+
+template <int LH, int GH, int LW, int GW>
+__global__ void __launch_bounds__((RectShape<LH, GH, LW, GW>::BT)) fft2d_c2r_rect_pair_kernel(RectInvPair m) {
+    const unsigned b = blockIdx.x;
+    const int o = b >= m.first[1];
+    fft2d_c2r_rect_body<LH, GH, LW, GW>(m.op[o], b - m.first[o]);
+}
+
 // Tile and bin count of the plane-tiled layout of a rectangular basis.
 inline int rect_tile_log2(int nr, int nc) { return (nr >= 18 || nc >= 18) ? 4 : 5; }
 inline int rect_layout_bins(int nr, int nc) { return (nr * (nc / 2 + 1) + 7) / 8 * 8; }
@@ -322,8 +341,8 @@ static hipError_t run_fwd_rect(const FwdOperand *ops, int nops, LaunchCtx st) {
 }
 
 template <int LH, int GH, int LW, int GW>
-static hipError_t run_inv_rect(const float *in, float *out, long planes, int h_out, int w_out, float scale,
-                               bool accumulate, LaunchCtx st) {
+static RectInvParams make_inv_rect(const float *in, float *out, long planes, int h_out, int w_out, float scale,
+                                   bool accumulate, size_t *lds) {
     typedef RectShape<LH, GH, LW, GW> S;
     RectInvParams prm;
     prm.in = in; prm.out = out; prm.planes = planes; prm.h_out = h_out; prm.w_out = w_out;
@@ -332,10 +351,41 @@ static hipError_t run_inv_rect(const float *in, float *out, long planes, int h_o
     prm.lay.bins = rect_layout_bins(S::NR, S::NC);
     prm.scale = scale; prm.accumulate = accumulate ? 1 : 0;
     const size_t a = (size_t)S::T * prm.MPS * sizeof(float2), b = ((size_t)S::T * h_out * w_out + 3) * sizeof(float);
-    const size_t lds = a > b ? a : b;
+    *lds = a > b ? a : b;
+    return prm;
+}
+
+template <int LH, int GH, int LW, int GW>
+static hipError_t run_inv_rect(const float *in, float *out, long planes, int h_out, int w_out, float scale,
+                               bool accumulate, LaunchCtx st) {
+    typedef RectShape<LH, GH, LW, GW> S;
+    size_t lds;
+    const RectInvParams prm = make_inv_rect<LH, GH, LW, GW>(in, out, planes, h_out, w_out, scale, accumulate, &lds);
     auto k = fft2d_c2r_rect_kernel<LH, GH, LW, GW>;
     if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
     launch_kernel(k, dim3((unsigned)((planes + S::T - 1) / S::T)), dim3(S::BT), lds, st, prm);
+    return hipGetLastError();
+}
+
+template <int LH, int GH, int LW, int GW>
+static hipError_t run_inv_rect_pair(const InvOperand *ops, LaunchCtx st) {
+    typedef RectShape<LH, GH, LW, GW> S;
+    RectInvPair m;
+    size_t lds = 0;
+    unsigned blocks = 0;
+    for (int o = 0; o < 2; ++o) {
+        size_t l;
+        m.first[o] = blocks;
+        m.op[o] = make_inv_rect<LH, GH, LW, GW>(ops[o].in, ops[o].out, ops[o].planes, ops[o].h_out, ops[o].w_out,
+                                                ops[o].scale, ops[o].accumulate, &l);
+        if (l > lds) lds = l;
+        blocks += (unsigned)((ops[o].planes + S::T - 1) / S::T);
+    }
+    m.first[2] = blocks;
+    if (blocks == 0) return hipSuccess;
+    auto k = fft2d_c2r_rect_pair_kernel<LH, GH, LW, GW>;
+    if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
+    launch_kernel(k, dim3(blocks), dim3(S::BT), lds, st, m);
     return hipGetLastError();
 }
 

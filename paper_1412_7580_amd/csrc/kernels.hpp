@@ -124,6 +124,8 @@ struct InvOperand {
     const PlaneView *view = nullptr;
 };
 hipError_t launch_fft2d_c2r_pair(const InvOperand *ops, int N, LaunchCtx st);
+// The same on a rectangular basis (whole planes only).
+hipError_t launch_fft2d_c2r_rect_pair(const InvOperand *ops, int nr, int nc, LaunchCtx st);
 
 // One-launch fprop of a small layer (basis N <= 16, f and f' within one plane tile): one
 // workgroup per sample; wf is the weight transform in the layout of basis N.

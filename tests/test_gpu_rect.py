@@ -94,9 +94,9 @@ def test_reuse_and_weights_ahead(hd, h, w, kh, kw):
     assert err <= TOL, f"accumulate {cfg}: {err:.2e}"
 
 
-def test_backward_with_paired_contractions(hd):
-    """On a rectangular basis the two backward contractions still share a launch (the layout is
-    the contraction's own); the inverse transforms stay separate: four launches."""
+def test_backward_with_shared_launches(hd):
+    """On a rectangular basis the two backward contractions share a launch (the layout is the
+    contraction's own) and so do the two inverse transforms: three launches."""
     import torch
     cfg = dict(S=8, f=8, fo=12, h=27, w=13, kh=5, kw=3)
     x, wt, gy = synth.conv_inputs(seed=77, **cfg)
@@ -108,9 +108,14 @@ def test_backward_with_paired_contractions(hd):
     gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], 27, 13, 5, 3)
     launches = len(hd.last_kernel_ms())
     hd.set_profiling(False)
-    assert launches == 4
+    assert launches == 3
     assert _relerr(_np(gx), oracle.conv_bprop(gy, wt, 27, 13)) <= TOL
     assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
+    # scale and accumulate go to the weight gradients only
+    gw0 = torch.full_like(gw, 2.0)
+    gx2, _ = hd.fft_conv_backward(dgy, saved, cfg["f"], 27, 13, 5, 3, gw=gw0, scale=0.5, accumulate=True)
+    assert torch.equal(gx2, gx)
+    assert _relerr(_np(gw0), 2.0 + 0.5 * oracle.conv_accgrad(x, gy)) <= TOL
 
 
 def test_square_images_keep_the_square_basis(hd):
