@@ -25,8 +25,10 @@ def _dev(a):
 
 
 @pytest.mark.parametrize("cfg", [dict(S=16, f=16, fo=16, h=13, w=13, kh=3, kw=3),      # smallest benchmark layer
-                                 dict(S=2, f=4, fo=4, h=70, w=70, kh=5, kw=5)],        # a layer the library tiles
-                         ids=["13x13", "70x70_tiled"])
+                                 dict(S=2, f=4, fo=4, h=70, w=70, kh=5, kw=5),         # a layer the library tiles
+                                 dict(S=8, f=8, fo=12, h=27, w=13, kh=5, kw=3),        # rectangular basis 28 x 14
+                                 dict(S=8, f=8, fo=8, h=27, w=27, kh=5, kw=5)],        # basis 28, shared launches
+                         ids=["13x13", "70x70_tiled", "27x13_rect", "27x27"])
 def test_graph_replay_equals_eager(hd, lib, cfg):
     import torch
     x, w, gy = synth.conv_inputs(seed=600, **cfg)
