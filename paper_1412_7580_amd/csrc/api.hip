@@ -268,12 +268,24 @@ static hipError_t transform(const PassPlan &p, const float *in, float *out, long
     return launch_fft2d_r2c(in, out, planes, h, w, p.N, true, lc, view);
 }
 
-// Forward transforms of both operands of a pass.  For the bases up to 32 they share one launch
-// (two short kernels would queue behind each other's ramp-up and tail; measured 14 us of 204
-// per step on the 32-basis layer).  For basis 64 and up the transform is ALU-bound and a shared
-// launch would give every block the larger operand's LDS footprint, costing occupancy
-// (measured slower), so the operands are launched one after the other.  Profiling then reports
-// the pair as one entry only in the shared case, so that case also pairs the events.
+// Whether two forward transforms of basis N (layout tile 2^tsh planes) go out as one launch.
+// Two short kernels would queue behind each other's ramp-up and tail (measured 14 us of 204 per
+// step on the 32-basis layer; 28 -> 21 us on a 64-channel 36x36 layer, 38 -> 32 at 45x45 on basis 48,
+// 63 -> 48 for the windows and weights of a 160x160 layer tiled at basis 64), so they share a
+// launch up to basis 56.  At 64 every block of a shared launch gets the LDS footprint of the
+// operand with more rows, which costs the other one occupancy: shared only when that other
+// operand is the smaller one (the 31x31 weights of the 64-basis benchmark layer, 16384 planes
+// against 4096 of x: 129 us apart, 143 shared).  From 80 on (one plane per workgroup) apart.
+static bool share_forward(int N, int tsh, int hA, long planesA, int hB, long planesB) {
+    if (tsh >= 3 || N <= 56) return true;
+    if (N > 64) return false;
+    const int lo = hA < hB ? hA : hB, hi = hA < hB ? hB : hA;
+    if (4 * lo >= 3 * hi) return true;        // about the same footprint (gy and the weights there: 118 -> 112 us)
+    return hA < hB ? planesA <= planesB : planesB <= planesA;
+}
+
+// Forward transforms of both operands of a pass, as one launch where share_forward says so.
+// Profiling reports the pair as one entry in both cases (the separate launches pair the events).
 static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a, float *AF,
                                const float *b, float *BF) {
     const PlaneView *va = p.viewA ? &p.vA : nullptr, *vb = p.viewB ? &p.vB : nullptr;
@@ -281,7 +293,7 @@ static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, nullptr}, {b, BF, p.planesB, p.hB, p.wB, nullptr}};
         return launch_fft2d_r2c_rect(ops, 2, p.Nr, p.Nc, next_ctx(c));
     }
-    if (p.lay.tsh >= 3) {
+    if (share_forward(p.N, p.lay.tsh, p.hA, p.planesA, p.hB, p.planesB)) {
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, va}, {b, BF, p.planesB, p.hB, p.wB, vb}};
         return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c));
     }
@@ -732,7 +744,7 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
         if ((e = transform(pb, gy, GYF, pb.planesA, pb.hA, pb.wA, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
     } else {
         // gy cut twice: overlapping windows for bprop, disjoint tiles for accGrad
-        if (gx && gw && pb.lay.tsh >= 3) {   // small bases: both in one launch, as for the two operands of a pass
+        if (gx && gw && share_forward(pb.N, pb.lay.tsh, pb.hA, pb.planesA, pa.hA, pa.planesA)) {   // as for the two operands of a pass
             FwdOperand ops[2] = {{gy, GYF, pb.planesA, pb.hA, pb.wA, &pb.vA}, {gy, GYFa, pa.planesA, pa.hA, pa.wA, &pa.vA}};
             if ((e = launch_fft2d_r2c_multi(ops, 2, pb.N, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
         } else {
