@@ -41,7 +41,8 @@ typedef enum {
     FFTCONV_INVALID_ARG = 1,         /* null pointer, non-positive size, kernel larger than input, n_in > n ... */
     FFTCONV_UNSUPPORTED = 2,         /* transform size that is not one of the bases; kernel larger than 128 */
     FFTCONV_WORKSPACE_TOO_SMALL = 3, /* caller-supplied workspace smaller than fftconv_workspace_bytes() */
-    FFTCONV_HIP_ERROR = 4            /* allocation or launch failure reported by the HIP runtime */
+    FFTCONV_HIP_ERROR = 4,           /* allocation or launch failure reported by the HIP runtime */
+    FFTCONV_STATIC_SCRATCH_EXCEEDED = 5 /* fft_conv_fprop_static: the layer needs more than fftconv_static_scratch_bytes() */
 } fftconv_status;
 
 enum { FFTCONV_FPROP = 0, FFTCONV_BPROP = 1, FFTCONV_ACCGRAD = 2 };
@@ -87,6 +88,23 @@ size_t fftconv_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int
 int fft_conv_fprop(fftconv_handle hd, const float *x, const float *wt, float *y,
                    int S, int f, int fo, int h, int w, int kh, int kw,
                    void *ws, size_t ws_bytes);
+
+/*
+ * fprop for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, result and kernels as
+ * fft_conv_fprop, but the three frequency-domain tensors live in an array that is part of the
+ * library's device code (32 MiB, fftconv_static_scratch_bytes(); every GPU the library runs on
+ * holds one copy until the process ends) instead of a workspace: the call makes no allocation
+ * of any kind.  A layer whose fprop needs more (fftconv_workspace_bytes(FFTCONV_FPROP, ...) above
+ * that size) gives FFTCONV_STATIC_SCRATCH_EXCEEDED and nothing is launched; other errors as for
+ * fft_conv_fprop.  All calls on one GPU, from every handle, share that GPU's array: two such
+ * calls that overlap in time on one GPU (different streams or handles) race and give wrong
+ * results; calls that follow each other on one stream are fine, and nothing of the array has
+ * to be cleared between them (every element a call reads, it has written before).
+ */
+size_t fftconv_static_scratch_bytes(void);
+int fft_conv_fprop_static(fftconv_handle hd, const float *x, const float *wt, float *y,
+                          int S, int f, int fo, int h, int w, int kh, int kw);
 
 /* bprop: dL/dx(s,i) = sum_j dL/dy(s,j) * w(j,i)  -- full convolution, reduces over fo.
  * gy[S,fo,oh,ow], wt[fo,f,kh,kw] -> gx[S,f,h,w]. */

@@ -29,6 +29,7 @@ SYMBOLS = [
     "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
     "fftconv_saved_bytes_padded", "fftconv_backward_workspace_bytes_padded",
     "fft_conv_fprop_save_padded", "fft_conv_backward_padded",
+    "fftconv_static_scratch_bytes", "fft_conv_fprop_static",
 ]
 
 
@@ -104,6 +105,9 @@ def load_library():
     lib.fftconv_backward_workspace_bytes_padded.restype = sz
     lib.fft_conv_fprop_save_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz, vp, sz]
     lib.fft_conv_backward_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [f, i, vp, sz, vp, sz]
+    lib.fftconv_static_scratch_bytes.argtypes = []
+    lib.fftconv_static_scratch_bytes.restype = sz
+    lib.fft_conv_fprop_static.argtypes = [vp, vp, vp, vp] + [i] * 7
     _lib = lib
     return lib
 
@@ -185,6 +189,21 @@ class Handle:
         self._sync_stream()
         _check(self._lib.fft_conv_fprop(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
                                         S, f, fo, h, w, kh, kw, *self._ws(ws)), "fft_conv_fprop")
+        return y
+
+    def static_scratch_bytes(self) -> int:
+        return int(self._lib.fftconv_static_scratch_bytes())
+
+    def fft_conv_fprop_static(self, x, wt, y):
+        """fft_conv_fprop on the library's static scratch array: no allocation, here or in the
+        library (so y is required)."""
+        S, f, h, w = x.shape
+        fo, f2, kh, kw = wt.shape
+        if f2 != f:
+            raise FFTConvError("x and wt disagree on the number of input planes")
+        self._sync_stream()
+        _check(self._lib.fft_conv_fprop_static(self._h, _dev_f32(x, "x"), _dev_f32(wt, "wt"), _dev_f32(y, "y"),
+                                               S, f, fo, h, w, kh, kw), "fft_conv_fprop_static")
         return y
 
     def fft_conv_fprop_save(self, x, wt, saved, y=None, ws=None):

@@ -11,17 +11,47 @@
 #include "../../include/fftconv.h"
 #include "kernels.hpp"
 
+#include <mutex>
 #include <new>
 
 using namespace fc;
 
 constexpr int kMaxKernels = 8;
 
+// Scratch for fft_conv_fprop_static, the entry point for callers that cannot allocate: the three
+// frequency-domain tensors of one fprop live in this array instead of a workspace.  Every GPU
+// the library runs on holds its own copy, at its own address, until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the address that kernels and
+// copies take is the one looked up per device in static_scratch_for().
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char fftconv_static_scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *g_static_scratch[kMaxDevices];   // device address of the array on each GPU, once looked up
+static std::mutex g_static_scratch_mutex;
+
+// Device address of the static scratch array on `device`, which must be the current device.
+static hipError_t static_scratch_for(int device, void **out) {
+    *out = nullptr;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch[device]) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(fftconv_static_scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_static_scratch[device] = ptr;
+    }
+    *out = g_static_scratch[device];
+    return hipSuccess;
+}
+
 struct fftconv_ctx {
     int device;
     hipStream_t stream;
     void *ws;
     size_t ws_bytes;
+    void *static_scratch;   // this device's copy of fftconv_static_scratch (device address)
     int profiling;
     hipEvent_t ev[2 * 8];   // start/stop pair per kernel of the last call
     int nk;                 // kernels of the last call that carry events
@@ -416,6 +446,9 @@ int fftconv_create(fftconv_handle *out, int device) {
     if (!c) return FFTCONV_HIP_ERROR;
     c->device = device; c->stream = nullptr; c->ws = nullptr; c->ws_bytes = 0;
     c->profiling = 0; c->nk = 0; c->last_hip_error[0] = 0;
+    c->static_scratch = nullptr;
+    // this device's copy of the static scratch array (the device is current here)
+    if (static_scratch_for(device, &c->static_scratch) != hipSuccess) { delete c; return FFTCONV_HIP_ERROR; }
     for (int i = 0; i < 2 * kMaxKernels; ++i)
         if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return FFTCONV_HIP_ERROR; }
     *out = c;
@@ -443,6 +476,7 @@ const char *fftconv_status_string(int status) {
         case FFTCONV_UNSUPPORTED: return "unsupported transform size or layer shape for this entry point";
         case FFTCONV_WORKSPACE_TOO_SMALL: return "workspace too small";
         case FFTCONV_HIP_ERROR: return "HIP runtime error";
+        case FFTCONV_STATIC_SCRATCH_EXCEEDED: return "layer needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
@@ -456,6 +490,23 @@ size_t fftconv_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int
 int fft_conv_fprop(fftconv_handle hd, const float *x, const float *wt, float *y,
                    int S, int f, int fo, int h, int w, int kh, int kw, void *ws, size_t ws_bytes) {
     return run_pass(hd, FFTCONV_FPROP, x, wt, y, S, f, fo, h, w, kh, kw, 1.0f, 0, ws, ws_bytes);
+}
+
+size_t fftconv_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int fft_conv_fprop_static(fftconv_handle hd, const float *x, const float *wt, float *y,
+                          int S, int f, int fo, int h, int w, int kh, int kw) {
+    if (!hd || !x || !wt || !y) return FFTCONV_INVALID_ARG;
+    PassPlan p;
+    const int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
+    if (rc != FFTCONV_OK) return rc;
+    if (p.total > kStaticScratchBytes) return FFTCONV_STATIC_SCRATCH_EXCEEDED;
+    if (!hd->static_scratch) return FFTCONV_HIP_ERROR;
+    // the same pipeline as fft_conv_fprop with the device's static array as the workspace: every
+    // frequency-domain element that is read was written by this call's transforms first, so
+    // nothing of the array needs clearing between calls
+    return run_pass(hd, FFTCONV_FPROP, x, wt, y, S, f, fo, h, w, kh, kw, 1.0f, 0, hd->static_scratch,
+                    kStaticScratchBytes);
 }
 
 int fft_conv_bprop(fftconv_handle hd, const float *gy, const float *wt, float *gx,

@@ -29,6 +29,8 @@ def test_host_only_calls():
     lib = pkg.load_library()
     assert lib.fftconv_status_string(0) == b"ok"
     assert b"workspace" in lib.fftconv_status_string(3)
+    assert b"static" in lib.fftconv_status_string(5)
+    assert lib.fftconv_static_scratch_bytes() == 32 << 20
     # fprop of the smallest configuration: 13x13 images take basis 14, so three frequency
     # tensors of 256 planes and 14 * 8 = 112 bins
     need = lib.fftconv_workspace_bytes(0, 16, 16, 16, 13, 13, 3, 3)
