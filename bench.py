@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the frequency-domain convolution hot path on one MI355X.
 
-One step = fprop + bprop + accGrad of the headline layer (S=128, f=f'=64, 27x27 input,
-5x5 kernel, 32x32 Fourier basis) as the two calls fft_conv_fprop_save + fft_conv_backward:
-six kernel launches (x, w and gy are transformed once each, the two backward contractions
-share a launch and so do the inverse transforms of the two gradients).  Inputs are seeded synthetic fp32 tensors
-already resident in device memory.  `extra` holds the same step as three independent passes,
-on the library's own Fourier basis, the other configurations, tiled layers, the FFT sweep.
+One step = fprop + bprop + accGrad of the headline layer, the largest single-GPU configuration
+(S=32, f=f'=128, 64x64 input, 31x31 kernel, 64x64 Fourier basis), as the two calls
+fft_conv_fprop_save + fft_conv_backward (x, w and gy are transformed once each).  Inputs are
+seeded synthetic fp32 tensors already resident in device memory.  Every step is timed by its own
+pair of HIP events; `ms_per_step` is the median.
 
-Prints ONE JSON line: effective TFLOP/s (direct-convolution FLOP count over measured time),
-the roofline of the dominant kernel (durations from HIP events recorded by the library on its
-own stream around each stage), and the fp64 CPU oracle timed on a bounded sample.
+Prints ONE JSON line: effective TFLOP/s (direct-convolution FLOP count over measured time); a
+`roofline` object for the dominant kernel (durations from HIP events that the library attaches
+to each dispatch on its own stream) that also holds every kernel of the step (`stages`), the
+other three convolution configurations (`other_configs`) and the stand-alone FFT sweep
+(`fft_sweep`: GB/s and fraction of 8 TB/s at the ten points of the fifth configuration); and
+the fp64 CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -132,68 +134,6 @@ def add_saved(hd, t, cfg, basis=None):
     t["saved"] = torch.empty(n // 4, device="cuda", dtype=torch.float32)
 
 
-def time_steps(hd, t, cfg, passes, steps, warmup, reuse=False, basis=None):
-    import torch
-    for _ in range(warmup):
-        run_step(hd, t, cfg, passes, reuse, basis)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        run_step(hd, t, cfg, passes, reuse, basis)
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
-
-
-def profile_stages(hd, t, cfg, passes, steps, basis=None):
-    """Average execution time (ms) of each kernel of each pass over `steps` repetitions, from the
-    start/stop events the library attaches to every dispatch on its stream.
-    Returns {pass: [fft, contraction, ifft]}."""
-    import torch
-    hd.set_profiling(True)
-    acc = {p: [0.0] * 3 for p in passes}
-    for _ in range(steps):
-        for p in passes:
-            run_step(hd, t, cfg, (p,), False, basis)
-            ms = hd.last_kernel_ms()
-            for i in range(3):
-                acc[p][i] += ms[i]
-    hd.set_profiling(False)
-    torch.cuda.synchronize()
-    return {p: [v / steps for v in acc[p]] for p in passes}
-
-
-FPROP_KERNELS = ("fprop.fft", "fprop.contraction", "fprop.ifft")
-# fft_conv_backward: five launches, or four when both contractions go out as one launch
-# (and three when the two inverse transforms share a launch as well)
-BACKWARD_KERNELS = {5: ("backward.fft", "bprop.contraction", "bprop.ifft", "accgrad.contraction", "accgrad.ifft"),
-                    4: ("backward.fft", "backward.contraction", "bprop.ifft", "accgrad.ifft"),
-                    3: ("backward.fft", "backward.contraction", "backward.ifft")}
-
-
-def profile_reuse_step(hd, t, cfg, steps, basis=None):
-    """Same for the two-call step with transform reuse: {kernel name: ms}."""
-    import torch
-    hd.set_profiling(True)
-    acc = {}
-    dims = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
-    for _ in range(steps):
-        if basis is None:
-            hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
-        else:
-            hd.fft_conv_fprop_save_tiled(t["x"], t["w"], basis, t["saved"], y=t["y"])
-        a = hd.last_kernel_ms()
-        if basis is None:
-            hd.fft_conv_backward(t["gy"], t["saved"], *dims, gx=t["gx"], gw=t["gw"])
-        else:
-            hd.fft_conv_backward_tiled(t["gy"], t["saved"], *dims, basis, gx=t["gx"], gw=t["gw"])
-        b = hd.last_kernel_ms()
-        for k, v in zip(FPROP_KERNELS + BACKWARD_KERNELS[len(b)], a + b):
-            acc[k] = acc.get(k, 0.0) + v
-    hd.set_profiling(False)
-    torch.cuda.synchronize()
-    return {k: v / steps for k, v in acc.items()}
-
-
 def cpu_baseline(cfg, host_inputs, budget_s=12.0):
     """fp64 oracle (as it stands, OpenMP over output planes) on the same inputs: whole passes
     when they are cheap, repeated until about budget_s of CPU work; otherwise a seeded sample
@@ -235,41 +175,6 @@ def cpu_baseline(cfg, host_inputs, budget_s=12.0):
         parts.append(f"{name}: {k}/{nplanes} planes x{reps} in {dt:.2f}s")
     return {"value": round(done_flops / spent / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle", "sample": "fp64 direct convolution oracle; " + "; ".join(parts)}
-
-
-def fft_sweep(hd, max_bytes=1 << 28, reps=3, sizes=None, sizes_1d_only=(256,)):
-    """Stand-alone FFT sweep: R2C then C2R of signals of n - 3 samples, input sized to 256 MiB,
-    algorithmic GB/s.  Default sizes: those of the benchmark definition (8 ... 128) plus n = 256
-    in 1-D, one size beyond it."""
-    import torch
-    from paper_1412_7580_amd import synth
-    sizes = synth.FFT_SWEEP_SIZES if sizes is None else sizes
-    out = {}
-    for dim in (1, 2):
-        for n in tuple(sizes) + (tuple(sizes_1d_only) if dim == 1 else ()):
-            ni = n - 3
-            B = max_bytes // (4 * ni ** dim)
-            shape = (B, ni) if dim == 1 else (B, ni, ni)
-            x = torch.randn(shape, device="cuda", dtype=torch.float32)
-            nbins = (n // 2 + 1) * (1 if dim == 1 else n)
-            X = torch.empty((B, n // 2 + 1, 2) if dim == 1 else (B, n, n // 2 + 1, 2), device="cuda")
-            y = torch.empty_like(x)
-            fwd = (lambda: hd.fft_r2c_1d(x, n, out=X)) if dim == 1 else (lambda: hd.fft_r2c_2d(x, n, out=X))
-            inv = (lambda: hd.fft_c2r_1d(X, n, ni, out=y)) if dim == 1 else (lambda: hd.fft_c2r_2d(X, n, ni, ni, out=y))
-            res = {}
-            for name, fn in (("r2c", fwd), ("c2r", inv)):
-                fn(); torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                for _ in range(reps):
-                    fn()
-                e1.record(); torch.cuda.synchronize()
-                ms = e0.elapsed_time(e1) / reps
-                byts = B * (4 * ni ** dim + 8 * nbins)
-                res[name] = {"ms": round(ms, 4), "GBps": round(byts / ms / 1e6, 1)}
-            out[f"{dim}d_n{n}"] = res
-            del x, X, y
-    return out
 
 
 def graph_replay_c1(hd, reps=200):
@@ -560,19 +465,220 @@ def rectangular_layers(hd, reps=10):
     return out
 
 
+# ------------------------------------------------------------------ timing and rooflines
+def time_steps_events(hd, t, cfg, passes, steps, warmup, reuse=False, basis=None):
+    """`warmup` untimed steps, then `steps` steps, each between its own pair of HIP events on the
+    stream the library launches on (torch's current stream, which the handle follows), the whole
+    region bracketed by synchronize().  Returns (median ms per step over the event pairs, mean ms
+    per step by the host clock around the region, [min, max] of the event times)."""
+    import statistics
+    import torch
+    for _ in range(warmup):
+        run_step(hd, t, cfg, passes, reuse, basis)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        run_step(hd, t, cfg, passes, reuse, basis)
+        b.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps * 1e3
+    ms = [a.elapsed_time(b) for a, b in ev]
+    return statistics.median(ms), wall, [min(ms), max(ms)]
+
+
+def profile_kernels(hd, t, cfg, passes, steps, reuse=False, basis=None):
+    """Average execution time (ms) of every kernel of one step over `steps` repetitions, from the
+    start/stop events the library attaches to each dispatch on its own stream; kernels are named
+    by the call they belong to and the label the library reports for them.
+    Returns {name: ms} in launch order."""
+    import torch
+    hd.set_profiling(True)
+    acc = {}
+    dims = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
+
+    def collect(prefix, backward=False):
+        ms, labels = hd.last_kernel_ms(), hd.last_kernel_labels()
+        seen = {}
+        for v, lab in zip(ms, labels):
+            if backward:
+                # fft_conv_backward: gy's transform, then the products of bprop and accGrad, in that
+                # order when they are separate launches
+                n = seen.get(lab, 0); seen[lab] = n + 1
+                if lab.startswith("fft"):
+                    name = "backward.fft" if lab == "fft.a" else "backward." + lab.replace(".", "_")
+                elif lab.endswith(".pair"):
+                    name = "backward." + lab.split(".")[0]
+                else:
+                    name = ("bprop." if n == 0 else "accgrad.") + lab
+            else:
+                name = prefix + "." + {"fft.ab": "fft", "fft.a": "fft_a", "fft.b": "fft_b"}.get(lab, lab)
+            acc[name] = acc.get(name, 0.0) + v
+
+    for _ in range(steps):
+        if reuse and len(passes) == 3:
+            if basis is None:
+                hd.fft_conv_fprop_save(t["x"], t["w"], t["saved"], y=t["y"])
+            else:
+                hd.fft_conv_fprop_save_tiled(t["x"], t["w"], basis, t["saved"], y=t["y"])
+            collect("fprop")
+            if basis is None:
+                hd.fft_conv_backward(t["gy"], t["saved"], *dims, gx=t["gx"], gw=t["gw"])
+            else:
+                hd.fft_conv_backward_tiled(t["gy"], t["saved"], *dims, basis, gx=t["gx"], gw=t["gw"])
+            collect("backward", backward=True)
+        else:
+            for p in passes:
+                run_step(hd, t, cfg, (p,), False, basis)
+                collect(p)
+    hd.set_profiling(False)
+    torch.cuda.synchronize()
+    return {k: v / steps for k, v in acc.items()}
+
+
+def kernel_model(cfg, name):
+    """Algorithmic bytes and executed flops of the kernel called `name` (see profile_kernels)."""
+    p, st = name.split(".")
+    if p == "backward":
+        mb, ma = stage_model(cfg, "bprop"), stage_model(cfg, "accgrad")
+        if st == "fft":
+            return mb["fft_a"]                      # gy, transformed once for both passes
+        if st == "contraction":
+            # GYF is an operand of both problems: counted once (the launch can read it once)
+            gyf = 8 * cfg["N"] * (cfg["N"] // 2 + 1) * cfg["S"] * cfg["fo"]
+            return {"bytes": mb["contraction"]["bytes"] + ma["contraction"]["bytes"] - gyf,
+                    "flops": mb["contraction"]["flops"] + ma["contraction"]["flops"]}
+        if st == "ifft":
+            return {"bytes": mb["ifft"]["bytes"] + ma["ifft"]["bytes"]}
+        return mb["fft_a"]                          # tiled layers: gy cut a second time
+    return stage_model(cfg, p)[st]
+
+
+def roofline_entry(ms, model):
+    """Roofline of one kernel: the bound is the roofline that allows the least (HBM for the
+    transforms; for a contraction whichever of executed flops / 157.3 TFLOP/s and algorithmic
+    bytes / 8 TB/s takes longer); frac = that least time over the measured time."""
+    ent = {"ms": round(ms, 5), "GBps": round(model["bytes"] / ms / 1e6, 1),
+           "frac_hbm": round(model["bytes"] / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    t_hbm = model["bytes"] / (HBM_PEAK_GBS * 1e9)
+    bound = "hbm"
+    if "flops" in model:
+        ent["TFLOPs"] = round(model["flops"] / ms / 1e9, 2)
+        ent["frac_mfma"] = round(model["flops"] / ms / 1e9 / MFMA_FP32_PEAK_TFLOPS, 4)
+        if model["flops"] / (MFMA_FP32_PEAK_TFLOPS * 1e12) > t_hbm:
+            bound = "mfma"
+    ent["bound"] = bound
+    ent["frac"] = ent["frac_mfma"] if bound == "mfma" else ent["frac_hbm"]
+    return ent
+
+
+KERNEL_FUNCTIONS = {   # which kernel function runs a stage (for matching rocprofv3 kernel stats)
+    "fft": "fft2d_r2c_multi_kernel (both operands in one launch)", "fft_a": "fft2d_r2c_kernel",
+    "fft_b": "fft2d_r2c_kernel", "ifft": "fft2d_c2r_kernel / fft2d_c2r_pair_kernel",
+    "contraction": "cgemm_bins_kernel / cgemm_tail_kernel / cgemm_pair_kernel / cgemm_bingroup_kernel",
+}
+
+# HBM bytes per launch of the headline's kernels from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (KiB per dispatch, scaled by what the same counters read for a plain 256 MiB copy).  Quoted
+# constants, not measured by the run that prints them: the profile named here holds the runs.
+QUOTED_TRAFFIC = {
+    "C2": ("profiles/c2_hbm_traffic.md", MEASURED_TRAFFIC_BYTES["C2"]),
+}
+
+
+def measure_config(hd, name, steps, warmup, prof_steps, separate=False, library_basis_=False):
+    """Step time (median of per-step event pairs) and per-kernel rooflines of configuration `name`
+    on the Fourier basis it names.  Returns (entry dict, cfg, host inputs)."""
+    import torch
+    from paper_1412_7580_amd import synth
+    cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k != "passes"}
+    passes = synth.CONV_CONFIGS[name]["passes"]
+    t, host = device_tensors(cfg, synth.CONV_SEEDS[name])
+    basis = None if library_basis_ else cfg["N"]
+    if library_basis_:
+        cfg["N"] = library_basis(cfg)
+    reuse = (len(passes) == 3) and not separate
+    if reuse:
+        add_saved(hd, t, cfg, basis)
+    med, wall, rng = time_steps_events(hd, t, cfg, passes, steps, warmup, reuse, basis)
+    flops = direct_flops(cfg) * len(passes)
+    km = profile_kernels(hd, t, cfg, passes, prof_steps, reuse, basis)
+    stages = {k: roofline_entry(ms, kernel_model(cfg, k)) for k, ms in km.items()}
+    dom = max(stages, key=lambda k: stages[k]["ms"])
+    ent = {
+        "workload": f"{name}: S={cfg['S']} f={cfg['f']} f'={cfg['fo']} input {cfg['h']}x{cfg['w']} "
+                    f"kernel {cfg['kh']}x{cfg['kw']} FFT {cfg['N']}x{cfg['N']}, passes " + "+".join(passes),
+        "calls": ("fft_conv_fprop_save + fft_conv_backward (x, w, gy transformed once each)" if reuse
+                  else "independent passes: " + ", ".join("fft_conv_" + p for p in passes)),
+        "ms_per_step": round(med, 5), "ms_per_step_wall_mean": round(wall, 5),
+        "ms_per_step_min_max": [round(v, 5) for v in rng], "steps": steps,
+        "effective_TFLOPs": round(flops / med / 1e9, 2),
+        "launches_per_step": len(km), "kernel_ms_sum": round(sum(km.values()), 5),
+        "dominant": dom, "stages": stages,
+    }
+    del t
+    torch.cuda.empty_cache()
+    return ent, cfg, host, passes, flops
+
+
+def fft_sweep_median(hd, max_bytes=1 << 28, reps=20, warm=3, sizes=None, sizes_1d_only=()):
+    """Stand-alone FFT sweep (the fifth configuration): R2C, then C2R with crop back, of signals
+    of n - 3 (squared) samples zero-padded to n, input sized to 256 MiB.  Every repetition has
+    its own event pair; reported: median ms, algorithmic GB/s and its fraction of 8 TB/s."""
+    import statistics
+    import torch
+    from paper_1412_7580_amd import synth
+    sizes = synth.FFT_SWEEP_SIZES if sizes is None else sizes
+    out = {}
+    for dim in (1, 2):
+        for n in tuple(sizes) + (tuple(sizes_1d_only) if dim == 1 else ()):
+            ni = n - 3
+            B = max_bytes // (4 * ni ** dim)
+            shape = (B, ni) if dim == 1 else (B, ni, ni)
+            x = torch.randn(shape, device="cuda", dtype=torch.float32)
+            nbins = (n // 2 + 1) * (1 if dim == 1 else n)
+            X = torch.empty((B, n // 2 + 1, 2) if dim == 1 else (B, n, n // 2 + 1, 2), device="cuda")
+            y = torch.empty_like(x)
+            fwd = (lambda: hd.fft_r2c_1d(x, n, out=X)) if dim == 1 else (lambda: hd.fft_r2c_2d(x, n, out=X))
+            inv = (lambda: hd.fft_c2r_1d(X, n, ni, out=y)) if dim == 1 else (lambda: hd.fft_c2r_2d(X, n, ni, ni, out=y))
+            byts = B * (4 * ni ** dim + 8 * nbins)
+            res = {"batch": B, "bytes": byts}
+            for nm, fn in (("r2c", fwd), ("c2r", inv)):
+                for _ in range(warm):
+                    fn()
+                ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+                torch.cuda.synchronize()
+                for a, b in ev:
+                    a.record(); fn(); b.record()
+                torch.cuda.synchronize()
+                ms = statistics.median(a.elapsed_time(b) for a, b in ev)
+                res[nm] = {"ms": round(ms, 4), "GBps": round(byts / ms / 1e6, 1),
+                           "frac": round(byts / ms / 1e6 / HBM_PEAK_GBS, 4)}
+            out[f"{dim}d_n{n}"] = res
+            del x, X, y
+            torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4"],
+                    help="headline configuration (default: the largest one, the 64x64 / 31x31 layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-passes", action="store_true",
                     help="time the three independent pass calls instead of fprop_save + backward")
     ap.add_argument("--library-basis", action="store_true",
-                    help="leave the Fourier basis to the library (28x28 for C2) instead of the one the "
-                         "configuration names")
-    ap.add_argument("--no-extra", action="store_true", help="skip the other configurations and the FFT sweep")
+                    help="leave the Fourier basis to the library (28x28 for the 27x27 layer) instead of the "
+                         "one the configuration names")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the other configurations and the FFT sweep of the roofline object (profiling runs)")
+    ap.add_argument("--extra", action="store_true",
+                    help="also time tiled layers, the paper's Table 4 shapes, weights transformed ahead, the 3x3 "
+                         "sweep of Section 5.4, rectangular bases, odd-factor FFT sizes (an `extra` object)")
     ap.add_argument("--tiled-only", action="store_true",
                     help="only time the tiled layers of the extra block and print them (for profiling runs)")
     ap.add_argument("--rect-only", action="store_true",
@@ -581,6 +687,7 @@ def main():
     ap.add_argument("--sweep-only", default=None, metavar="SIZES",
                     help="only run the stand-alone FFT sweep at these comma-separated sizes and print it "
                          "(for profiling runs)")
+    ap.add_argument("--sweep-reps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 256 MiB device copy a few times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
@@ -613,138 +720,62 @@ def main():
         return
     if args.sweep_only:
         sizes = tuple(int(v) for v in args.sweep_only.split(","))
-        print(json.dumps({"fft_sweep_256MiB": fft_sweep(hd, sizes=sizes, sizes_1d_only=())}))
+        print(json.dumps({"fft_sweep_256MiB": fft_sweep_median(hd, sizes=sizes, reps=args.sweep_reps)}))
         return
     name = args.workload
-    cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k != "passes"}
-    passes = synth.CONV_CONFIGS[name]["passes"]
-    t, host = device_tensors(cfg, synth.CONV_SEEDS[name])
-
-    # The headline runs on the Fourier basis the configuration names (FFT 32x32 for C2); the
-    # library's own choice, the smallest basis that holds the image, is timed next to it below.
-    basis = None if args.library_basis else cfg["N"]
-    if args.library_basis:
-        cfg["N"] = library_basis(cfg)
-    reuse = (len(passes) == 3) and not args.separate_passes
-    if reuse:
-        add_saved(hd, t, cfg, basis)
-    sec = time_steps(hd, t, cfg, passes, args.steps, args.warmup, reuse, basis)
-    flops = direct_flops(cfg) * len(passes)
-    value = flops / sec / 1e12
-
-    # Per-kernel durations over a second run of the same region, with per-dispatch events on.
     prof_steps = max(1, min(args.steps, 50))
-    kernels = {}
-    models = {p: stage_model(cfg, p) for p in passes}
-
-    def entry(ms, model):
-        ent = {"ms": round(ms, 5), "GBps": round(model["bytes"] / ms / 1e6, 1)}
-        if "flops" in model:
-            ent["TFLOPs"] = round(model["flops"] / ms / 1e9, 2)
-        return ent
-
-    if reuse:
-        km = profile_reuse_step(hd, t, cfg, prof_steps, basis)
-        for k, ms in km.items():
-            p, s_ = k.split(".")
-            if k == "fprop.fft":
-                model = models["fprop"]["fft"]
-            elif k == "backward.fft":
-                model = models["bprop"]["fft_a"]
-            elif k == "backward.contraction":
-                mb, ma = models["bprop"]["contraction"], models["accgrad"]["contraction"]
-                model = {"bytes": mb["bytes"] + ma["bytes"], "flops": mb["flops"] + ma["flops"]}
-            elif k == "backward.ifft":
-                model = {"bytes": models["bprop"]["ifft"]["bytes"] + models["accgrad"]["ifft"]["bytes"]}
-            else:
-                model = models[p][s_]
-            kernels[k] = entry(ms, model)
-            kernels[k]["_model"] = model
-    else:
-        stage_ms = profile_stages(hd, t, cfg, passes, prof_steps, basis)
-        for p in passes:
-            for i, s_ in enumerate(STAGES):
-                kernels[f"{p}.{s_}"] = entry(stage_ms[p][i], models[p][s_])
-                kernels[f"{p}.{s_}"]["_model"] = models[p][s_]
-    dom = max(kernels, key=lambda k: kernels[k]["ms"])
-    ds = dom.split(".")[1]
-    model = kernels[dom]["_model"]
-    for k in kernels:
-        del kernels[k]["_model"]
-    dms = kernels[dom]["ms"]
-    if ds == "contraction":
-        ach = model["flops"] / dms / 1e9
-        kname = "cgemm_pair_kernel" if dom == "backward.contraction" else "cgemm_bins_kernel / cgemm_tail_kernel"
-        roof = {"kernel": f"{dom} ({kname})", "bound": "mfma", "achieved": round(ach, 2),
-                "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(ach / MFMA_FP32_PEAK_TFLOPS, 4),
-                "traffic": None,
-                "note": "executed flops: 6 M N K per bin (3-multiplication complex product); "
-                        "the 4-multiplication equivalent rate is 4/3 of `achieved`"}
-    else:
-        ach = model["bytes"] / dms / 1e6
-        kn = "fft2d_c2r_kernel" if ds == "ifft" else "fft2d_r2c_kernel"
-        roof = {"kernel": f"{dom} ({kn})", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
-    tr = MEASURED_TRAFFIC_BYTES.get(name, {}).get(dom) if (reuse or ds == "contraction") else None
-    roof["traffic"] = None if tr is None else round(tr)
-    roof["algorithmic_bytes"] = model["bytes"]
-    roof["avg_launch_ms"] = dms
-    roof["launches_averaged"] = prof_steps
+    head, cfg, host, passes, flops = measure_config(hd, name, args.steps, args.warmup, prof_steps,
+                                                    args.separate_passes, args.library_basis)
+    stages = head["stages"]
+    dom = head["dominant"]
+    d = stages[dom]
+    model = kernel_model(cfg, dom)
+    traffic_src, traffic_tab = QUOTED_TRAFFIC.get(name, (None, {}))
+    traffic = traffic_tab.get(dom) if not (args.separate_passes or args.library_basis) else None
+    roof = {
+        "kernel": f"{dom} ({KERNEL_FUNCTIONS.get(dom.split('.')[1], 'fft2d_r2c_multi_kernel')})",
+        "bound": d["bound"],
+        "achieved": d["TFLOPs"] if d["bound"] == "mfma" else d["GBps"],
+        "peak": MFMA_FP32_PEAK_TFLOPS if d["bound"] == "mfma" else HBM_PEAK_GBS,
+        "unit": "TFLOP/s" if d["bound"] == "mfma" else "GB/s",
+        "frac": d["frac"],
+        "traffic": None if traffic is None else round(traffic),
+        "traffic_source": None if traffic is None else
+        f"quoted from {traffic_src} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain copy); not measured in this run",
+        "algorithmic_bytes": model["bytes"],
+        "avg_launch_ms": d["ms"], "launches_averaged": prof_steps,
+        "note": "per-kernel times: HIP event pair attached to each dispatch on the library's stream; "
+                "contraction flops are the executed ones, 6 M N K per bin (3-multiplication complex product)",
+        "stages": stages,
+    }
+    if "flops" in model:
+        roof["executed_flops"] = model["flops"]
+    if not args.no_others:
+        others = {}
+        for other in ("C1", "C2", "C3", "C4"):
+            if other == name:
+                continue
+            ent, *_ = measure_config(hd, other, 30, 5, 20)
+            others[other] = ent
+        roof["other_configs"] = others
+        roof["fft_sweep"] = fft_sweep_median(hd, reps=args.sweep_reps)
 
     out = {
-        "metric": "effective conv TFLOP/s (direct-conv FLOPs), fprop+bprop+accGrad",
-        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{name}: S={cfg['S']} f={cfg['f']} f'={cfg['fo']} input {cfg['h']}x{cfg['w']} "
-                               f"kernel {cfg['kh']}x{cfg['kw']} FFT {cfg['N']}x{cfg['N']}, passes " + "+".join(passes),
-                   "seed": synth.CONV_SEEDS[name],
-                   "calls": "fft_conv_fprop_save + fft_conv_backward (x, w, gy transformed once each)" if reuse
-                            else "fft_conv_fprop, fft_conv_bprop, fft_conv_accgrad (independent passes)"},
+        "metric": "effective conv TFLOP/s (direct-conv FLOPs), fprop+bprop+accGrad; FFT GB/s",
+        "value": round(flops / head["ms_per_step"] / 1e9, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": head["workload"], "seed": synth.CONV_SEEDS[name], "calls": head["calls"],
+                   "timing": f"median of {args.steps} per-step HIP event pairs after {args.warmup} warm-up steps, "
+                             f"region bracketed by synchronize(); host-clock mean over the same steps "
+                             f"{head['ms_per_step_wall_mean']} ms, min/max {head['ms_per_step_min_max']}",
+                   "launches_per_step": head["launches_per_step"], "kernel_ms_sum": head["kernel_ms_sum"]},
         "roofline": roof,
-        "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, host)
-    if not args.no_extra:
+    if args.extra:
         extra = {}
-        def measure(c, ps, b, n):
-            """Separate passes and, for three-pass workloads, the reuse step of configuration c on
-            basis b (None: the library's choice)."""
-            s3 = time_steps(hd, t, c, ps, n, 5, False, b)
-            sm = profile_stages(hd, t, c, ps, 5, b)
-            ent = {"basis": library_basis(c) if b is None else b,
-                   "ms_per_step_separate_passes": round(s3 * 1e3, 4),
-                   "effective_TFLOPs_separate_passes": round(direct_flops(c) * len(ps) / s3 / 1e12, 2),
-                   "kernel_ms[fft,contraction,ifft]": {p: [round(v, 4) for v in sm[p]] for p in ps}}
-            if len(ps) == 3:
-                add_saved(hd, t, c, b)
-                s2 = time_steps(hd, t, c, ps, n, 5, True, b)
-                ent["ms_per_step"] = round(s2 * 1e3, 4)
-                ent["effective_TFLOPs"] = round(direct_flops(c) * 3 / s2 / 1e12, 2)
-            return ent
-
-        if reuse:
-            s3 = time_steps(hd, t, cfg, passes, max(10, args.steps // 4), 5, False, basis)
-            extra[name + "_separate_passes"] = {"ms_per_step": round(s3 * 1e3, 5),
-                                                "effective_TFLOPs": round(flops / s3 / 1e12, 2)}
-        if basis is not None and library_basis(cfg) != basis:
-            # the same workload with the basis left to the library (Section 3.4's basis search)
-            extra[name + "_library_basis"] = measure(cfg, passes, None, max(10, args.steps // 2))
-        for other in ("C1", "C3", "C4"):
-            if other == name:
-                continue
-            del t
-            torch.cuda.empty_cache()
-            ocfg = {k: v for k, v in synth.CONV_CONFIGS[other].items() if k != "passes"}
-            opasses = synth.CONV_CONFIGS[other]["passes"]
-            t, _ = device_tensors(ocfg, synth.CONV_SEEDS[other])
-            n = 20 if other == "C4" else 50
-            extra[other] = measure(ocfg, opasses, ocfg["N"], n)
-            if library_basis(ocfg) != ocfg["N"]:
-                extra[other + "_library_basis"] = measure(ocfg, opasses, None, n)
-        del t
-        torch.cuda.empty_cache()
         extra["C1_fprop_hip_graph"] = graph_replay_c1(hd)
         extra["tiled_layers"] = tiled_layers(hd)
         torch.cuda.empty_cache()
@@ -758,11 +789,12 @@ def main():
         torch.cuda.empty_cache()
         extra["device_copy_GBps"] = device_copy_bandwidth()
         torch.cuda.empty_cache()
-        extra["fft_sweep_256MiB"] = fft_sweep(hd)
-        torch.cuda.empty_cache()
+        for nm in ("C2", "C3", "C1"):
+            ent, *_ = measure_config(hd, nm, 30, 5, 20, library_basis_=True)
+            extra[nm + "_library_basis"] = ent
         # the sizes with an odd factor (not part of the benchmark definition's sweep)
-        extra["fft_sweep_mixed_sizes_256MiB"] = fft_sweep(hd, sizes=(10, 12, 14, 18, 20, 24, 28, 36, 40, 48, 56, 80, 96, 112),
-                                                          sizes_1d_only=(160, 192, 224))
+        extra["fft_sweep_mixed_sizes_256MiB"] = fft_sweep_median(
+            hd, sizes=(10, 12, 14, 18, 20, 24, 28, 36, 40, 48, 56, 80, 96, 112), sizes_1d_only=(160, 192, 224, 256))
         out["extra"] = extra
     print(json.dumps(out))
 

@@ -80,7 +80,9 @@ size_t fftconv_workspace_bytes(int pass, int S, int f, int fo, int h, int w, int
  * basis).  The same basis serves all three passes of a layer.
  * `ws`/`ws_bytes`: optional caller-owned device scratch of at least
  * fftconv_workspace_bytes(); with ws == NULL the handle grows and reuses its own buffer
- * (hipMalloc on first use or growth only).
+ * (hipMalloc on first use or growth only; growth waits for the stream first).  While the
+ * handle's stream is being captured into a graph the buffer cannot grow: a call that would need
+ * to returns FFTCONV_WORKSPACE_TOO_SMALL (pass a workspace, or make one eager call first).
  */
 
 /* fprop: y(s,j) = sum_i x(s,i) (star) w(j,i)  -- valid cross-correlation.
@@ -165,6 +167,22 @@ int fft_conv_accgrad_tiled(fftconv_handle hd, const float *x, const float *gy, f
 int fftconv_autotune_basis(fftconv_handle hd, const float *x, const float *wt, const float *gy,
                            float *y, float *gx, float *gw, int S, int f, int fo, int h, int w, int kh, int kw,
                            int reps, int *basis_out, float *ms_out);
+
+/*
+ * The plan of one pass as numbers (host only; for tests of the planner, which check on the CPU
+ * that the windows, crops and buffer offsets of every layer shape stay inside their tensors and
+ * that a plain re-enactment of the plan gives the convolution).  tile_n: -1 as the ordinary
+ * entry points choose, else as for the tiled passes.  Writes min(cap, count) values to out and
+ * returns count (61), or a negative fftconv_status.  Values, in order: basis rows, basis
+ * columns, tiled, rectangular, bins per plane tile of the layout, log2(planes per layout tile);
+ * planes of operand A, operand B, product C; window / crop sizes hA, wA, hB, wB, hC, wC;
+ * contraction sizes M, N, K; conjugate A, conjugate B; plane strides of A(m,k): row, column, of
+ * B(k,n), of C(m,n); workspace offsets of A, B, C and total bytes; bytes of A's buffer; then for
+ * A, B and C ten values each: is a window view, channels, tiles down, tiles across, tile step
+ * rows, columns, window offset rows, columns, image rows, columns.
+ */
+int fftconv_describe_plan(int pass, int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                          int pad_h, int pad_w, long *out, int cap);
 
 /*
  * Passes of a layer whose input images are surrounded by pad_h rows and pad_w columns of zeros
@@ -264,9 +282,13 @@ int fft_conv_bprop_fused(fftconv_handle hd, const float *gy, const void *wf, siz
  * made.  Complex data are interleaved (re,im) fp32; only the Hermitian half
  * k = 0..n/2 along the innermost axis is stored (Table 1), in natural bin order.
  * The inverse calls are true inverses (scaled by 1/n per dimension) that keep the first
- * n_out (h_out x w_out) samples.  Their input must be the transform of a real signal;
- * imaginary parts of self-conjugate bins are not looked at.  B = 0 is a no-op that
- * returns FFTCONV_OK (pointers may then be NULL).
+ * n_out (h_out x w_out) samples.  Their input must be the transform of a real signal.  In
+ * 1-D that constrains only bins 0 and n/2, whose imaginary parts are not looked at.  In 2-D the
+ * two self-conjugate columns k2 = 0 and k2 = n/2 must be Hermitian along the other axis,
+ * X[k1][k2] = conj(X[(n - k1) % n][k2]) (every transform of real data, and every product of such
+ * transforms, is); the inverse relies on it, and for input without that symmetry the result is
+ * unspecified (no error is reported).  Columns 0 < k2 < n/2 are unconstrained.  B = 0 is a
+ * no-op that returns FFTCONV_OK (pointers may then be NULL).
  */
 /* in[B,n_in] -> out[B,n/2+1,2];  1 <= n_in <= n. */
 int fft_r2c_1d(fftconv_handle hd, const float *in, float *out, long B, int n_in, int n);
@@ -305,15 +327,24 @@ int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
  * With profiling enabled every kernel of a convolution call is launched with a start/stop
  * HIP event pair attached to that dispatch on the handle's stream.
  * fftconv_last_kernel_ms() waits for the last call and writes the execution times in
- * milliseconds, in launch order, to ms_out[0 .. *count):
- *   fft_conv_fprop / bprop / accgrad / fprop_save: forward FFT of both operands (one launch),
- *     per-bin contraction, inverse FFT                                             (3 kernels)
- *   fft_conv_backward: forward FFT of gy, then contraction + inverse FFT for gx and again
- *     for gw (those requested)                                                 (3 or 5 kernels)
+ * milliseconds, in launch order, to ms_out[0 .. *count) (at most 8 kernels per call);
+ * fftconv_last_kernel_label(h, i) names kernel i of that list (a static string, "" when there
+ * is no such entry):
+ *   "fft.ab"  forward FFT of both operands in one launch; "fft.a", "fft.b" when they are two
+ *             launches or there is only one operand to transform (a = first operand of the pass:
+ *             x for fprop, gy for bprop, accGrad and fft_conv_backward; b = weights, or x for
+ *             accGrad; fft_conv_backward on a tiled layer cuts gy twice: a for bprop, b for accGrad)
+ *   "contraction"       per-bin contraction of one pass
+ *   "contraction.pair"  the bprop and accGrad contractions of fft_conv_backward in one launch
+ *   "ifft", "ifft.pair" inverse FFT + clip of one product, or of gx and gw in one launch
+ *   "fused"             the one-launch passes
+ * fft_conv_fprop / bprop / accgrad / fprop_save give 3 or 4 entries; fft_conv_backward gives
+ * fft of gy, then contraction and ifft for gx and again for gw (5), or 4 or 3 with shared launches.
  * Off by default.
  */
 int fftconv_set_profiling(fftconv_handle h, int enabled);
 int fftconv_last_kernel_ms(fftconv_handle h, float *ms_out, int capacity, int *count);
+const char *fftconv_last_kernel_label(fftconv_handle h, int i);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,7 @@ SYMBOLS = [
     "fftconv_create", "fftconv_destroy", "fftconv_set_stream", "fftconv_status_string",
     "fftconv_workspace_bytes", "fft_conv_fprop", "fft_conv_bprop", "fft_conv_accgrad",
     "fft_r2c_1d", "fft_c2r_1d", "fft_r2c_2d", "fft_c2r_2d",
-    "fftconv_set_profiling", "fftconv_last_kernel_ms",
+    "fftconv_set_profiling", "fftconv_last_kernel_ms", "fftconv_last_kernel_label",
     "fftconv_saved_bytes", "fftconv_backward_workspace_bytes", "fft_conv_fprop_save", "fft_conv_backward",
     "fftconv_tiled_workspace_bytes", "fftconv_tile_basis", "fftconv_layer_basis",
     "fft_conv_fprop_tiled", "fft_conv_bprop_tiled", "fft_conv_accgrad_tiled", "fftconv_autotune_basis",
@@ -29,7 +29,7 @@ SYMBOLS = [
     "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
     "fftconv_saved_bytes_padded", "fftconv_backward_workspace_bytes_padded",
     "fft_conv_fprop_save_padded", "fft_conv_backward_padded",
-    "fftconv_static_scratch_bytes", "fft_conv_fprop_static",
+    "fftconv_static_scratch_bytes", "fft_conv_fprop_static", "fftconv_describe_plan",
 ]
 
 
@@ -66,6 +66,8 @@ def load_library():
     lib.fft_c2r_2d.argtypes = [vp, vp, vp, l, i, i, i]
     lib.fftconv_set_profiling.argtypes = [vp, i]
     lib.fftconv_last_kernel_ms.argtypes = [vp, ctypes.POINTER(f), i, ctypes.POINTER(i)]
+    lib.fftconv_last_kernel_label.argtypes = [vp, i]
+    lib.fftconv_last_kernel_label.restype = ctypes.c_char_p
     lib.fftconv_saved_bytes.argtypes = [i] * 7
     lib.fftconv_saved_bytes.restype = sz
     lib.fftconv_backward_workspace_bytes.argtypes = [i] * 7
@@ -105,6 +107,8 @@ def load_library():
     lib.fftconv_backward_workspace_bytes_padded.restype = sz
     lib.fft_conv_fprop_save_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz, vp, sz]
     lib.fft_conv_backward_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [f, i, vp, sz, vp, sz]
+    lib.fftconv_describe_plan.argtypes = [i] * 11 + [ctypes.POINTER(ctypes.c_long), i]
+    lib.fftconv_describe_plan.restype = i
     lib.fftconv_static_scratch_bytes.argtypes = []
     lib.fftconv_static_scratch_bytes.restype = sz
     lib.fft_conv_fprop_static.argtypes = [vp, vp, vp, vp] + [i] * 7
@@ -126,6 +130,27 @@ def _dev_f32(t, name):
 
 
 FPROP, BPROP, ACCGRAD = 0, 1, 2
+
+PLAN_FIELDS = ("Nr Nc tiled rect bins tile_log2 planesA planesB planesC hA wA hB wB hC wC M N K conjA conjB "
+               "a_rs a_cs b_rs b_cs c_rs c_cs offA offB offC total bytesA").split()
+VIEW_FIELDS = "view C nty ntx dy dx oy ox H W".split()
+
+
+def describe_plan(pass_, S, f, fo, h, w, kh, kw, tile_n=-1, pad_h=0, pad_w=0):
+    """fftconv_describe_plan as a dict (host only): the fields of PLAN_FIELDS, and "A", "B", "C":
+    dicts of VIEW_FIELDS.  Raises FFTConvError for shapes the planner rejects."""
+    lib = load_library()
+    buf = (ctypes.c_long * 64)()
+    n = int(lib.fftconv_describe_plan(pass_, S, f, fo, h, w, kh, kw, tile_n, pad_h, pad_w, buf, 64))
+    if n < 0:
+        _check(-n, "fftconv_describe_plan")
+    vals = [int(buf[k]) for k in range(n)]
+    out = dict(zip(PLAN_FIELDS, vals))
+    at = len(PLAN_FIELDS)
+    for name in "ABC":
+        out[name] = dict(zip(VIEW_FIELDS, vals[at:at + len(VIEW_FIELDS)]))
+        at += len(VIEW_FIELDS)
+    return out
 
 
 class Handle:
@@ -170,6 +195,16 @@ class Handle:
         n = ctypes.c_int(0)
         _check(self._lib.fftconv_last_kernel_ms(self._h, buf, 8, ctypes.byref(n)), "fftconv_last_kernel_ms")
         return [float(buf[k]) for k in range(n.value)]
+
+    def last_kernel_labels(self):
+        """Names of the kernels whose times last_kernel_ms() returns, in the same order."""
+        out = []
+        for k in range(8):
+            s = self._lib.fftconv_last_kernel_label(self._h, k)
+            if not s:
+                break
+            out.append(s.decode())
+        return out
 
     def saved_bytes(self, S, f, fo, h, w, kh, kw) -> int:
         return int(self._lib.fftconv_saved_bytes(S, f, fo, h, w, kh, kw))

@@ -46,8 +46,13 @@ static hipError_t static_scratch_for(int device, void **out) {
     return hipSuccess;
 }
 
+struct PassPlan;
+struct PlanCache;
+
 struct fftconv_ctx {
     int device;
+    GemmSwitches sw;        // A/B switches of the contraction, read from the environment at creation
+    PlanCache *plans;       // plans of the layer shapes seen so far
     hipStream_t stream;
     void *ws;
     size_t ws_bytes;
@@ -55,6 +60,7 @@ struct fftconv_ctx {
     int profiling;
     hipEvent_t ev[2 * 8];   // start/stop pair per kernel of the last call
     int nk;                 // kernels of the last call that carry events
+    const char *label[8];   // what each of them is (see fftconv_last_kernel_label)
     char last_hip_error[256];
 };
 
@@ -257,6 +263,38 @@ static int make_plan(int pass, int S, int f, int fo, int h, int w, int kh, int k
     return FFTCONV_OK;
 }
 
+// Plans by layer shape, kept in the handle (the per-problem-size strategy cache of Section 3.4 of
+// the paper): a call on a shape seen before skips the basis choice and tiling arithmetic.  A
+// small ring, searched linearly; a training loop cycles through a handful of layer shapes.
+struct PlanKey {
+    int v[11];   // pass, S, f, fo, h, w, kh, kw, tile_n, ph, pw
+    bool operator==(const PlanKey &o) const {
+        for (int i = 0; i < 11; ++i) if (v[i] != o.v[i]) return false;
+        return true;
+    }
+};
+struct PlanCache {
+    static constexpr int kSlots = 48;
+    PlanKey key[kSlots];
+    PassPlan plan[kSlots];
+    int used = 0, next = 0;
+};
+
+// make_plan through the handle's cache (only valid plans are kept).
+static int cached_plan(fftconv_ctx *c, int pass, int S, int f, int fo, int h, int w, int kh, int kw, PassPlan *p,
+                       int tile_n = -1, int ph = 0, int pw = 0) {
+    if (!c || !c->plans) return make_plan(pass, S, f, fo, h, w, kh, kw, p, tile_n, ph, pw);
+    PlanCache &pc = *c->plans;
+    const PlanKey k{{pass, S, f, fo, h, w, kh, kw, tile_n, ph, pw}};
+    for (int i = 0; i < pc.used; ++i)
+        if (pc.key[i] == k) { *p = pc.plan[i]; return FFTCONV_OK; }
+    const int rc = make_plan(pass, S, f, fo, h, w, kh, kw, p, tile_n, ph, pw);
+    if (rc != FFTCONV_OK) return rc;
+    const int slot = pc.used < PlanCache::kSlots ? pc.used++ : (pc.next = (pc.next + 1) % PlanCache::kSlots);
+    pc.key[slot] = k; pc.plan[slot] = *p;
+    return FFTCONV_OK;
+}
+
 static int hip_fail(fftconv_ctx *c, hipError_t e) {
     if (c) snprintf(c->last_hip_error, sizeof(c->last_hip_error), "HIP error: %s", hipGetErrorString(e));
     return FFTCONV_HIP_ERROR;
@@ -266,6 +304,12 @@ static int get_workspace(fftconv_ctx *c, size_t need, void **ws, size_t ws_bytes
     if (*ws) return ws_bytes < need ? FFTCONV_WORKSPACE_TOO_SMALL : FFTCONV_OK;
     hipError_t e;
     if (c->ws_bytes < need) {
+        // Growing means a synchronisation, a free and an allocation: none of them may happen
+        // while the stream is being captured into a graph.  Such a caller passes a workspace (or
+        // makes one eager call first, after which the handle's buffer is large enough).
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(c->stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+            return FFTCONV_WORKSPACE_TOO_SMALL;
         if (c->ws) {
             if ((e = hipStreamSynchronize(c->stream)) != hipSuccess) return hip_fail(c, e);
             (void)hipFree(c->ws);
@@ -280,10 +324,11 @@ static int get_workspace(fftconv_ctx *c, size_t need, void **ws, size_t ws_bytes
 
 // Launch context for the next kernel of the current call: with profiling on, each kernel gets
 // its own start/stop event pair (kMaxKernels per call).
-static LaunchCtx next_ctx(fftconv_ctx *c) {
-    if (!c->profiling || c->nk >= kMaxKernels) return LaunchCtx{c->stream, nullptr, nullptr};
+static LaunchCtx next_ctx(fftconv_ctx *c, const char *label) {
+    if (!c->profiling || c->nk >= kMaxKernels) return LaunchCtx{c->stream, nullptr, nullptr, &c->sw};
     const int k = c->nk++;
-    return LaunchCtx{c->stream, c->ev[2 * k], c->ev[2 * k + 1]};
+    c->label[k] = label;
+    return LaunchCtx{c->stream, c->ev[2 * k], c->ev[2 * k + 1], &c->sw};
 }
 
 static float *at(void *base, size_t off) { return reinterpret_cast<float *>(static_cast<char *>(base) + off); }
@@ -315,23 +360,21 @@ static bool share_forward(int N, int tsh, int hA, long planesA, int hB, long pla
 }
 
 // Forward transforms of both operands of a pass, as one launch where share_forward says so.
-// Profiling reports the pair as one entry in both cases (the separate launches pair the events).
+// Profiling reports a shared launch as one entry ("fft.ab"), separate ones as "fft.a", "fft.b".
 static hipError_t forward_pair(fftconv_ctx *c, const PassPlan &p, const float *a, float *AF,
                                const float *b, float *BF) {
     const PlaneView *va = p.viewA ? &p.vA : nullptr, *vb = p.viewB ? &p.vB : nullptr;
     if (p.rect) {
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, nullptr}, {b, BF, p.planesB, p.hB, p.wB, nullptr}};
-        return launch_fft2d_r2c_rect(ops, 2, p.Nr, p.Nc, next_ctx(c));
+        return launch_fft2d_r2c_rect(ops, 2, p.Nr, p.Nc, next_ctx(c, "fft.ab"));
     }
     if (share_forward(p.N, p.lay.tsh, p.hA, p.planesA, p.hB, p.planesB)) {
         FwdOperand ops[2] = {{a, AF, p.planesA, p.hA, p.wA, va}, {b, BF, p.planesB, p.hB, p.wB, vb}};
-        return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c));
+        return launch_fft2d_r2c_multi(ops, 2, p.N, next_ctx(c, "fft.ab"));
     }
-    // one event pair around both launches: start from the first, stop from the second
-    LaunchCtx lc = next_ctx(c);
-    hipError_t e = transform(p, a, AF, p.planesA, p.hA, p.wA, LaunchCtx{lc.stream, lc.start, nullptr}, va);
+    hipError_t e = transform(p, a, AF, p.planesA, p.hA, p.wA, next_ctx(c, "fft.a"), va);
     if (e != hipSuccess) return e;
-    return transform(p, b, BF, p.planesB, p.hB, p.wB, LaunchCtx{lc.stream, nullptr, lc.stop}, vb);
+    return transform(p, b, BF, p.planesB, p.hB, p.wB, next_ctx(c, "fft.b"), vb);
 }
 
 // The contraction of one pass as the kernels see it.
@@ -347,8 +390,8 @@ static GemmProblem gemm_problem(const PassPlan &p, const float *AF, const float 
 // Inverse transform + crop of one pass's product (1/N^2 folded into the output scale).
 static hipError_t invert(fftconv_ctx *c, const PassPlan &p, const float *CF, float *out, float scale, int accumulate) {
     const float s = scale / ((float)p.Nr * (float)p.Nc);
-    if (p.rect) return launch_fft2d_c2r_rect(CF, out, p.planesC, p.Nr, p.Nc, p.hC, p.wC, s, accumulate != 0, next_ctx(c));
-    return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c),
+    if (p.rect) return launch_fft2d_c2r_rect(CF, out, p.planesC, p.Nr, p.Nc, p.hC, p.wC, s, accumulate != 0, next_ctx(c, "ifft"));
+    return launch_fft2d_c2r(CF, out, p.planesC, p.N, p.hC, p.wC, true, s, accumulate != 0, next_ctx(c, "ifft"),
                             p.viewC ? &p.vC : nullptr);
 }
 
@@ -361,7 +404,7 @@ static hipError_t invert_pair(fftconv_ctx *c, const PassPlan &pb, const float *G
         const InvOperand ops[2] = {{GXF, gx, pb.planesC, pb.hC, pb.wC, sb, false, nullptr},
                                    {GWF, gw, pa.planesC, pa.hC, pa.wC, sa, accumulate != 0, nullptr}};
         const int nk = c->nk;
-        const hipError_t e = launch_fft2d_c2r_rect_pair(ops, pb.Nr, pb.Nc, next_ctx(c));
+        const hipError_t e = launch_fft2d_c2r_rect_pair(ops, pb.Nr, pb.Nc, next_ctx(c, "ifft.pair"));
         if (e != hipErrorNotSupported) return e;
         c->nk = nk;
     }
@@ -370,7 +413,7 @@ static hipError_t invert_pair(fftconv_ctx *c, const PassPlan &pb, const float *G
         const InvOperand ops[2] = {{GXF, gx, pb.planesC, pb.hC, pb.wC, sb, false, pb.viewC ? &pb.vC : nullptr},
                                    {GWF, gw, pa.planesC, pa.hC, pa.wC, sa, accumulate != 0, pa.viewC ? &pa.vC : nullptr}};
         const int nk = c->nk;
-        const hipError_t e = launch_fft2d_c2r_pair(ops, pb.N, next_ctx(c));
+        const hipError_t e = launch_fft2d_c2r_pair(ops, pb.N, next_ctx(c, "ifft.pair"));
         if (e != hipErrorNotSupported) return e;
         c->nk = nk;   // nothing was launched: give the event pair back
     }
@@ -382,7 +425,7 @@ static hipError_t invert_pair(fftconv_ctx *c, const PassPlan &pb, const float *G
 static hipError_t contract_and_invert(fftconv_ctx *c, const PassPlan &p, const float *AF, const float *BF,
                                       float *CF, float *out, float scale, int accumulate) {
     const GemmProblem g = gemm_problem(p, AF, BF, CF);
-    if (hipError_t e = launch_cgemm_bins(g.A, g.B, g.C, g.layC, g.C_rs, g.C_cs, g.M, g.N, g.K, g.bins, next_ctx(c)); e != hipSuccess) return e;
+    if (hipError_t e = launch_cgemm_bins(g.A, g.B, g.C, g.layC, g.C_rs, g.C_cs, g.M, g.N, g.K, g.bins, next_ctx(c, "contraction")); e != hipSuccess) return e;
     return invert(c, p, CF, out, scale, accumulate);
 }
 
@@ -391,7 +434,7 @@ static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB
                     void *ws, size_t ws_bytes, int tile_n = -1, int ph = 0, int pw = 0) {
     if (!c || !opA || !opB || !out) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw);
+    int rc = cached_plan(c, pass, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw);
     if (rc != FFTCONV_OK) return rc;
     if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     float *AF = at(ws, p.offA), *BF = at(ws, p.offB), *CF = at(ws, p.offC);
@@ -409,13 +452,13 @@ static int run_pass_weights(fftconv_ctx *c, int pass, const float *opA, const vo
                             void *ws, size_t ws_bytes) {
     if (!c || !opA || !wf || !out) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p, -1, ph, pw);
+    int rc = cached_plan(c, pass, S, f, fo, h, w, kh, kw, &p, -1, ph, pw);
     if (rc != FFTCONV_OK) return rc;
     if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
     if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     float *AF = at(ws, p.offA), *CF = at(ws, p.offC);
     c->nk = 0;
-    hipError_t e = transform(p, opA, AF, p.planesA, p.hA, p.wA, next_ctx(c), p.viewA ? &p.vA : nullptr);
+    hipError_t e = transform(p, opA, AF, p.planesA, p.hA, p.wA, next_ctx(c, "fft.a"), p.viewA ? &p.vA : nullptr);
     if (e != hipSuccess) return hip_fail(c, e);
     if ((e = contract_and_invert(c, p, AF, static_cast<const float *>(wf), CF, out, 1.0f, 0)) != hipSuccess) return hip_fail(c, e);
     return FFTCONV_OK;
@@ -447,10 +490,16 @@ int fftconv_create(fftconv_handle *out, int device) {
     c->device = device; c->stream = nullptr; c->ws = nullptr; c->ws_bytes = 0;
     c->profiling = 0; c->nk = 0; c->last_hip_error[0] = 0;
     c->static_scratch = nullptr;
+    c->sw = read_gemm_switches();
+    c->plans = new (std::nothrow) PlanCache();   // without it every call plans afresh
     // this device's copy of the static scratch array (the device is current here)
-    if (static_scratch_for(device, &c->static_scratch) != hipSuccess) { delete c; return FFTCONV_HIP_ERROR; }
+    if (static_scratch_for(device, &c->static_scratch) != hipSuccess) { delete c->plans; delete c; return FFTCONV_HIP_ERROR; }
     for (int i = 0; i < 2 * kMaxKernels; ++i)
-        if (hipEventCreate(&c->ev[i]) != hipSuccess) { delete c; return FFTCONV_HIP_ERROR; }
+        if (hipEventCreate(&c->ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(c->ev[j]);
+            delete c->plans; delete c;
+            return FFTCONV_HIP_ERROR;
+        }
     *out = c;
     return FFTCONV_OK;
 }
@@ -459,6 +508,7 @@ int fftconv_destroy(fftconv_handle h) {
     if (!h) return FFTCONV_INVALID_ARG;
     if (h->ws) (void)hipFree(h->ws);
     for (int i = 0; i < 2 * kMaxKernels; ++i) (void)hipEventDestroy(h->ev[i]);
+    delete h->plans;
     delete h;
     return FFTCONV_OK;
 }
@@ -498,7 +548,7 @@ int fft_conv_fprop_static(fftconv_handle hd, const float *x, const float *wt, fl
                           int S, int f, int fo, int h, int w, int kh, int kw) {
     if (!hd || !x || !wt || !y) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    const int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
+    const int rc = cached_plan(hd, FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
     if (rc != FFTCONV_OK) return rc;
     if (p.total > kStaticScratchBytes) return FFTCONV_STATIC_SCRATCH_EXCEEDED;
     if (!hd->static_scratch) return FFTCONV_HIP_ERROR;
@@ -533,6 +583,32 @@ int fftconv_layer_basis(int h, int w, int kh, int kw, int pad_h, int pad_w, int 
     if (n_rows) *n_rows = p.Nr;
     if (n_cols) *n_cols = p.Nc;
     return p.tiled ? 1 : 0;
+}
+
+int fftconv_describe_plan(int pass, int S, int f, int fo, int h, int w, int kh, int kw, int tile_n,
+                          int pad_h, int pad_w, long *out, int cap) {
+    PassPlan p;
+    const int rc = make_plan(pass, S, f, fo, h, w, kh, kw, &p, tile_n, pad_h, pad_w);
+    if (rc != FFTCONV_OK) return -rc;
+    long v[61];
+    int n = 0;
+    v[n++] = p.Nr; v[n++] = p.Nc; v[n++] = p.tiled; v[n++] = p.rect; v[n++] = p.bins; v[n++] = p.lay.tsh;
+    v[n++] = p.planesA; v[n++] = p.planesB; v[n++] = p.planesC;
+    v[n++] = p.hA; v[n++] = p.wA; v[n++] = p.hB; v[n++] = p.wB; v[n++] = p.hC; v[n++] = p.wC;
+    v[n++] = p.M; v[n++] = p.Nn; v[n++] = p.K;
+    v[n++] = p.conjA; v[n++] = p.conjB;
+    v[n++] = p.a_rs; v[n++] = p.a_cs; v[n++] = p.b_rs; v[n++] = p.b_cs; v[n++] = p.c_rs; v[n++] = p.c_cs;
+    v[n++] = (long)p.offA; v[n++] = (long)p.offB; v[n++] = (long)p.offC; v[n++] = (long)p.total;
+    v[n++] = (long)(p.lay.floats(p.planesA) * sizeof(float));
+    const bool has[3] = {p.viewA, p.viewB, p.viewC};
+    const PlaneView *views[3] = {&p.vA, &p.vB, &p.vC};
+    for (int i = 0; i < 3; ++i) {
+        const PlaneView &q = *views[i];
+        v[n++] = has[i]; v[n++] = q.C; v[n++] = q.nty; v[n++] = q.ntx; v[n++] = q.dy; v[n++] = q.dx;
+        v[n++] = q.oy; v[n++] = q.ox; v[n++] = q.H; v[n++] = q.W;
+    }
+    for (int i = 0; i < n && i < cap; ++i) if (out) out[i] = v[i];
+    return n;
 }
 
 int fftconv_tile_basis(int h, int w, int kh, int kw, int tile_n) {
@@ -681,6 +757,11 @@ int fftconv_set_profiling(fftconv_handle h, int enabled) {
     return FFTCONV_OK;
 }
 
+const char *fftconv_last_kernel_label(fftconv_handle h, int i) {
+    if (!h || !h->profiling || i < 0 || i >= h->nk) return "";
+    return h->label[i];
+}
+
 int fftconv_last_kernel_ms(fftconv_handle h, float *ms_out, int capacity, int *count) {
     if (!h || !ms_out || !count || capacity < 0) return FFTCONV_INVALID_ARG;
     *count = 0;
@@ -758,7 +839,7 @@ static int fprop_save_impl(fftconv_handle hd, const float *x, const float *wt, f
                            void *saved, size_t saved_bytes, void *ws, size_t ws_bytes, int tile_n = -1) {
     if (!hd || !x || !wt || !y || !saved) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw);
+    int rc = cached_plan(hd, FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw);
     if (rc != FFTCONV_OK) return rc;
     const SavedPlan sp = saved_plan(p);
     if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
@@ -778,10 +859,10 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
                          void *ws, size_t ws_bytes, int tile_n = -1) {
     if (!hd || !gy || !saved || (!gx && !gw)) return FFTCONV_INVALID_ARG;
     PassPlan pf, pb, pa;
-    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &pf, tile_n, ph, pw);
+    int rc = cached_plan(hd, FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &pf, tile_n, ph, pw);
     if (rc != FFTCONV_OK) return rc;
-    (void)make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, tile_n, ph, pw);
-    (void)make_plan(FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, tile_n, ph, pw);
+    if ((rc = cached_plan(hd, FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &pb, tile_n, ph, pw)) != FFTCONV_OK) return rc;
+    if ((rc = cached_plan(hd, FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &pa, tile_n, ph, pw)) != FFTCONV_OK) return rc;
     const SavedPlan sp = saved_plan(pf);
     if (saved_bytes < sp.total) return FFTCONV_WORKSPACE_TOO_SMALL;
     const BackwardPlan bp = backward_plan(pb, pa);
@@ -792,28 +873,27 @@ static int backward_impl(fftconv_handle hd, const float *gy, float *gx, float *g
     hd->nk = 0;
     hipError_t e;
     if (!pb.tiled) {
-        if ((e = transform(pb, gy, GYF, pb.planesA, pb.hA, pb.wA, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+        if ((e = transform(pb, gy, GYF, pb.planesA, pb.hA, pb.wA, next_ctx(hd, "fft.a"))) != hipSuccess) return hip_fail(hd, e);
     } else {
         // gy cut twice: overlapping windows for bprop, disjoint tiles for accGrad
         if (gx && gw && share_forward(pb.N, pb.lay.tsh, pb.hA, pb.planesA, pa.hA, pa.planesA)) {   // as for the two operands of a pass
             FwdOperand ops[2] = {{gy, GYF, pb.planesA, pb.hA, pb.wA, &pb.vA}, {gy, GYFa, pa.planesA, pa.hA, pa.wA, &pa.vA}};
-            if ((e = launch_fft2d_r2c_multi(ops, 2, pb.N, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+            if ((e = launch_fft2d_r2c_multi(ops, 2, pb.N, next_ctx(hd, "fft.ab"))) != hipSuccess) return hip_fail(hd, e);
         } else {
-        LaunchCtx lc = next_ctx(hd);
-        if (gx && (e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true,
-                                        LaunchCtx{lc.stream, lc.start, gw ? nullptr : lc.stop}, &pb.vA)) != hipSuccess) return hip_fail(hd, e);
-        if (gw && (e = launch_fft2d_r2c(gy, GYFa, pa.planesA, pa.hA, pa.wA, pa.N, true,
-                                        LaunchCtx{lc.stream, gx ? nullptr : lc.start, lc.stop}, &pa.vA)) != hipSuccess) return hip_fail(hd, e);
+            if (gx && (e = launch_fft2d_r2c(gy, GYF, pb.planesA, pb.hA, pb.wA, pb.N, true, next_ctx(hd, "fft.a"),
+                                            &pb.vA)) != hipSuccess) return hip_fail(hd, e);
+            if (gw && (e = launch_fft2d_r2c(gy, GYFa, pa.planesA, pa.hA, pa.wA, pa.N, true, next_ctx(hd, "fft.b"),
+                                            &pa.vA)) != hipSuccess) return hip_fail(hd, e);
         }
     }
     // bprop: GX = GY . W ; accGrad: GW = conj(GY) . X  (operand A of both plans is GYF)
     if (gx && gw) {
         const GemmProblem qb = gemm_problem(pb, GYF, WF, GXF), qa = gemm_problem(pa, GYFa, XF, GWF);
-        if (cgemm_pair_supported(qb, qa)) {
+        if (cgemm_pair_supported(qb, qa, &hd->sw)) {
             // both contractions in one launch, then the two inverse transforms
             // (the one with the longer reduction first: its workgroups run longest)
             const bool a_first = pa.K >= pb.K;
-            if ((e = launch_cgemm_pair(a_first ? qa : qb, a_first ? qb : qa, next_ctx(hd))) != hipSuccess) return hip_fail(hd, e);
+            if ((e = launch_cgemm_pair(a_first ? qa : qb, a_first ? qb : qa, next_ctx(hd, "contraction.pair"))) != hipSuccess) return hip_fail(hd, e);
             if ((e = invert_pair(hd, pb, GXF, gx, pa, GWF, gw, scale, accumulate)) != hipSuccess) return hip_fail(hd, e);
             return FFTCONV_OK;
         }
@@ -879,11 +959,11 @@ int fft_conv_transform_weights(fftconv_handle hd, const float *wt, void *wf, siz
                                int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w) {
     if (!hd || !wt || !wf) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(FFTCONV_FPROP, 1, f, fo, h, w, kh, kw, &p, -1, pad_h, pad_w);
+    int rc = cached_plan(hd, FFTCONV_FPROP, 1, f, fo, h, w, kh, kw, &p, -1, pad_h, pad_w);
     if (rc != FFTCONV_OK) return rc;
     if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
     hd->nk = 0;
-    hipError_t e = transform(p, wt, static_cast<float *>(wf), p.planesB, p.hB, p.wB, next_ctx(hd));
+    hipError_t e = transform(p, wt, static_cast<float *>(wf), p.planesB, p.hB, p.wB, next_ctx(hd, "fft.b"));
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
 
@@ -903,12 +983,12 @@ int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size
                          int S, int f, int fo, int h, int w, int kh, int kw) {
     if (!hd || !x || !wf || !y) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
+    int rc = cached_plan(hd, FFTCONV_FPROP, S, f, fo, h, w, kh, kw, &p);
     if (rc != FFTCONV_OK) return rc;
     if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
     if (p.tiled || p.rect || !fused_fprop_supported(p.N, f, fo, static_cast<const float *>(wf))) return FFTCONV_UNSUPPORTED;
     hd->nk = 0;
-    const hipError_t e = launch_fused_fprop(x, static_cast<const float *>(wf), y, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd));
+    const hipError_t e = launch_fused_fprop(x, static_cast<const float *>(wf), y, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd, "fused"));
     if (e == hipErrorInvalidValue) return FFTCONV_UNSUPPORTED;   // the layer's planes do not fit the kernel's LDS plan
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }
@@ -917,12 +997,12 @@ int fft_conv_bprop_fused(fftconv_handle hd, const float *gy, const void *wf, siz
                          int S, int f, int fo, int h, int w, int kh, int kw) {
     if (!hd || !gy || !wf || !gx) return FFTCONV_INVALID_ARG;
     PassPlan p;
-    int rc = make_plan(FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &p);
+    int rc = cached_plan(hd, FFTCONV_BPROP, S, f, fo, h, w, kh, kw, &p);
     if (rc != FFTCONV_OK) return rc;
     if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
     if (p.tiled || p.rect || !fused_bprop_supported(p.N, f, fo, static_cast<const float *>(wf))) return FFTCONV_UNSUPPORTED;
     hd->nk = 0;
-    const hipError_t e = launch_fused_bprop(gy, static_cast<const float *>(wf), gx, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd));
+    const hipError_t e = launch_fused_bprop(gy, static_cast<const float *>(wf), gx, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd, "fused"));
     if (e == hipErrorInvalidValue) return FFTCONV_UNSUPPORTED;   // the layer's planes do not fit the kernel's LDS plan
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }

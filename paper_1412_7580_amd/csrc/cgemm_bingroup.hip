@@ -207,9 +207,7 @@ static hipError_t dispatch_bg(int shape, const GemmParams &prm, LaunchCtx st) {
 
 // Per-wave tile (rows x cols of one bin): 0 32x32, 1 32x64, 2 64x32, 3 64x64.
 hipError_t launch_cgemm_bingroup(const GemmParams &prm, bool akf, bool bkf, LaunchCtx st) {
-    int shape;
-    if (const char *e = getenv("FFTCONV_BG_TILE")) shape = atoi(e);
-    else shape = 0;   // measured fastest for every pass of the 64-basis layer
+    const int shape = st.sw ? st.sw->bg_tile : 0;   // 0 measured fastest for every pass of the 64-basis layer
     if (akf && bkf) return dispatch_bg<true, true>(shape, prm, st);
     if (akf && !bkf) return dispatch_bg<true, false>(shape, prm, st);
     if (!akf && !bkf) return dispatch_bg<false, false>(shape, prm, st);

@@ -555,13 +555,24 @@ static hipError_t dispatch_tile(int shape, GemmParams prm, LaunchCtx st) {
 
 hipError_t launch_cgemm_bingroup(const GemmParams &prm, bool akf, bool bkf, LaunchCtx st);
 
-static int pick_tile() {
-    if (const char *e = getenv("FFTCONV_GEMM_TILE")) return atoi(e);
-    // 64x64 tiles on four waves with one tile of register staging ahead measured fastest for
-    // every layer shape tried (more workgroups in flight beat the larger tiles' operand
-    // reuse and the deeper staging's registers).
-    return 3;
+GemmSwitches read_gemm_switches() {
+    GemmSwitches s;
+    auto on = [](const char *name) { const char *e = getenv(name); return e && atoi(e) != 0; };
+    if (const char *e = getenv("FFTCONV_GEMM_TILE")) s.tile = atoi(e);
+    s.no_tail = on("FFTCONV_GEMM_NO_TAIL");
+    s.no_pair = on("FFTCONV_GEMM_NO_PAIR");
+    s.no_bingroup = on("FFTCONV_GEMM_NO_BINGROUP");
+    s.no_fast = on("FFTCONV_GEMM_NO_FAST");
+    if (const char *e = getenv("FFTCONV_BG_TILE")) s.bg_tile = atoi(e);
+    return s;
 }
+static const GemmSwitches kDefaultSwitches{};
+static const GemmSwitches &switches_of(const GemmSwitches *sw) { return sw ? *sw : kDefaultSwitches; }
+
+// 64x64 tiles on four waves with one tile of register staging ahead (shape 3) measured fastest
+// for every layer shape tried (more workgroups in flight beat the larger tiles' operand reuse
+// and the deeper staging's registers).
+static int pick_tile(const GemmSwitches &sw) { return sw.tile >= 0 ? sw.tile : 3; }
 
 // Fast addressing of an operand (see TileLoader::prepare_fast): one index of the matrix is the
 // contiguous plane index, the other moves `stride` planes per step.  When that stride is a
@@ -583,7 +594,7 @@ struct Prepared {
 };
 
 static hipError_t prepare(const GemmOperand &A, const GemmOperand &B, float *C, FreqLayout layC, long C_rs,
-                          long C_cs, int M, int N, int K, int bins, Prepared *out) {
+                          long C_cs, int M, int N, int K, int bins, const GemmSwitches &sw, Prepared *out) {
     if (bins % kXcds != 0) return hipErrorInvalidValue;   // N*(N/2+1) with N >= 8 always is
     GemmParams &prm = out->prm;
     prm.A = A.ptr; prm.B = B.ptr; prm.C = C;
@@ -606,12 +617,10 @@ static hipError_t prepare(const GemmOperand &A, const GemmOperand &B, float *C, 
     out->akf = akf; out->bkf = bkf; out->vec = va && vb;
     prm.fast = (out->vec && fast_addressing(A.lay, akf ? A.rs : A.cs, bins) &&
                 fast_addressing(B.lay, bkf ? B.cs : B.rs, bins) && C_cs == 1 && fast_addressing(layC, C_rs, bins) &&
-                !getenv("FFTCONV_GEMM_NO_FAST")) ? 1 : 0;
+                !sw.no_fast) ? 1 : 0;
     // Layouts with runs of 4 planes (basis 64) put four bins in every 128-byte line: the
     // bin-group kernel loads whole lines and multiplies the four bins side by side.
-    const char *no_bg_env = getenv("FFTCONV_GEMM_NO_BINGROUP");
-    const bool no_bg = no_bg_env && atoi(no_bg_env);
-    out->bingroup = out->vec && !no_bg && A.lay.tsh == 2 && B.lay.tsh == 2 && layC.tsh == 2 &&
+    out->bingroup = out->vec && !sw.no_bingroup && A.lay.tsh == 2 && B.lay.tsh == 2 && layC.tsh == 2 &&
                     bins % (4 * kXcds) == 0 && (akf || A.rs == 1) && (bkf || B.cs == 1) && C_cs == 1 &&
                     C_rs % 4 == 0 && N % 4 == 0 && ((size_t)C & 15) == 0;
     return hipSuccess;
@@ -642,9 +651,10 @@ static hipError_t run_tail(GemmParams prm, long full, long rem, LaunchCtx st) {
 
 static hipError_t launch_prepared(const Prepared &q, LaunchCtx st) {
     const GemmParams &prm = q.prm;
+    const GemmSwitches &sw = switches_of(st.sw);
     if (q.bingroup) return launch_cgemm_bingroup(prm, q.akf, q.bkf, st);
-    const int shape = pick_tile();
-    if (q.vec && shape == 3 && !getenv("FFTCONV_GEMM_TILE") && !getenv("FFTCONV_GEMM_NO_TAIL")) {
+    const int shape = pick_tile(sw);
+    if (q.vec && shape == 3 && sw.tile < 0 && !sw.no_tail) {
         // a short last round (at most a quarter of the resident workgroups): split its tiles
         GemmParams p2 = prm;
         p2.tiles_m = (p2.M + 63) / 64; p2.tiles_n = (p2.N + 63) / 64;
@@ -672,7 +682,7 @@ static hipError_t launch_prepared(const Prepared &q, LaunchCtx st) {
 hipError_t launch_cgemm_bins(GemmOperand A, GemmOperand B, float *C, FreqLayout layC, long C_rs,
                              long C_cs, int M, int N, int K, int bins, LaunchCtx st) {
     Prepared q;
-    if (hipError_t e = prepare(A, B, C, layC, C_rs, C_cs, M, N, K, bins, &q); e != hipSuccess) return e;
+    if (hipError_t e = prepare(A, B, C, layC, C_rs, C_cs, M, N, K, bins, switches_of(st.sw), &q); e != hipSuccess) return e;
     return launch_prepared(q, st);
 }
 
@@ -690,7 +700,7 @@ static hipError_t run_pair(GemmPairParams &pp, LaunchCtx st) {
     // its tiles into quadrants (the 27x27 layer on basis 28: 424 + 848 workgroups, 248 left over)
     const long slots = resident_workgroups(), rem = (n1 + n2) % slots, full = n1 + n2 - rem;
     long split = n2;
-    if (!getenv("FFTCONV_GEMM_NO_TAIL") && full > 0 && rem > 0 && 4 * rem <= slots && rem <= n2 && rem % kXcds == 0 &&
+    if (!switches_of(st.sw).no_tail && full > 0 && rem > 0 && 4 * rem <= slots && rem <= n2 && rem % kXcds == 0 &&
         (n2 - rem) % kXcds == 0)
         split = n2 - rem;
     pp.split2 = (unsigned)split;
@@ -709,19 +719,21 @@ static hipError_t pair_second(const Prepared &q2, GemmPairParams &pp, LaunchCtx 
     return run_pair<AKF1, BKF1, false, true>(pp, st);
 }
 
-bool cgemm_pair_supported(const GemmProblem &g1, const GemmProblem &g2) {
-    if (getenv("FFTCONV_GEMM_TILE")) return false;       // A/B runs of single-kernel shapes
-    if (const char *e = getenv("FFTCONV_GEMM_NO_PAIR")) if (atoi(e)) return false;
+bool cgemm_pair_supported(const GemmProblem &g1, const GemmProblem &g2, const GemmSwitches *swp) {
+    const GemmSwitches &sw = switches_of(swp);
+    if (sw.tile >= 0) return false;       // A/B runs of single-kernel shapes
+    if (sw.no_pair) return false;
     Prepared q1, q2;
-    if (prepare(g1.A, g1.B, g1.C, g1.layC, g1.C_rs, g1.C_cs, g1.M, g1.N, g1.K, g1.bins, &q1) != hipSuccess) return false;
-    if (prepare(g2.A, g2.B, g2.C, g2.layC, g2.C_rs, g2.C_cs, g2.M, g2.N, g2.K, g2.bins, &q2) != hipSuccess) return false;
+    if (prepare(g1.A, g1.B, g1.C, g1.layC, g1.C_rs, g1.C_cs, g1.M, g1.N, g1.K, g1.bins, sw, &q1) != hipSuccess) return false;
+    if (prepare(g2.A, g2.B, g2.C, g2.layC, g2.C_rs, g2.C_cs, g2.M, g2.N, g2.K, g2.bins, sw, &q2) != hipSuccess) return false;
     return q1.vec && q2.vec && !q1.bingroup && !q2.bingroup;
 }
 
 hipError_t launch_cgemm_pair(const GemmProblem &g1, const GemmProblem &g2, LaunchCtx st) {
     Prepared q1, q2;
-    if (hipError_t e = prepare(g1.A, g1.B, g1.C, g1.layC, g1.C_rs, g1.C_cs, g1.M, g1.N, g1.K, g1.bins, &q1); e != hipSuccess) return e;
-    if (hipError_t e = prepare(g2.A, g2.B, g2.C, g2.layC, g2.C_rs, g2.C_cs, g2.M, g2.N, g2.K, g2.bins, &q2); e != hipSuccess) return e;
+    const GemmSwitches &sw = switches_of(st.sw);
+    if (hipError_t e = prepare(g1.A, g1.B, g1.C, g1.layC, g1.C_rs, g1.C_cs, g1.M, g1.N, g1.K, g1.bins, sw, &q1); e != hipSuccess) return e;
+    if (hipError_t e = prepare(g2.A, g2.B, g2.C, g2.layC, g2.C_rs, g2.C_cs, g2.M, g2.N, g2.K, g2.bins, sw, &q2); e != hipSuccess) return e;
     if (!(q1.vec && q2.vec) || q1.bingroup || q2.bingroup) return hipErrorInvalidValue;
     GemmPairParams pp;
     pp.p1 = q1.prm; pp.p2 = q2.prm; pp.n1 = 0;

@@ -9,9 +9,20 @@ namespace fc {
 // Where a kernel is launched and, optionally, a pair of events that the runtime attaches to
 // that one dispatch (their elapsed time is the kernel's own execution time, without the gaps
 // that events recorded between launches would include).
+// Switches of the contraction for A/B runs (environment variables FFTCONV_GEMM_TILE, _NO_TAIL,
+// _NO_PAIR, _NO_BINGROUP, _NO_FAST and FFTCONV_BG_TILE), read once when a handle is created; none
+// changes a result beyond rounding.  All off by default.
+struct GemmSwitches {
+    int tile = -1;          // 0..5: another tile shape, single kernels only; -1: the default
+    bool no_tail = false, no_pair = false, no_bingroup = false, no_fast = false;
+    int bg_tile = 0;        // per-wave tile of the four-bins-per-line kernel
+};
+GemmSwitches read_gemm_switches();
+
 struct LaunchCtx {
     hipStream_t stream;
     hipEvent_t start, stop;
+    const GemmSwitches *sw = nullptr;   // contraction launches: the handle's switches (nullptr: defaults)
 };
 
 template <class K, class P>
@@ -162,7 +173,7 @@ struct GemmProblem {
     long C_rs, C_cs;
     int M, N, K, bins;
 };
-bool cgemm_pair_supported(const GemmProblem &g1, const GemmProblem &g2);
+bool cgemm_pair_supported(const GemmProblem &g1, const GemmProblem &g2, const GemmSwitches *sw = nullptr);
 hipError_t launch_cgemm_pair(const GemmProblem &g1, const GemmProblem &g2, LaunchCtx st);
 
 }  // namespace fc

@@ -211,10 +211,11 @@ def test_reuse_at_c2(hd, named):
 
 @pytest.mark.parametrize("name", ["C3", "C4"])
 def test_reuse_equals_separate_passes_at_full_size(hd, name):
-    """The two-call step at the full size of the larger configurations (the launch
-    configuration the benchmark times, with both backward contractions in one launch where
-    that applies) against the three independent passes, which the tests above check against
-    the oracle.  Same transforms and the same products; only the order in which a contraction
+    """The two-call step at the full size of the larger configurations on the library's own
+    basis (14 and 64; both backward contractions in one launch where that applies) against the
+    three independent passes, which the tests above check against the oracle (the step on the
+    named bases, which the benchmark times, is checked against the oracle itself in
+    test_bench_step_against_oracle_at_full_size).  Same transforms and the same products; only the order in which a contraction
     sums over k may differ (a lone contraction may split the tiles of a short last round of
     workgroups over its waves), so the results agree to rounding, far inside the 1e-4 bound."""
     import torch
@@ -233,6 +234,40 @@ def test_reuse_equals_separate_passes_at_full_size(hd, name):
     assert close(gw, hd.fft_conv_accgrad(dx, dgy))
 
 
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_bench_step_against_oracle_at_full_size(hd, name):
+    """The launch configuration bench.py times, against the oracle: fft_conv_fprop_save_tiled +
+    fft_conv_backward_tiled at full size on the Fourier basis the configuration names (16 for
+    the 13x13 layer, 64 for the 64x64 one).  The 13x13 layer is compared over the whole of y, gx
+    and gw; for the 64x64 layer the oracle evaluates a seeded sample of output planes, all pixels
+    of each, first and last plane included (256 planes of y and of gx, 1024 of gw)."""
+    import torch
+    cfg = {k: v for k, v in synth.CONV_CONFIGS[name].items() if k not in ("passes", "N")}
+    n = synth.CONV_CONFIGS[name]["N"]
+    x, w, gy = synth.conv_inputs(seed=synth.CONV_SEEDS[name], **cfg)
+    dx, dw, dgy = _dev(x), _dev(w), _dev(gy)
+    S, f, fo, h, wd, kh, kw = (cfg[k] for k in ("S", "f", "fo", "h", "w", "kh", "kw"))
+    saved = torch.empty(hd.saved_bytes_tiled(S, f, fo, h, wd, kh, kw, n) // 4, device="cuda", dtype=torch.float32)
+    y = _np(hd.fft_conv_fprop_save_tiled(dx, dw, n, saved))
+    gx, gw = hd.fft_conv_backward_tiled(dgy, saved, f, h, wd, kh, kw, n)
+    gx, gw = _np(gx), _np(gw)
+    if name == "C3":
+        assert _relerr(y, oracle.conv_fprop(x, w)) <= TOL
+        assert _relerr(gx, oracle.conv_bprop(gy, w, h, wd)) <= TOL
+        assert _relerr(gw, oracle.conv_accgrad(x, gy)) <= TOL
+        return
+    rng = np.random.default_rng(11)
+
+    def sample(planes, k):
+        return np.unique(np.concatenate([[0, planes - 1], rng.choice(planes, size=k - 2, replace=False)]))
+    sel = sample(S * fo, 256)
+    assert _relerr(y.reshape(S * fo, h - kh + 1, wd - kw + 1)[sel], oracle.conv_fprop(x, w, sel)) <= TOL
+    sel = sample(S * f, 256)
+    assert _relerr(gx.reshape(S * f, h, wd)[sel], oracle.conv_bprop(gy, w, h, wd, sel)) <= TOL
+    sel = sample(fo * f, 1024)
+    assert _relerr(gw.reshape(fo * f, kh, kw)[sel], oracle.conv_accgrad(x, gy, sel)) <= TOL
+
+
 def test_saved_buffer_too_small(hd, lib):
     import torch
     cfg = dict(S=2, f=3, fo=4, h=9, w=9, kh=3, kw=3)
@@ -247,7 +282,7 @@ def test_saved_buffer_too_small(hd, lib):
 @pytest.mark.parametrize("cfg", [dict(S=128, f=64, fo=64, h=27, w=27, kh=5, kw=5),      # basis 28, 64x64 tiles + split tail
                                  dict(S=70, f=32, fo=96, h=13, w=13, kh=3, kw=3),       # basis 14, ragged M
                                  dict(S=8, f=64, fo=32, h=8, w=8, kh=3, kw=3)])         # basis 8: 64 planes per tile
-def test_contraction_addressing_paths_agree(hd, cfg, monkeypatch):
+def test_contraction_addressing_paths_agree(hd, lib, cfg, monkeypatch):
     """The contraction splits its gather / store addresses into a uniform and a per-lane part
     when every strided index moves in whole plane tiles; the general index arithmetic must
     give bit-identical results (same loads, same order of summation)."""
@@ -257,13 +292,18 @@ def test_contraction_addressing_paths_agree(hd, cfg, monkeypatch):
     dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
     saved = torch.empty(hd.saved_bytes(*dims) // 4, device="cuda")
 
-    def run():
+    def run(hd):
         y = hd.fft_conv_fprop_save(dx, dw, saved).clone()
         gx, gw = hd.fft_conv_backward(dgy, saved, cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
         return y, gx.clone(), gw.clone(), hd.fft_conv_bprop(dgy, dw, cfg["h"], cfg["w"]).clone()
-    fast = run()
+    fast = run(hd)
     monkeypatch.setenv("FFTCONV_GEMM_NO_FAST", "1")
-    general = run()
+    hd2 = lib.Handle(0)      # the switches are read from the environment when a handle is created
+    try:
+        general = run(hd2)
+        torch.cuda.synchronize()
+    finally:
+        hd2.close()
     for a, b in zip(fast, general):
         assert torch.equal(a, b)
     ref = oracle.conv_fprop(x, w)

@@ -95,6 +95,33 @@ def test_c2r_2d(hd, n, B):
         assert _relerr(got, oracle.idft_c2r_2d(X, n, h_out, w_out)) <= TOL, (h_out, w_out)
 
 
+def _random_real_signal_spectrum(seed, B, n):
+    """A random complex half spectrum [B, n, n/2+1] that is the transform of SOME real n x n
+    signal without being computed from one: columns 0 < k2 < n/2 are free; the two
+    self-conjugate columns k2 = 0 and k2 = n/2 are made Hermitian along k1
+    (X[k1] = conj(X[n - k1]), real at k1 = 0 and n/2), which is the precondition of the 2-D
+    inverse."""
+    X = synth.normal01(seed, 0, (B, n, n // 2 + 1)) + 1j * synth.normal01(seed, 1, (B, n, n // 2 + 1))
+    for k2 in (0, n // 2):
+        col = X[:, :, k2]
+        col = 0.5 * (col + np.conj(col[:, (-np.arange(n)) % n]))
+        X[:, :, k2] = col
+    return X.astype(np.complex64).astype(np.complex128)
+
+
+@pytest.mark.parametrize("n", [8, 12, 16, 28, 32, 64, 128])
+def test_c2r_2d_symmetrised_random_spectrum(hd, n):
+    """2-D inverse of spectra that no forward transform produced: random bins, with only the
+    columns k2 = 0 and n/2 symmetrised along k1 as the header requires.  (Without that symmetry
+    the result is unspecified: the kernel packs the two columns into one complex line on the
+    assumption that their column-inverse is real, while the oracle drops the imaginary part.)"""
+    B = 9
+    X = _random_real_signal_spectrum(31, B, n)
+    for (h_out, w_out) in [(n, n), (n - 3, n - 3), (5, n)]:
+        got = hd.fft_c2r_2d(_cdev(X), n, h_out, w_out).cpu().numpy().astype(np.float64)
+        assert _relerr(got, oracle.idft_c2r_2d(X, n, h_out, w_out)) <= TOL, (h_out, w_out)
+
+
 @pytest.mark.parametrize("dim", [1, 2])
 @pytest.mark.parametrize("n", POW2)
 def test_sweep_roundtrip_subset(hd, dim, n):
