@@ -181,17 +181,24 @@ __device__ __forceinline__ int group_block(int g) {
 // of a group must be active together.  The cross-lane part is one (G = 2) or two (G = 4)
 // radix-2 decimation-in-time steps: the upper lane of each pair multiplies by the step's
 // twiddle, the pair swaps values through DPP and forms sum / difference.
-template <int L, int G, int DIR>
+// HALF (lane pairs only): the result is scaled by 1/2, at no cost: the factor goes into the
+// twiddles of the cross-lane step, whose product every lane forms anyway.
+template <int L, int G, int DIR, bool HALF = false>
 __device__ __forceinline__ void fft_group(float (&re)[L], float (&im)[L], int g) {
     static_assert(G == 1 || G == 2 || G == 4 || G == 8, "one, two, four or eight lanes per line");
+    static_assert(!HALF || G == 2, "the free scaling exists for lane pairs");
+    constexpr double SCALE = HALF ? 0.5 : 1.0;
     fft_leaf<L, DIR>(re, im);
     if constexpr (G == 2) {
-        const float sgn = g ? -1.0f : 1.0f;
+        float sgn = g ? -1.0f : 1.0f;
+        // (opaque to the compiler: knowing that it is +-1 it would form both the sum and the
+        // difference and select between them, three instructions where a product and a sum do)
+        asm volatile("" : "+v"(sgn));
         static_for<0, L>([&](auto kk) {
             constexpr int k = decltype(kk)::value;
             constexpr cplx_d w = unit_root(DIR * k, 2 * L);
-            constexpr float cr = (float)w.re, ci = (float)w.im;
-            const float wr = g ? cr : 1.0f, wi = g ? ci : 0.0f;
+            constexpr float cr = (float)(SCALE * w.re), ci = (float)(SCALE * w.im), one = (float)SCALE;
+            const float wr = g ? cr : one, wi = g ? ci : 0.0f;
             const float tr = wr * re[k] - wi * im[k];
             const float ti = wr * im[k] + wi * re[k];
             const float qr = lane_xor1(tr), qi = lane_xor1(ti);
@@ -339,11 +346,17 @@ __device__ __forceinline__ void fft_group_lds(float (&re)[L], float (&im)[L], in
 
 // The line transform as the kernels call it: lines of four or eight lanes take their twiddles
 // from the table at `tw` in LDS, the others have them as immediates.
-template <int L, int G, int DIR>
+template <int L, int G, int DIR, bool HALF = false>
 __device__ __forceinline__ void fft_lines(float (&re)[L], float (&im)[L], int g, const float *tw) {
     if constexpr (kLdsTwiddles<G>) fft_group_lds<L, G, DIR>(re, im, g, reinterpret_cast<const float2 *>(tw) + g);
-    else fft_group<L, G, DIR>(re, im, g);
+    else fft_group<L, G, DIR, HALF>(re, im, g);
 }
+
+// Whether the forward 2-D kernels move the factor 1/2 of the two-for-one split of their row phase
+// into the column transform (lane pairs: see fft_group's HALF).  The row phase then leaves twice
+// the row spectra, the column phase halves them again; results are unchanged bit for bit,
+// since halving is exact.
+template <int G> constexpr bool kDeferHalf = G == 2;
 
 // Number of registers of split spectrum a lane keeps (see split_two_real).
 template <int L, int G> struct SplitRegs { static constexpr int A = (G == 1) ? L / 2 : L, B = (G == 1) ? L / 2 : 1; };
@@ -376,12 +389,14 @@ __device__ __forceinline__ int split_slot(int g, int k) {
 //   G == 1: are/aim[k], bre/bim[k] for k < NH are slot k of a and of b.
 //   G  > 1: even lanes get line a, odd lanes line b; register k holds slot split_slot(g, k).
 //           Both are returned in are/aim.
-template <int L, int G>
+// TWICE: leave out the factor 1/2 (the spectra come out doubled; G > 1 only).
+template <int L, int G, bool TWICE = false>
 __device__ __forceinline__ void split_two_real(const float (&re)[L], const float (&im)[L], int g,
                                                float (&are)[SplitRegs<L, G>::A],
                                                float (&aim)[SplitRegs<L, G>::A],
                                                float (&bre)[SplitRegs<L, G>::B],
                                                float (&bim)[SplitRegs<L, G>::B]) {
+    static_assert(!TWICE || G == 2, "the doubled split is used with lane pairs only");
     if constexpr (G == 1) {
         constexpr int NH = L / 2;
         are[0] = re[0]; aim[0] = re[NH];
@@ -399,8 +414,9 @@ __device__ __forceinline__ void split_two_real(const float (&re)[L], const float
         {   // register 0: bins 0, N/2 (and N/4, 3N/4 for G = 4) pair up with the neighbour lane
             const float o0r = lane_xor1(re[0]), o0i = lane_xor1(im[0]);
             if constexpr (G == 2) {
-                are[0] = odd ? o0i : re[0];
-                aim[0] = odd ? im[0] : o0r;
+                constexpr float two = TWICE ? 2.0f : 1.0f;
+                are[0] = two * (odd ? o0i : re[0]);
+                aim[0] = two * (odd ? im[0] : o0r);
             } else if constexpr (G == 4) {
                 const float a_r = 0.5f * (re[0] + o0r), a_i = 0.5f * (im[0] - o0i);
                 const float b_r = 0.5f * (o0i + im[0]), b_i = 0.5f * (re[0] - o0r);
@@ -426,8 +442,9 @@ __device__ __forceinline__ void split_two_real(const float (&re)[L], const float
             if constexpr (G == 2) { orr = lane_xor1(re[L - k]); oi = lane_xor1(im[L - k]); }
             else if constexpr (G == 4) { orr = lane_xor3(re[L - k]); oi = lane_xor3(im[L - k]); }
             else { orr = lane_xor7(re[L - k]); oi = lane_xor7(im[L - k]); }
-            const float a_r = 0.5f * (re[k] + orr), a_i = 0.5f * (im[k] - oi);
-            const float b_r = 0.5f * (oi + im[k]), b_i = 0.5f * (re[k] - orr);
+            constexpr float h = TWICE ? 1.0f : 0.5f;
+            const float a_r = h * (re[k] + orr), a_i = h * (im[k] - oi);
+            const float b_r = h * (oi + im[k]), b_i = h * (re[k] - orr);
             are[k] = odd ? b_r : a_r;
             aim[k] = odd ? b_i : a_i;
         });

@@ -130,11 +130,15 @@ __device__ __forceinline__ void unstage_linear(float *dst, const float *src, uns
 // Copy a contiguous block of `rows` rows of w floats (consecutive planes of h rows each) into
 // an LDS image with padded strides (row stride rs, plane stride ps), V floats per load
 // (V divides w; the block start is V*4-byte aligned).  Batched like stage_linear.
-template <int BT, int V>
+// FPL: floats per lane of the largest block the kernel can be given (2 N / G).  The batch is
+// sized so that such a block is in flight as ONE batch of up to sixteen loads per lane (four
+// 64 x 64 planes on 256 lanes: sixteen 16-byte loads): a second batch would wait for the first
+// one's round trip to memory before it is even issued.
+template <int BT, int V, int FPL>
 __device__ __forceinline__ void stage_padded(float *dst, const float *src, unsigned rows, unsigned w,
                                              unsigned h, unsigned rs, unsigned ps, MagicDiv div_wv,
                                              MagicDiv div_h, int tid) {
-    constexpr int U = (V == 1) ? 8 : 6;
+    constexpr int U = FPL / V < 4 ? 4 : (FPL / V > 16 ? 16 : FPL / V);
     typedef float vec_t __attribute__((ext_vector_type(V)));
     const unsigned wv = w / V, total = rows * wv;
     const vec_t *sv = reinterpret_cast<const vec_t *>(src);
@@ -277,6 +281,17 @@ struct Fwd2dParams {
     PlaneView view;
 };
 
+// How the forward kernels write the plane-tiled layout.  With runs of 16 planes or more a lane's
+// 4-byte stores fill whole 64-byte segments.  With short runs (8 planes at basis 32, 4 from 36 on)
+// the same stores are 16- or 32-byte pieces at twice that stride, half of every 64-byte request
+// empty, and the time goes into issuing them: on the 64-basis layer the stores were 40 % of the
+// weight transform's time (85 us with, 52 us without them; a plain fill of as many bytes takes
+// 43).  There the two lanes of a pair swap halves, so that one instruction writes the real and
+// the imaginary run of a bin side by side (85 -> 74 us; assembling the block in LDS and writing it
+// with linear 16-byte stores, in halves to keep the occupancy, came to 76 and cost the smaller
+// transforms 10 .. 25 %).
+template <int G, int T> constexpr bool kPairedStores = (G > 1) && (T <= 8);
+
 // Store helpers for the two output layouts.  `base` is uniform over the workgroup (block
 // or LDS image start) and the lane's part of the address is a 32-bit element offset, so that a
 // store costs one 32-bit add instead of 64-bit pointer arithmetic.
@@ -334,12 +349,13 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
             stage_linear<BT>(sin, src, (unsigned)np * hw, tid, true);
         } else {
             const unsigned rows = (unsigned)np * h_in;
+            constexpr int FPL = 2 * N / G;
             if (prm.vecw == 4)
-                stage_padded<BT, 4>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+                stage_padded<BT, 4, FPL>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
             else if (prm.vecw == 2)
-                stage_padded<BT, 2>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+                stage_padded<BT, 2, FPL>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
             else
-                stage_padded<BT, 1>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+                stage_padded<BT, 1, FPL>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
         }
     }
     __syncthreads();
@@ -366,7 +382,7 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
             im[m] = (in && hasb) ? pb[j] : 0.0f;
         }
         fft_lines<L, G, -1>(re, im, g, smem + prm.tw_off);
-        split_two_real<L, G>(re, im, g, are, aim, bre, bim);
+        split_two_real<L, G, kDeferHalf<G>>(re, im, g, are, aim, bre, bim);   // (doubled: halved in the column phase)
     }
     __syncthreads();   // every lane has read its rows; the staging area may be overwritten
     if (row_active) {
@@ -406,7 +422,7 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
             if (r < h_in) v = mp[r * MRS];
             re[m] = v.x; im[m] = v.y;
         }
-        fft_lines<L, G, -1>(re, im, cg, smem + prm.tw_off);
+        fft_lines<L, G, -1, kDeferHalf<G>>(re, im, cg, smem + prm.tw_off);
     }
 
     // Results go either straight to global memory or, when OSTAGE, into an LDS image of the
@@ -424,8 +440,25 @@ __device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned 
 
     if (col_active) {
         if (cc != 0) {
+            if constexpr (CONV && !OSTAGE && kPairedStores<G, T>) {
+                // The two lanes of a pair (cg, cg ^ 1) hold the same bins k2 of two different rows.
+                // They swap halves: the even lane writes the real parts of both rows, the odd lane
+                // the imaginary parts, so that one store instruction fills the real and the
+                // imaginary run of a bin, and with the neighbouring columns whole 64-byte segments.
+                const bool odd = (cg & 1) != 0;
+                const int row_e = L * group_block<G>(cg & ~1), row_o = L * group_block<G>(cg | 1);
+                float *pe = st.base + st.lane_off + (unsigned)(((row_e * NB + cc) * 2 + (odd ? 1 : 0)) * T);
+                float *po = st.base + st.lane_off + (unsigned)(((row_o * NB + cc) * 2 + (odd ? 1 : 0)) * T);
 #pragma unroll
-            for (int k = 0; k < L; ++k) st(k + L * group_block<G>(cg), cc, re[k], im[k]);
+                for (int k = 0; k < L; ++k) {
+                    const float got = lane_xor1(odd ? re[k] : im[k]);
+                    pe[(k * NB * 2) * T] = odd ? got : re[k];
+                    po[(k * NB * 2) * T] = odd ? im[k] : got;
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < L; ++k) st(k + L * group_block<G>(cg), cc, re[k], im[k]);
+            }
         } else {
             float ur[NA], ui[NA], vr[NBR], vi[NBR];
             split_two_real<L, G>(re, im, cg, ur, ui, vr, vi);

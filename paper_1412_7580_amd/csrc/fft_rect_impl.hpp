@@ -57,11 +57,11 @@ __device__ __forceinline__ void fft2d_r2c_rect_body(const RectFwdParams &prm, un
         } else {
             const unsigned rows = (unsigned)np * h_in;
             if (prm.vecw == 4)
-                stage_padded<BT, 4>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+                stage_padded<BT, 4, 24>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
             else if (prm.vecw == 2)
-                stage_padded<BT, 2>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+                stage_padded<BT, 2, 12>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
             else
-                stage_padded<BT, 1>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
+                stage_padded<BT, 1, 8>(sin, src, rows, w_in, h_in, prm.RS, prm.IPS, prm.div_wv, prm.div_h, tid);
         }
     }
     __syncthreads();
