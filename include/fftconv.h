@@ -237,6 +237,8 @@ int fft_conv_backward_tiled(fftconv_handle hd, const float *gy, float *gx, float
  * fft_conv_fprop(_padded) / fft_conv_bprop(_padded) with one forward transform instead of two.
  * The transform may run on another handle and stream than the passes (the caller orders
  * them).  Workspace as for the ordinary passes; a short wf gives FFTCONV_WORKSPACE_TOO_SMALL.
+ * Small layers (those fft_conv_fprop_fused / fft_conv_bprop_fused support, up to 512 samples)
+ * run as one launch by themselves and then touch no workspace.
  */
 size_t fftconv_weights_bytes(int f, int fo, int h, int w, int kh, int kw, int pad_h, int pad_w);
 int fft_conv_transform_weights(fftconv_handle hd, const float *wt, void *wf, size_t wf_bytes,

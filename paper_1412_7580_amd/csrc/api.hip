@@ -455,6 +455,22 @@ static int run_pass_weights(fftconv_ctx *c, int pass, const float *opA, const vo
     int rc = cached_plan(c, pass, S, f, fo, h, w, kh, kw, &p, -1, ph, pw);
     if (rc != FFTCONV_OK) return rc;
     if (wf_bytes < align_up(p.lay.floats(p.planesB) * sizeof(float), 256)) return FFTCONV_WORKSPACE_TOO_SMALL;
+    // Latency-bound layers (a few dozen small planes) run as ONE launch: three launches of a few
+    // microseconds each cost more than their arithmetic (Section 6 plans such an integration).
+    // The one-launch kernels carry one sample per workgroup, so they pay while the samples are a
+    // single round of workgroups.
+    if (!p.tiled && !p.rect && ph == 0 && pw == 0 && S <= 512) {
+        const float *wff = static_cast<const float *>(wf);
+        const bool ok = pass == FFTCONV_FPROP ? fused_fprop_supported(p.N, f, fo, wff) : fused_bprop_supported(p.N, f, fo, wff);
+        if (ok) {
+            c->nk = 0;
+            const hipError_t e = pass == FFTCONV_FPROP
+                                     ? launch_fused_fprop(opA, wff, out, S, f, fo, h, w, kh, kw, p.N, next_ctx(c, "fused"))
+                                     : launch_fused_bprop(opA, wff, out, S, f, fo, h, w, kh, kw, p.N, next_ctx(c, "fused"));
+            if (e == hipSuccess) return FFTCONV_OK;
+            if (e != hipErrorInvalidValue) return hip_fail(c, e);   // (invalid value: the planes do not fit the kernel's LDS plan)
+        }
+    }
     if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     float *AF = at(ws, p.offA), *CF = at(ws, p.offC);
     c->nk = 0;
