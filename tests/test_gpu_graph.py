@@ -67,22 +67,25 @@ def test_graph_replay_equals_eager(hd, lib, cfg):
 
 
 def test_graph_replay_of_inference_paths(hd, lib):
-    """fprop on weights transformed ahead, as three launches (caller's workspace) and as the
-    one-launch kernel (no workspace at all), and the one-launch bprop: captured once, replayed
-    with changing inputs."""
+    """fprop on weights transformed ahead, as three launches (a layer beyond the one-launch
+    kernels' range; caller's workspace) and as the one-launch kernel (no workspace at all), and
+    the one-launch bprop: captured once, replayed with changing inputs."""
     import torch
     cfg = dict(S=16, f=16, fo=16, h=16, w=16, kh=3, kw=3)       # basis 16: the fused kernel needs > 64 KB of LDS
     x, w, _ = synth.conv_inputs(seed=601, **cfg)
     dx, dw = _dev(x), _dev(w)
-    dims = (cfg["S"], cfg["f"], cfg["fo"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
     wf = hd.fft_conv_transform_weights(dw, cfg["h"], cfg["w"])
-    ws = torch.empty(hd.workspace_bytes(lib.FPROP, *dims) // 4, device="cuda", dtype=torch.float32)
-    y3 = torch.empty((16, 16, 14, 14), device="cuda")
-    y1 = torch.empty_like(y3)
+    big = dict(S=16, f=32, fo=48, h=16, w=16, kh=3, kw=3)
+    xb, wb, _ = synth.conv_inputs(seed=602, **big)
+    dxb, dwb = _dev(xb), _dev(wb)
+    wfb = hd.fft_conv_transform_weights(dwb, 16, 16)
+    ws = torch.empty(hd.workspace_bytes(lib.FPROP, 16, 32, 48, 16, 16, 3, 3) // 4, device="cuda", dtype=torch.float32)
+    y3 = torch.empty((16, 48, 14, 14), device="cuda")
+    y1 = torch.empty((16, 16, 14, 14), device="cuda")
     gx1 = torch.empty_like(dx)          # the one-launch bprop, fed with the fused fprop's output
 
     def step():
-        hd.fft_conv_fprop_weights(dx, wf, cfg["fo"], 3, 3, y=y3, ws=ws)
+        hd.fft_conv_fprop_weights(dxb, wfb, 48, 3, 3, y=y3, ws=ws)
         hd.fft_conv_fprop_fused(dx, wf, cfg["fo"], 3, 3, y=y1)
         hd.fft_conv_bprop_fused(y1, wf, cfg["f"], 16, 16, 3, 3, gx=gx1)
 
@@ -97,7 +100,7 @@ def test_graph_replay_of_inference_paths(hd, lib):
         step()
     for rep in range(3):
         if rep == 1:
-            dx.mul_(-1.5)
+            dx.mul_(-1.5); dxb.mul_(0.75)
             ref = eager()
         y3.zero_(); y1.zero_(); gx1.zero_()
         torch.cuda.synchronize()
@@ -105,3 +108,39 @@ def test_graph_replay_of_inference_paths(hd, lib):
         torch.cuda.synchronize()
         assert torch.equal(y3, ref[0]) and torch.equal(y1, ref[1]) and torch.equal(gx1, ref[2]), rep
         _ = (dx + 1).sum().item()
+
+
+def test_handle_workspace_never_grows_during_capture(lib):
+    """A call without a caller workspace may have to grow the handle's own buffer, which means a
+    synchronisation, a free and an allocation.  Under stream capture it must refuse instead
+    (workspace too small) and launch nothing; once an eager call has grown the buffer, the same
+    call captures and replays like any other."""
+    import torch
+    cfg = dict(S=8, f=8, fo=8, h=20, w=20, kh=3, kw=3)
+    x, w, _ = synth.conv_inputs(seed=603, **cfg)
+    dx, dw = _dev(x), _dev(w)
+    y = torch.empty((8, 8, 18, 18), device="cuda")
+    hd = lib.Handle(0)                  # a fresh handle: it owns no buffer yet
+    try:
+        warm = lib.Handle(0)
+        ref = warm.fft_conv_fprop(dx, dw).clone()    # kernel attributes are set outside any capture
+        warm.close()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with pytest.raises(lib.FFTConvError, match="workspace too small"):
+            with torch.cuda.graph(graph):
+                hd.fft_conv_fprop(dx, dw, y=y)
+        torch.cuda.synchronize()
+        hd.fft_conv_fprop(dx, dw, y=y)               # eager: the buffer grows here
+        torch.cuda.synchronize()
+        assert torch.equal(y, ref)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            hd.fft_conv_fprop(dx, dw, y=y)           # large enough now: nothing to allocate
+        for _ in range(2):
+            y.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, ref)
+    finally:
+        hd.close()
