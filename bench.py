@@ -32,19 +32,27 @@ STAGES = ("fft", "contraction", "ifft")   # kernels of one pass, in launch order
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
 # scaled by what the same counters read for a plain 256 MiB copy: x2.00 and x1.00); the runs
-# and the table are in profiles/c2_hbm_traffic.md.  Keyed by workload, then "pass.stage".
+# and the tables are in profiles/c2_hbm_traffic.md and profiles/c4_hbm_traffic.md.  Keyed by
+# workload, then by the stage names of `roofline.stages` (fprop_save + backward step).
 MEASURED_TRAFFIC_BYTES = {
-    "C2": {   # keys: the launches of the fprop_save + backward step (paired or separate contractions)
+    "C2": {
         "fprop.fft": (1.205e4 * 2.0 + 5.225e4) * 1024,
         "fprop.contraction": (2.625e4 * 2.0 + 3.483e4) * 1024,
         "fprop.ifft": (1.748e4 * 2.0 + 1.693e4) * 1024,
-        "backward.fft": (8.610e3 * 2.0 + 3.487e4) * 1024,
-        "bprop.contraction": (2.617e4 * 2.0 + 3.482e4) * 1024,
-        "backward.contraction": (5.572e4 * 2.0 + 5.313e4) * 1024,
-        "bprop.ifft": (1.748e4 * 2.0 + 2.333e4) * 1024,
-        "accgrad.contraction": (3.489e4 * 2.0 + 1.741e4) * 1024,
-        "accgrad.ifft": (8.778e3 * 2.0 + 4.00e2) * 1024,
+        "backward.fft": (8.621e3 * 2.0 + 3.485e4) * 1024,
+        "backward.contraction": (5.575e4 * 2.0 + 5.310e4) * 1024,
         "backward.ifft": (2.619e4 * 2.0 + 2.373e4) * 1024,
+    },
+    "C4": {
+        "fprop.fft_a": (3.301e4 * 2.0 + 6.966e4) * 1024,
+        "fprop.fft_b": (3.120e4 * 2.0 + 2.815e5) * 1024,
+        "fprop.contraction": (1.696e5 * 2.0 + 6.758e4) * 1024,
+        "fprop.ifft": (3.387e4 * 2.0 + 1.850e4) * 1024,
+        "backward.fft": (9.523e3 * 2.0 + 7.091e4) * 1024,
+        "bprop.contraction": (1.691e5 * 2.0 + 6.758e4) * 1024,
+        "bprop.ifft": (3.387e4 * 2.0 + 6.554e4) * 1024,
+        "accgrad.contraction": (6.765e4 * 2.0 + 2.703e5) * 1024,
+        "accgrad.ifft": (1.352e5 * 2.0 + 6.157e4) * 1024,
     },
 }
 
@@ -584,6 +592,7 @@ KERNEL_FUNCTIONS = {   # which kernel function runs a stage (for matching rocpro
 # constants, not measured by the run that prints them: the profile named here holds the runs.
 QUOTED_TRAFFIC = {
     "C2": ("profiles/c2_hbm_traffic.md", MEASURED_TRAFFIC_BYTES["C2"]),
+    "C4": ("profiles/c4_hbm_traffic.md", MEASURED_TRAFFIC_BYTES["C4"]),
 }
 
 
@@ -605,6 +614,10 @@ def measure_config(hd, name, steps, warmup, prof_steps, separate=False, library_
     flops = direct_flops(cfg) * len(passes)
     km = profile_kernels(hd, t, cfg, passes, prof_steps, reuse, basis)
     stages = {k: roofline_entry(ms, kernel_model(cfg, k)) for k, ms in km.items()}
+    if reuse and not library_basis_:
+        for k, v in QUOTED_TRAFFIC.get(name, (None, {}))[1].items():
+            if k in stages:
+                stages[k]["traffic"] = round(v)     # quoted constant: see QUOTED_TRAFFIC
     dom = max(stages, key=lambda k: stages[k]["ms"])
     ent = {
         "workload": f"{name}: S={cfg['S']} f={cfg['f']} f'={cfg['fo']} input {cfg['h']}x{cfg['w']} "
