@@ -116,7 +116,9 @@ int fft_conv_bprop(fftconv_handle hd, const float *gy, const float *wt, float *g
 
 /* accGrad: dL/dw(j,i) = sum_s dL/dy(s,j) (star) x(s,i)  -- reduces over the minibatch.
  * x[S,f,h,w], gy[S,fo,oh,ow] -> gw[fo,f,kh,kw] = scale * result (+ previous gw if
- * accumulate != 0). */
+ * accumulate != 0).  Layers of few samples or very small images (those fft_conv_accgrad_fused
+ * supports, with samples x frequency bins up to 900) run as one launch by themselves and then
+ * touch no workspace. */
 int fft_conv_accgrad(fftconv_handle hd, const float *x, const float *gy, float *gw,
                      int S, int f, int fo, int h, int w, int kh, int kw,
                      float scale, int accumulate, void *ws, size_t ws_bytes);
@@ -273,6 +275,21 @@ int fft_conv_fprop_fused(fftconv_handle hd, const float *x, const void *wf, size
  */
 int fft_conv_bprop_fused(fftconv_handle hd, const float *gy, const void *wf, size_t wf_bytes, float *gx,
                          int S, int f, int fo, int h, int w, int kh, int kw);
+
+/*
+ * accGrad of a small layer in ONE launch (Section 6's planned integration of the product with
+ * the transforms, for the pass that reduces over the samples).  The launch has no dependence
+ * between workgroups: each owns a block of output channels and a block of input channels,
+ * transforms the planes of gy and x of those channels for all S samples itself, sums
+ * conj(GY_sj) . X_si over the samples per frequency and inverts its own products with the crop to
+ * kh x kw; a plane is therefore transformed by several workgroups.  Arguments, scale and
+ * accumulate as for fft_conv_accgrad; same result up to rounding; no workspace.  Supported for
+ * untiled, unpadded layers on a square basis of at most 16 with at most 32 samples (64 on basis
+ * 8) and at most 256 channel blocks: otherwise FFTCONV_UNSUPPORTED, and the caller uses
+ * fft_conv_accgrad.
+ */
+int fft_conv_accgrad_fused(fftconv_handle hd, const float *x, const float *gy, float *gw,
+                           int S, int f, int fo, int h, int w, int kh, int kw, float scale, int accumulate);
 
 /*
  * Stand-alone batched real FFTs (Section 5).  X_k = sum_j x_j exp(-2 pi i jk/n)

@@ -24,7 +24,7 @@ SYMBOLS = [
     "fftconv_saved_bytes_tiled", "fftconv_backward_workspace_bytes_tiled",
     "fft_conv_fprop_save_tiled", "fft_conv_backward_tiled",
     "fftconv_weights_bytes", "fft_conv_transform_weights", "fft_conv_fprop_weights", "fft_conv_bprop_weights",
-    "fft_conv_fprop_fused", "fft_conv_bprop_fused",
+    "fft_conv_fprop_fused", "fft_conv_bprop_fused", "fft_conv_accgrad_fused",
     "fftconv_padded_workspace_bytes",
     "fft_conv_fprop_padded", "fft_conv_bprop_padded", "fft_conv_accgrad_padded",
     "fftconv_saved_bytes_padded", "fftconv_backward_workspace_bytes_padded",
@@ -96,6 +96,7 @@ def load_library():
     lib.fft_conv_bprop_weights.argtypes = [vp, vp, vp, sz, vp] + [i] * 9 + [vp, sz]
     lib.fft_conv_fprop_fused.argtypes = [vp, vp, vp, sz, vp] + [i] * 7
     lib.fft_conv_bprop_fused.argtypes = [vp, vp, vp, sz, vp] + [i] * 7
+    lib.fft_conv_accgrad_fused.argtypes = [vp, vp, vp, vp] + [i] * 7 + [f, i]
     lib.fftconv_padded_workspace_bytes.argtypes = [i] * 10
     lib.fftconv_padded_workspace_bytes.restype = sz
     lib.fft_conv_fprop_padded.argtypes = [vp, vp, vp, vp] + [i] * 9 + [vp, sz]
@@ -478,6 +479,24 @@ class Handle:
         _check(self._lib.fft_conv_bprop_fused(self._h, _dev_f32(gy, "gy"), *self._ws(wf), _dev_f32(gx, "gx"),
                                               S, f, fo, h, w, kh, kw), "fft_conv_bprop_fused")
         return gx
+
+    def fft_conv_accgrad_fused(self, x, gy, gw=None, scale=1.0, accumulate=False):
+        """One-launch accGrad of a small layer; raises FFTConvError("unsupported ...") for others."""
+        import torch
+        S, f, h, w = x.shape
+        S2, fo, oh, ow = gy.shape
+        if S2 != S:
+            raise FFTConvError("x and gy disagree on the minibatch size")
+        kh, kw = h - oh + 1, w - ow + 1
+        if gw is None:
+            if accumulate:
+                raise FFTConvError("accumulate needs an existing gw")
+            gw = torch.empty((fo, f, kh, kw), device=x.device, dtype=torch.float32)
+        self._sync_stream()
+        _check(self._lib.fft_conv_accgrad_fused(self._h, _dev_f32(x, "x"), _dev_f32(gy, "gy"), _dev_f32(gw, "gw"),
+                                                S, f, fo, h, w, kh, kw, float(scale), 1 if accumulate else 0),
+               "fft_conv_accgrad_fused")
+        return gw
 
     def fft_conv_bprop_weights(self, gy, wf, f, h, w, kh, kw, pad_h=0, pad_w=0, gx=None, ws=None):
         import torch

@@ -436,6 +436,16 @@ static int run_pass(fftconv_ctx *c, int pass, const float *opA, const float *opB
     PassPlan p;
     int rc = cached_plan(c, pass, S, f, fo, h, w, kh, kw, &p, tile_n, ph, pw);
     if (rc != FFTCONV_OK) return rc;
+    // accGrad of a layer of few samples or very small images runs as ONE launch (as the
+    // weights-ahead fprop / bprop of small layers do): no workspace is touched then.
+    if (pass == FFTCONV_ACCGRAD && tile_n < 0 && !p.tiled && !p.rect && ph == 0 && pw == 0 &&
+        fused_accgrad_pays(p.N, S, f, fo)) {
+        c->nk = 0;
+        const hipError_t e1 = launch_fused_accgrad(opA, opB, out, S, f, fo, h, w, kh, kw, p.N, scale, accumulate,
+                                                   next_ctx(c, "fused"));
+        if (e1 == hipSuccess) return FFTCONV_OK;
+        if (e1 != hipErrorInvalidValue) return hip_fail(c, e1);   // (invalid value: the planes do not fit the kernel's LDS plan)
+    }
     if ((rc = get_workspace(c, p.total, &ws, ws_bytes)) != FFTCONV_OK) return rc;
     float *AF = at(ws, p.offA), *BF = at(ws, p.offB), *CF = at(ws, p.offC);
     c->nk = 0;
@@ -1019,6 +1029,19 @@ int fft_conv_bprop_fused(fftconv_handle hd, const float *gy, const void *wf, siz
     if (p.tiled || p.rect || !fused_bprop_supported(p.N, f, fo, static_cast<const float *>(wf))) return FFTCONV_UNSUPPORTED;
     hd->nk = 0;
     const hipError_t e = launch_fused_bprop(gy, static_cast<const float *>(wf), gx, S, f, fo, h, w, kh, kw, p.N, next_ctx(hd, "fused"));
+    if (e == hipErrorInvalidValue) return FFTCONV_UNSUPPORTED;   // the layer's planes do not fit the kernel's LDS plan
+    return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
+}
+
+int fft_conv_accgrad_fused(fftconv_handle hd, const float *x, const float *gy, float *gw,
+                           int S, int f, int fo, int h, int w, int kh, int kw, float scale, int accumulate) {
+    if (!hd || !gy || !x || !gw) return FFTCONV_INVALID_ARG;
+    PassPlan p;
+    int rc = cached_plan(hd, FFTCONV_ACCGRAD, S, f, fo, h, w, kh, kw, &p);
+    if (rc != FFTCONV_OK) return rc;
+    if (p.tiled || p.rect || !fused_accgrad_supported(p.N, S, f, fo)) return FFTCONV_UNSUPPORTED;
+    hd->nk = 0;
+    const hipError_t e = launch_fused_accgrad(gy, x, gw, S, f, fo, h, w, kh, kw, p.N, scale, accumulate, next_ctx(hd, "fused"));
     if (e == hipErrorInvalidValue) return FFTCONV_UNSUPPORTED;   // the layer's planes do not fit the kernel's LDS plan
     return e == hipSuccess ? FFTCONV_OK : hip_fail(hd, e);
 }

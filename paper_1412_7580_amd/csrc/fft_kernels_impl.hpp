@@ -178,7 +178,8 @@ __device__ __forceinline__ PlaneOrigin plane_origin(const PlaneView &v, long p) 
     const int tx = (int)(m - q * v.ntx);
     const long s = q / v.nty;
     const int ty = (int)(q - s * v.nty);
-    return PlaneOrigin{((s * v.C + ch) * (long long)v.H) * v.W, ty * v.dy, tx * v.dx};
+    const int cimg = v.Cimg ? v.Cimg : v.C;
+    return PlaneOrigin{((s * cimg + ch) * (long long)v.H) * v.W, ty * v.dy, tx * v.dx};
 }
 
 // Per-workgroup table of the origins of its np planes, kept in LDS at `info`
@@ -313,17 +314,23 @@ struct BinStore {
 
 // KEEP (with CONV and OSTAGE): stop once the block's spectra stand in LDS, as the image
 // smem[(bin * 2 + c) * T + plane], and leave them there for the caller (after a barrier).
+// tid_sub / lds_off: a part of a larger workgroup (BT consecutive threads, numbered from 0 in
+// tid_sub) runs the transform in its own part of LDS, lds_off floats (a multiple of 4) from the
+// start; every thread of the workgroup must then make a call of this function, since its barriers
+// are the workgroup's.
 template <int L, int G, int T, bool CONV, bool OSTAGE, bool KEEP = false>
-__device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned block) {
+__device__ __forceinline__ void fft2d_r2c_body(const Fwd2dParams &prm, unsigned block, int tid_sub = -1,
+                                               unsigned lds_off = 0) {
     static_assert(!KEEP || (CONV && OSTAGE), "KEEP leaves the plane-tiled image in LDS");
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G, MRS = MidLayout<L, G>::MRS;
     constexpr int NA = SplitRegs<L, G>::A;   // registers of split spectrum per lane
     constexpr int NBR = SplitRegs<L, G>::B;
-    extern __shared__ float smem[];
+    extern __shared__ float smem_dyn[];
+    float *const smem = smem_dyn + lds_off;
     float *sin = smem;
     float2 *mid = reinterpret_cast<float2 *>(smem);
 
-    const int tid = threadIdx.x;
+    const int tid = tid_sub < 0 ? (int)threadIdx.x : tid_sub;
     const long p0 = (long)block * T;
     const int h_in = prm.h_in, w_in = prm.w_in, hw = h_in * w_in;
     const long left = prm.planes - p0;
@@ -544,15 +551,18 @@ struct Inv2dParams {
 // PRE (plane-tiled layout only): the block's input already stands in LDS at pre_img, laid out
 // like one tile of the layout ((bin * 2 + c) * T + plane), beyond the first
 // max(T * MPS float2, T * h_out * w_out + 3 floats) of LDS, which this function uses.
+// tid_sub: as for the forward body (threads of a larger workgroup beyond the BT that do the work call
+// with a plan of no planes and still pass the barriers).
 template <int L, int G, int T, bool CONV, bool ISTAGE, bool PRE = false>
-__device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned block, const float *pre_img = nullptr) {
+__device__ __forceinline__ void fft2d_c2r_body(const Inv2dParams &prm, unsigned block, const float *pre_img = nullptr,
+                                               int tid_sub = -1) {
     static_assert(!PRE || (CONV && !ISTAGE), "a preloaded tile is in the plane-tiled layout and needs no staging");
     constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
     typedef MidLayout<L, G> ML;
     extern __shared__ float smem[];
     float2 *mid = reinterpret_cast<float2 *>(smem);
 
-    const int tid = threadIdx.x;
+    const int tid = tid_sub < 0 ? (int)threadIdx.x : tid_sub;
     const long p0 = (long)block * T;
     // the output block assembled in LDS shares the 16-byte phase of its place in global memory
     // (contiguous outputs only; scattered windows keep an aligned image)

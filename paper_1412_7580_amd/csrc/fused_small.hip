@@ -187,4 +187,199 @@ hipError_t launch_fused_bprop(const float *gy, const float *wf, float *gx, int S
     }
 }
 
+// accGrad in one launch.  GW_ji = sum_s conj(GY_sj) . X_si reduces over the samples, so a workgroup
+// that is to work alone needs every sample's planes of the channels it owns: it takes a block of
+// JB output channels and IB input channels, transforms the S x JB planes of gy and the S x IB
+// planes of x itself (each set within one plane tile, gathered through a view that selects the
+// block's channels of every sample), forms the JB x IB products per bin on the vector ALUs and
+// inverts them with the crop to kh x kw.  A plane of x is transformed by f' / JB workgroups: the
+// price of having no dependence between workgroups, affordable while the whole layer is a few
+// microseconds of arithmetic.  Measured (back-to-back calls, us, one launch against the three of
+// fft_conv_accgrad): 16 samples of 16 x 16 planes 7x7 10.1 / 13.6; 2 samples of 64 x 64 planes 13x13
+// 12.0 / 16.7; 8 of 64 x 64 15.7 / 16.8; 8 of 32 x 32 15.2 / 15.4; 16 of 16 x 16 13x13 16.3 / 14.6
+// (in the kernel: transforms 8.0, products 3.9, inverse 2.7); 32 of 16 x 16 17.9 / 15.4: it pays for
+// few samples or very small images, which is when fft_conv_accgrad takes it by itself.
+struct FusedAccParams {
+    Fwd2dParams fg, fx;        // in = gy / x (first sample, channel 0); planes = S * JB / S * IB
+    Inv2dParams inv;           // out = gw (pair (0, 0)); planes = JB * IB
+    int S, JB, IB, nib;        // nib = f / IB blocks of input channels
+    int QP;                    // JB * IB rounded up to a power of two
+    long gy_plane, x_plane, gw_plane;   // floats per plane
+    int f;
+    int imgB, imgC;            // float offsets of the second and third LDS image
+};
+
+// The workgroup is two sets of BT threads: the first transforms the block's planes of gy, the
+// second, at the same time and in its own part of LDS, those of x.
+template <int L, int G, int T>
+__global__ void __launch_bounds__(2 * T *(L * G / 2) * G) fused_accgrad_kernel(FusedAccParams ap) {
+    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G, BINS = N * NB;
+    static_assert(BT % 64 == 0, "the two thread sets are whole waves");
+    extern __shared__ float smem[];
+    const int tid = threadIdx.x;
+    const int jb = blockIdx.x / ap.nib, ib = blockIdx.x - jb * ap.nib;
+    const bool second = __builtin_amdgcn_readfirstlane(tid >= BT) != 0;    // (uniform over a wave)
+    const int t = second ? tid - BT : tid;
+
+    {
+        Fwd2dParams fw = second ? ap.fx : ap.fg;
+        fw.in += second ? (long)ib * ap.IB * ap.x_plane : (long)jb * ap.JB * ap.gy_plane;
+        // GY[(bin * 2 + c) * T + s * JB + jj] at smem, X[(bin * 2 + c) * T + s * IB + ii] at smem + imgB
+        fft2d_r2c_body<L, G, T, true, true, true>(fw, 0, t, second ? (unsigned)ap.imgB : 0u);
+    }
+
+    // Products: a wave takes a few bins at a time; for one bin its lanes are (pair q = (jj, ii),
+    // sample group), so that the planes read by the lanes of a wave differ (or coincide: a
+    // broadcast) and the LDS reads meet no bank twice -- lanes on different bins would all read the
+    // same plane index, i.e. the same bank.  Each lane sums its samples, then the groups of a pair
+    // are added up by a butterfly of lane exchanges; UB bins go through that together so that the
+    // exchanges of one overlap with those of the others.
+    constexpr int UB = 4, NW = 2 * BT / 64;
+    const float *ximg = smem + ap.imgB;
+    float *wimg = smem + ap.imgC;
+    const int S = ap.S, JB = ap.JB, IB = ap.IB, Q = JB * IB, QP = ap.QP;   // QP: Q rounded up to a power of two
+    const int lane = tid & 63, wave = tid >> 6;
+    const int q = lane & (QP - 1), sg = lane / QP, nsg = 64 / QP;
+    const bool live = q < Q;
+    const int jj = live ? q / IB : 0, ii = live ? q - jj * IB : 0;
+    for (int b0 = wave * UB; b0 < BINS; b0 += NW * UB) {
+        float wr[UB], wi[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int bin = b0 + u < BINS ? b0 + u : BINS - 1;
+            const float *gr = smem + (bin * 2) * T + jj, *gi = gr + T;
+            const float *xr = ximg + (bin * 2) * T + ii, *xi = xr + T;
+            wr[u] = 0.f; wi[u] = 0.f;
+            if (live) {
+                for (int s = sg; s < S; s += nsg) {
+                    const float a = gr[s * JB], b = gi[s * JB], c = xr[s * IB], d = xi[s * IB];
+                    // conj(gy) . x = (a c + b d) + i (a d - b c)
+                    wr[u] += a * c + b * d;
+                    wi[u] += a * d - b * c;
+                }
+            }
+        }
+        for (int m = QP; m < 64; m <<= 1) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                wr[u] += __shfl_xor(wr[u], m, 64);
+                wi[u] += __shfl_xor(wi[u], m, 64);
+            }
+        }
+        if (live && sg == 0) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u)
+                if (b0 + u < BINS) {
+                    wimg[((b0 + u) * 2) * T + q] = wr[u];
+                    wimg[((b0 + u) * 2 + 1) * T + q] = wi[u];
+                }
+        }
+    }
+    __syncthreads();
+
+    Inv2dParams iv = ap.inv;
+    iv.out += ((long)jb * JB * ap.f + (long)ib * IB) * ap.gw_plane;
+    if (second) iv.planes = 0;      // (the second thread set only passes the barriers)
+    fft2d_c2r_body<L, G, T, true, false, true>(iv, 0, wimg, t);
+}
+
+// Channel blocks (JB of f', IB of f; divisors, so that no block is ragged) with S * JB, S * IB and
+// JB * IB within one plane tile, chosen to transform the fewest planes over the whole grid.
+static bool accgrad_blocks(int T, int S, int f, int fo, int *JB, int *IB) {
+    double best = 0.0;
+    *JB = *IB = 0;
+    for (int j = 1; j <= fo && S * j <= T; ++j) {
+        if (fo % j) continue;
+        for (int i = 1; i <= f && S * i <= T && j * i <= T; ++i) {
+            if (f % i) continue;
+            const double cost = 1.0 / j + 1.0 / i;      // planes transformed ~ S f f' (1/IB + 1/JB)
+            if (*JB == 0 || cost < best) { best = cost; *JB = j; *IB = i; }
+        }
+    }
+    return *JB != 0;
+}
+
+bool fused_accgrad_supported(int N, int S, int f, int fo) {
+    const int tsh = fft2d_tile_log2(N);
+    if (tsh < 5 || N > 16) return false;                // bases 8 .. 16: 32 or 64 planes per tile
+    int JB, IB;
+    if (!accgrad_blocks(1 << tsh, S, f, fo, &JB, &IB)) return false;
+    // one round of workgroups at most, each transforming S (JB + IB) planes of its own
+    return (long)(fo / JB) * (f / IB) <= 256;
+}
+
+// Where the one launch measured faster than the three of the ordinary pass: few samples or very
+// small images (samples x bins up to 900: 8 samples at basis 14, 16 at basis 8).
+bool fused_accgrad_pays(int N, int S, int f, int fo) {
+    return fused_accgrad_supported(N, S, f, fo) && (long)S * N * (N / 2 + 1) <= 900;
+}
+
+template <int L, int G, int T>
+static hipError_t run_fused_accgrad(const float *gy, const float *x, float *gw, int S, int f, int fo, int h, int w,
+                                    int kh, int kw, float scale, int accumulate, LaunchCtx st) {
+    constexpr int N = L * G, NH = N / 2, NB = NH + 1, BT = T * NH * G;
+    const int oh = h - kh + 1, ow = w - kw + 1;
+    FusedAccParams ap;
+    if (!accgrad_blocks(T, S, f, fo, &ap.JB, &ap.IB)) return hipErrorInvalidValue;
+    ap.S = S; ap.f = f; ap.nib = f / ap.IB;
+    ap.QP = 1;
+    while (ap.QP < ap.JB * ap.IB) ap.QP <<= 1;
+    ap.gy_plane = (long)oh * ow; ap.x_plane = (long)h * w; ap.gw_plane = (long)kh * kw;
+    // views: plane p of a set = (sample p / C, channel p % C of the block) of a tensor with Cimg channels
+    const PlaneView vg{ap.JB, 1, 1, N, N, 0, 0, oh, ow, fo}, vx{ap.IB, 1, 1, N, N, 0, 0, h, w, f},
+        vo{ap.IB, 1, 1, N, N, 0, 0, kh, kw, f};
+    size_t lds_g = 0, lds_x = 0, lds_i = 0;
+    bool istage = false;
+    ap.fg = make_fwd2d<L, G, T>(gy, nullptr, (long)S * ap.JB, oh, ow, &lds_g, &vg);
+    ap.fx = make_fwd2d<L, G, T>(x, nullptr, (long)S * ap.IB, h, w, &lds_x, &vx);
+    // LDS is what limits this kernel: stage the planes with the plain odd strides instead of the
+    // bank-spreading ones (up to 34 floats per row of 8), which the transforms read equally well
+    auto compact = [](Fwd2dParams &p, size_t *lds) {
+        p.RS = p.w_in | 1;
+        p.IPS = (p.h_in * p.RS) | 1;
+        const size_t a = ((size_t)T * p.IPS + N) * sizeof(float), b = (size_t)T * p.MPS * sizeof(float2);
+        *lds = a > b ? a : b;
+    };
+    compact(ap.fg, &lds_g);
+    compact(ap.fx, &lds_x);
+    ap.inv = make_inv2d<L, G, T>(nullptr, gw, (long)ap.JB * ap.IB, kh, kw, true, scale / ((float)N * (float)N),
+                                 accumulate != 0, &vo, &lds_i, &istage);
+    const size_t img = (size_t)T * N * NB * 2 * sizeof(float);      // bytes of one LDS image
+    // Two regions of equal size, one per thread set, each holding its forward transform's staging
+    // and transposed data and then its spectra (the first later also the inverse's transposed data
+    // and output block); the products' image behind them, the two origin tables last.
+    size_t first = img;
+    if (lds_g > first) first = lds_g;
+    if (lds_x > first) first = lds_x;
+    const size_t inv_a = (size_t)T * ap.inv.MPS * sizeof(float2), inv_b = ((size_t)T * kh * kw + 3) * sizeof(float);
+    if (inv_a > first) first = inv_a;
+    if (inv_b > first) first = inv_b;
+    first = (first + 15) / 16 * 16;
+    ap.imgB = (int)(first / sizeof(float));
+    ap.imgC = (int)(2 * first / sizeof(float));
+    int info0 = 0, info1 = 0;
+    size_t lds = with_origin_table(2 * first + img, T, &info0);
+    lds = with_origin_table(lds, T, &info1);
+    ap.fg.info_off = ap.inv.info_off = info0;
+    ap.fx.info_off = info1 - ap.imgB;          // relative to the second region
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    auto k = fused_accgrad_kernel<L, G, T>;
+    if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
+    launch_kernel(k, dim3((unsigned)((fo / ap.JB) * ap.nib)), dim3(2 * BT), lds, st, ap);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused_accgrad(const float *gy, const float *x, float *gw, int S, int f, int fo, int h, int w,
+                                int kh, int kw, int N, float scale, int accumulate, LaunchCtx st) {
+    if (!fused_accgrad_supported(N, S, f, fo) || h > N || w > N) return hipErrorInvalidValue;
+    switch (N) {
+        case 8: return run_fused_accgrad<4, 2, 64>(gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, st);
+        case 10: return run_fused_accgrad<5, 2, 32>(gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, st);
+        case 12: return run_fused_accgrad<6, 2, 32>(gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, st);
+        case 14: return run_fused_accgrad<7, 2, 32>(gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, st);
+        case 16: return run_fused_accgrad<8, 2, 32>(gy, x, gw, S, f, fo, h, w, kh, kw, scale, accumulate, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace fc

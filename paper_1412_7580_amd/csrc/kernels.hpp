@@ -76,6 +76,7 @@ struct PlaneView {
     int dy, dx;
     int oy, ox;
     int H, W;
+    int Cimg = 0;   // channels per sample of the image tensor when the view selects C of them (0: C)
 };
 
 // Planes per workgroup (= layout tile) of the 2-D kernels for basis N.
@@ -148,6 +149,14 @@ hipError_t launch_fused_fprop(const float *x, const float *wf, float *y, int S, 
 bool fused_bprop_supported(int N, int f, int fo, const float *wf);
 hipError_t launch_fused_bprop(const float *gy, const float *wf, float *gx, int S, int f, int fo, int h, int w,
                               int kh, int kw, int N, LaunchCtx st);
+
+// One-launch accGrad of a small layer (basis N <= 16, all S samples of a block of output and input
+// channels within one plane tile): one workgroup per block of (j, i) pairs, which transforms the
+// planes of gy and x it needs itself, reduces over the samples and inverts its own products.
+bool fused_accgrad_supported(int N, int S, int f, int fo);
+bool fused_accgrad_pays(int N, int S, int f, int fo);     // ... and measured faster than three launches
+hipError_t launch_fused_accgrad(const float *gy, const float *x, float *gw, int S, int f, int fo, int h, int w,
+                                int kh, int kw, int N, float scale, int accumulate, LaunchCtx st);
 
 hipError_t launch_fft1d_r2c(const float *in, float *out, long B, int n_in, int n, LaunchCtx st);
 hipError_t launch_fft1d_c2r(const float *in, float *out, long B, int n, int n_out, LaunchCtx st);

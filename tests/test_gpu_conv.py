@@ -381,6 +381,73 @@ def test_fused_bprop(hd, lib, cfg):
     assert _relerr(_np(gx), ref) <= TOL
 
 
+FUSED_ACC = [dict(S=16, f=16, fo=16, h=13, w=13, kh=3, kw=3),     # the smallest benchmark layer: 2 x 2 channel blocks
+             dict(S=32, f=4, fo=4, h=14, w=14, kh=5, kw=5),       # a plane tile full of samples: one pair per workgroup
+             dict(S=5, f=6, fo=9, h=12, w=11, kh=1, kw=1),        # 3 x 6 blocks: 18 pairs, padded to 32 lanes
+             dict(S=3, f=16, fo=8, h=8, w=8, kh=3, kw=3),         # basis 8 (64 planes per tile)
+             dict(S=64, f=3, fo=5, h=8, w=8, kh=8, kw=8),         # 64 samples on basis 8, kernel = image
+             dict(S=7, f=10, fo=14, h=10, w=10, kh=3, kw=3),      # basis 10, odd sample count
+             dict(S=2, f=64, fo=64, h=13, w=13, kh=3, kw=3)]      # 128 blocks of 4 x 8 channels
+
+
+@pytest.mark.parametrize("cfg", FUSED_ACC, ids=lambda c: "S{S}f{f}fo{fo}_{h}x{w}_k{kh}x{kw}".format(**c))
+def test_fused_accgrad(hd, lib, cfg):
+    """The one-launch accGrad of small layers against the oracle and against the three-launch path
+    (the same basis named through the tiled entry point, which never takes the one-launch kernel),
+    with scale and accumulate, and into an output that holds stale values."""
+    import torch
+    x, _, gy = synth.conv_inputs(seed=90, **cfg)
+    dx, dgy = _dev(x), _dev(gy)
+    gw = hd.fft_conv_accgrad_fused(dx, dgy)
+    torch.cuda.synchronize()
+    ref = oracle.conv_accgrad(x, gy)
+    assert gw.shape == ref.shape
+    assert _relerr(_np(gw), ref) <= TOL
+    n = hd.layer_basis(cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])[0]
+    gw3 = hd.fft_conv_accgrad_tiled(dx, dgy, n)
+    assert float((gw - gw3).abs().max()) <= 2e-5 * float(np.max(np.abs(ref)))
+    gw.fill_(7.0)
+    hd.fft_conv_accgrad_fused(dx, dgy, gw=gw)
+    assert _relerr(_np(gw), ref) <= TOL
+    acc = torch.full_like(gw, 1.5)
+    hd.fft_conv_accgrad_fused(dx, dgy, gw=acc, scale=0.25, accumulate=True)
+    assert _relerr(_np(acc), 1.5 + 0.25 * ref) <= TOL
+
+
+def test_accgrad_takes_one_launch_for_few_samples(hd):
+    """fft_conv_accgrad runs a layer of few samples as one launch by itself (the profiling
+    interface reports a single kernel, "fused") with the oracle's result; the smallest benchmark
+    layer, where three launches measured faster, keeps them."""
+    import torch
+    small = dict(S=2, f=32, fo=32, h=13, w=13, kh=3, kw=3)
+    x, _, gy = synth.conv_inputs(seed=92, **small)
+    c1 = {k: v for k, v in synth.CONV_CONFIGS["C1"].items() if k not in ("passes", "N")}
+    x1, _, gy1 = synth.conv_inputs(seed=synth.CONV_SEEDS["C1"], **c1)
+    hd.set_profiling(True)
+    try:
+        gw = hd.fft_conv_accgrad(_dev(x), _dev(gy))
+        assert hd.last_kernel_labels() == ["fused"]
+        gw1 = hd.fft_conv_accgrad(_dev(x1), _dev(gy1))
+        assert hd.last_kernel_labels() == ["fft.ab", "contraction", "ifft"]
+    finally:
+        hd.set_profiling(False)
+    torch.cuda.synchronize()
+    assert _relerr(_np(gw), oracle.conv_accgrad(x, gy)) <= TOL
+    assert _relerr(_np(gw1), oracle.conv_accgrad(x1, gy1)) <= TOL
+
+
+def test_fused_accgrad_unsupported_shapes(hd, lib):
+    import torch
+    for cfg in (dict(S=33, f=4, fo=4, h=13, w=13, kh=3, kw=3),     # more samples than a plane tile holds
+                dict(S=32, f=32, fo=32, h=13, w=13, kh=3, kw=3),   # 1024 single-pair blocks
+                dict(S=2, f=16, fo=16, h=27, w=27, kh=5, kw=5),    # basis 28
+                dict(S=2, f=8, fo=8, h=14, w=9, kh=1, kw=1)):      # rectangular basis 14 x 10
+        x = torch.zeros((cfg["S"], cfg["f"], cfg["h"], cfg["w"]), device="cuda")
+        gy = torch.zeros((cfg["S"], cfg["fo"], cfg["h"] - cfg["kh"] + 1, cfg["w"] - cfg["kw"] + 1), device="cuda")
+        with pytest.raises(lib.FFTConvError, match="unsupported"):
+            hd.fft_conv_accgrad_fused(x, gy)
+
+
 def test_fused_fprop_unsupported_shapes(hd, lib):
     import torch
     for cfg in (dict(S=2, f=12, fo=8, h=13, w=13, kh=3, kw=3),     # f does not divide the plane tile
