@@ -38,6 +38,47 @@ struct GroupLoader {
         }
     }
 
+    // Fast addressing (the strided matrix index moves in whole plane tiles, see fast_addressing()
+    // in cgemm_kernels.hip): the element index splits into a part that is uniform over the
+    // workgroup and changes with the K tile, left to the scalar unit (tile_base), and a per-lane
+    // byte offset that never changes, computed once (prepare).  A gather then costs no vector
+    // arithmetic and no 64-bit address registers.
+    unsigned boff[NV];
+    __device__ __forceinline__ void prepare(int bins, long rs, long cs, int r0, int R, int tid) {
+        const int j = tid & 7, ub = tid >> 3;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int u = ub + 32 * i;
+            int rr, kk;
+            if constexpr (KF) { kk = (u % (TK / 4)) * 4; rr = u / (TK / 4); }
+            else { rr = (u % (ROWS / 4)) * 4; kk = u / (ROWS / 4); }
+            size_t o;
+            if constexpr (KF) o = (size_t)rr * (rs >> 2) + (kk >> 2);
+            else o = (size_t)(rr >> 2) + (size_t)kk * (cs >> 2);
+            o = o * bins * 8 + j * 4;
+            boff[i] = (u < UNITS && r0 + rr < R) ? (unsigned)(o * sizeof(float)) : 0xffffffffu;
+        }
+    }
+    static __device__ __forceinline__ const char *tile_base(const float *base, int bins, long rs, long cs, int b0,
+                                                            int r0, int k0) {
+        size_t o;
+        if constexpr (KF) o = (size_t)r0 * (rs >> 2) + (k0 >> 2);
+        else o = (size_t)(r0 >> 2) + (size_t)k0 * (cs >> 2);
+        return reinterpret_cast<const char *>(base + (o * bins + b0) * 8);
+    }
+    __device__ __forceinline__ void load_fast(const char *ub, int k0, int K, int tid) {
+        const int ubi = tid >> 3;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int u = ubi + 32 * i;
+            int kk;
+            if constexpr (KF) kk = (u % (TK / 4)) * 4;
+            else kk = u / (ROWS / 4);
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (boff[i] != 0xffffffffu && k0 + kk < K) v[i] = *reinterpret_cast<const float4 *>(ub + boff[i]);
+        }
+    }
+
     // LDS image: region-major, inside a region [k][row] with row stride STRIDE.
     __device__ __forceinline__ void store(float *dst, int tid) const {
         const int j = tid & 7, ub = tid >> 3;
@@ -61,7 +102,11 @@ struct GroupLoader {
     }
 };
 
-template <int FM, int FN, int TK, bool AKF, bool BKF>
+// FAST: fast addressing (GroupLoader::prepare) of both operands and of the result.  C4 layer, us per
+// pass (fprop / bprop / accGrad), same box: 107 / 100 / 117 without, 100 / 93 / 103 with it.  (Loads of
+// two K tiles in flight instead of one need 64 more registers: at three waves per SIMD that
+// build spilled, at two it measured 117 / 108 / 140.)
+template <int FM, int FN, int TK, bool AKF, bool BKF, bool FAST>
 __global__ void __launch_bounds__(256, (FM * FN == 1 && AKF == BKF ? 4 : 1)) cgemm_bingroup_kernel(GemmParams prm) {
     constexpr int TM = 32 * FM, TN = 32 * FN;
     constexpr int SA = TM + 2, SB = TN + 2;
@@ -93,8 +138,20 @@ __global__ void __launch_bounds__(256, (FM * FN == 1 && AKF == BKF ? 4 : 1)) cge
     GroupLoader<TM, TK, SA, RA, AKF> la;
     GroupLoader<TN, TK, SB, RB, BKF> lb;
     const int nkt = (K + TK - 1) / TK;
-    la.load(prm.A, bins, prm.a_rs, prm.a_cs, b0, m0, 0, M, K, tid);
-    lb.load(prm.B, bins, prm.b_cs, prm.b_rs, b0, n0, 0, N, K, tid);
+    if constexpr (FAST) {
+        la.prepare(bins, prm.a_rs, prm.a_cs, m0, M, tid);
+        lb.prepare(bins, prm.b_cs, prm.b_rs, n0, N, tid);
+    }
+    auto fetch = [&](int kt) {
+        if constexpr (FAST) {
+            la.load_fast(la.tile_base(prm.A, bins, prm.a_rs, prm.a_cs, b0, m0, kt * TK), kt * TK, K, tid);
+            lb.load_fast(lb.tile_base(prm.B, bins, prm.b_cs, prm.b_rs, b0, n0, kt * TK), kt * TK, K, tid);
+        } else {
+            la.load(prm.A, bins, prm.a_rs, prm.a_cs, b0, m0, kt * TK, M, K, tid);
+            lb.load(prm.B, bins, prm.b_cs, prm.b_rs, b0, n0, kt * TK, N, K, tid);
+        }
+    };
+    fetch(0);
     la.store(As, tid);
     lb.store(Bs, tid);
     __syncthreads();
@@ -104,10 +161,7 @@ __global__ void __launch_bounds__(256, (FM * FN == 1 && AKF == BKF ? 4 : 1)) cge
     const float *b0p = Bs + (2 * wave) * RB + lrow;
     for (int kt = 0; kt < nkt; ++kt) {
         const bool more = kt + 1 < nkt;
-        if (more) {
-            la.load(prm.A, bins, prm.a_rs, prm.a_cs, b0, m0, (kt + 1) * TK, M, K, tid);
-            lb.load(prm.B, bins, prm.b_cs, prm.b_rs, b0, n0, (kt + 1) * TK, N, K, tid);
-        }
+        if (more) fetch(kt + 1);
 #pragma unroll
         for (int ks = 0; ks < TK; ks += 2) {
             float a_re[FM], a_im[FM], a_sm[FM], b_re[FN], b_im[FN], b_sm[FN];
@@ -163,7 +217,25 @@ __global__ void __launch_bounds__(256, (FM * FN == 1 && AKF == BKF ? 4 : 1)) cge
             }
         }
     __syncthreads();
-    {
+    if constexpr (FAST) {
+        // rows ub / NQ + it * (32 / NQ), column quad ub % NQ: the index is a uniform base, a per-lane
+        // offset and a uniform step per round
+        static_assert(32 % NQ == 0, "a round of 32 units covers whole rows");
+        const int jq = tid & 7, ub = tid >> 3;
+        const size_t crs4 = (size_t)(prm.c_rs >> 2);
+        char *cb = reinterpret_cast<char *>(prm.C + (((size_t)m0 * crs4 + (n0 >> 2)) * bins + b0) * 8);
+        const int mm0 = ub / NQ, nq = ub % NQ;
+        const unsigned loff = (unsigned)((((size_t)mm0 * crs4 + nq) * bins * 8 + jq * 4) * sizeof(float));
+        const size_t step = (size_t)(32 / NQ) * crs4 * bins * 8 * sizeof(float);
+        const bool col_ok = n0 + 4 * nq < N;
+#pragma unroll
+        for (int it = 0; it < TM * NQ / 32; ++it) {
+            const int mm = mm0 + it * (32 / NQ);
+            if (col_ok && m0 + mm < M)
+                *reinterpret_cast<float4 *>(cb + it * step + loff) =
+                    *reinterpret_cast<const float4 *>(img + (ub + 32 * it) * LSTR + jq * 4);
+        }
+    } else {
         const int jq = tid & 7, ub = tid >> 3;
 #pragma unroll
         for (int u = ub; u < TM * NQ; u += 32) {
@@ -178,7 +250,7 @@ __global__ void __launch_bounds__(256, (FM * FN == 1 && AKF == BKF ? 4 : 1)) cge
     }
 }
 
-template <int FM, int FN, int TK, bool AKF, bool BKF>
+template <int FM, int FN, int TK, bool AKF, bool BKF, bool FAST = false>
 static hipError_t run_bg(GemmParams prm, LaunchCtx st) {
     constexpr int TM = 32 * FM, TN = 32 * FN;
     constexpr int RA = TK * (TM + 2) + (AKF ? 1 : 2), RB = TK * (TN + 2) + (BKF ? 1 : 2);
@@ -188,7 +260,7 @@ static hipError_t run_bg(GemmParams prm, LaunchCtx st) {
     size_t lds = (size_t)8 * (RA + RB) * sizeof(float);
     const size_t img = (size_t)TM * (TN / 4) * 36 * sizeof(float);
     if (img > lds) lds = img;
-    auto k = cgemm_bingroup_kernel<FM, FN, TK, AKF, BKF>;
+    auto k = cgemm_bingroup_kernel<FM, FN, TK, AKF, BKF, FAST>;
     if (hipError_t e = allow_big_lds((const void *)k, lds); e != hipSuccess) return e;
     launch_kernel(k, dim3((unsigned)grid), dim3(256), lds, st, prm);
     return hipGetLastError();
@@ -197,7 +269,7 @@ static hipError_t run_bg(GemmParams prm, LaunchCtx st) {
 template <bool AKF, bool BKF>
 static hipError_t dispatch_bg(int shape, const GemmParams &prm, LaunchCtx st) {
     switch (shape) {
-        case 0: return run_bg<1, 1, 16, AKF, BKF>(prm, st);
+        case 0: return prm.fast ? run_bg<1, 1, 16, AKF, BKF, true>(prm, st) : run_bg<1, 1, 16, AKF, BKF>(prm, st);
         case 1: return run_bg<1, 2, 16, AKF, BKF>(prm, st);
         case 2: return run_bg<2, 1, 16, AKF, BKF>(prm, st);
         case 3: return run_bg<2, 2, 16, AKF, BKF>(prm, st);
