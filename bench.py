@@ -46,13 +46,13 @@ MEASURED_TRAFFIC_BYTES = {
     "C4": {
         "fprop.fft_a": (3.301e4 * 2.0 + 6.966e4) * 1024,
         "fprop.fft_b": (3.120e4 * 2.0 + 2.815e5) * 1024,
-        "fprop.contraction": (1.696e5 * 2.0 + 6.758e4) * 1024,
-        "fprop.ifft": (3.387e4 * 2.0 + 1.850e4) * 1024,
-        "backward.fft": (9.523e3 * 2.0 + 7.091e4) * 1024,
+        "fprop.contraction": (1.702e5 * 2.0 + 6.758e4) * 1024,
+        "fprop.ifft": (3.388e4 * 2.0 + 1.850e4) * 1024,
+        "backward.fft": (9.523e3 * 2.0 + 7.069e4) * 1024,
         "bprop.contraction": (1.691e5 * 2.0 + 6.758e4) * 1024,
-        "bprop.ifft": (3.387e4 * 2.0 + 6.554e4) * 1024,
-        "accgrad.contraction": (6.765e4 * 2.0 + 2.703e5) * 1024,
-        "accgrad.ifft": (1.352e5 * 2.0 + 6.157e4) * 1024,
+        "bprop.ifft": (3.389e4 * 2.0 + 6.554e4) * 1024,
+        "accgrad.contraction": (6.763e4 * 2.0 + 2.703e5) * 1024,
+        "accgrad.ifft": (1.353e5 * 2.0 + 6.157e4) * 1024,
     },
 }
 
@@ -223,9 +223,24 @@ def graph_replay_c1(hd, reps=200):
     dims = (cfg["f"], cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])
     bprop = timed(lambda: hd.fft_conv_bprop(gy, t["w"], cfg["h"], cfg["w"], gx=gx))
     bfused = timed(lambda: hd.fft_conv_bprop_fused(gy, wf, *dims, gx=gx))
+    # accGrad: the three launches (the layer's basis named through the tiled call, which never takes the
+    # one-launch kernel) against the one-launch kernel, on this layer (where the ordinary call keeps
+    # its three launches) and on one of few samples (where it takes the one launch by itself)
+    gw = torch.empty_like(t["w"])
+    n = hd.layer_basis(cfg["h"], cfg["w"], cfg["kh"], cfg["kw"])[0]
+    acc3 = timed(lambda: hd.fft_conv_accgrad_tiled(t["x"], gy, n, gw=gw))
+    acc1 = timed(lambda: hd.fft_conv_accgrad_fused(t["x"], gy, gw=gw))
+    xs = torch.empty((2, 64, 13, 13), device="cuda").uniform_(-1, 1)
+    gys = torch.empty((2, 64, 11, 11), device="cuda").uniform_(-1, 1)
+    gws = torch.empty((64, 64, 3, 3), device="cuda")
+    few3 = timed(lambda: hd.fft_conv_accgrad_tiled(xs, gys, n, gw=gws))
+    few1 = timed(lambda: hd.fft_conv_accgrad(xs, gys, gw=gws))
     return {"eager_us_per_fprop": round(eager * 1e6, 2), "graph_replay_us_per_fprop": round(replay * 1e6, 2),
             "fused_one_launch_us_per_fprop": round(fused * 1e6, 2),
-            "eager_us_per_bprop": round(bprop * 1e6, 2), "fused_one_launch_us_per_bprop": round(bfused * 1e6, 2)}
+            "eager_us_per_bprop": round(bprop * 1e6, 2), "fused_one_launch_us_per_bprop": round(bfused * 1e6, 2),
+            "three_launch_us_per_accgrad": round(acc3 * 1e6, 2), "fused_one_launch_us_per_accgrad": round(acc1 * 1e6, 2),
+            "S2_f64_13x13_three_launch_us_per_accgrad": round(few3 * 1e6, 2),
+            "S2_f64_13x13_ordinary_call_us_per_accgrad": round(few1 * 1e6, 2)}
 
 
 def tiled_layers(hd, reps=10):
