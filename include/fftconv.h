@@ -357,7 +357,8 @@ int fft_conv_backward(fftconv_handle hd, const float *gy, float *gx, float *gw,
  *   "contraction.pair"  the bprop and accGrad contractions of fft_conv_backward in one launch
  *   "ifft", "ifft.pair" inverse FFT + clip of one product, or of gx and gw in one launch
  *   "fused"             the one-launch passes
- * fft_conv_fprop / bprop / accgrad / fprop_save give 3 or 4 entries; fft_conv_backward gives
+ * fft_conv_fprop / bprop / accgrad / fprop_save give 3 or 4 entries (1 when the pass runs as one
+ * launch); fft_conv_backward gives
  * fft of gy, then contraction and ifft for gx and again for gw (5), or 4 or 3 with shared launches.
  * Off by default.
  */

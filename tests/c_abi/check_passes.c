@@ -196,6 +196,17 @@ int main(int argc, char **argv) {
         bad += check("fft_conv_fprop_fused", dy2, ry2, ny2, 1e-4);
         FC_OK(fft_conv_bprop_fused(hd, dg2, wf, wb, dgx2, S2, f2, fo2, h2, h2, k2, k2));
         bad += check("fft_conv_bprop_fused", dgx2, rgx2, nx2, 1e-4);
+        /* accGrad of the same layer as one launch (needs no weights: it reduces over the samples) */
+        {
+            double *rgw2 = (double *)malloc(nw2 * sizeof(double));
+            oracle_conv_accgrad(x2d, g2d, rgw2, S2, f2, fo2, h2, h2, k2, k2, NULL, 0);
+            float *dgw2;
+            HIP_OK(hipMalloc((void **)&dgw2, nw2 * sizeof(float)));
+            FC_OK(fft_conv_accgrad_fused(hd, dx2, dg2, dgw2, S2, f2, fo2, h2, h2, k2, k2, 1.0f, 0));
+            bad += check("fft_conv_accgrad_fused", dgw2, rgw2, nw2, 1e-4);
+            HIP_OK(hipFree(dgw2));
+            free(rgw2);
+        }
         HIP_OK(hipFree(dx2)); HIP_OK(hipFree(dw2)); HIP_OK(hipFree(dg2)); HIP_OK(hipFree(dy2)); HIP_OK(hipFree(dgx2));
         HIP_OK(hipFree(wf));
         free(x2); free(w2); free(g2); free(x2d); free(w2d); free(g2d); free(ry2); free(rgx2);

@@ -35,4 +35,4 @@ def test_plain_c_caller_matches_oracle():
     print(run.stdout, run.stderr)
     assert run.returncode == 0, run.stdout + run.stderr
     assert "all checks passed" in run.stdout
-    assert run.stdout.count("  ok\n") == 11
+    assert run.stdout.count("  ok\n") == 12
