@@ -395,12 +395,26 @@ def weights_ahead(hd, reps=30):
     return out
 
 
-def device_copy_bandwidth(reps=20):
+def cpu_fft_baseline(n=64, count=4096):
+    """The DFT oracle (the definition, O(n^2) per line, fp64, OpenMP over planes) on the first
+    `count` planes of the sweep's 2-D input at size n: algorithmic GB/s as for the GPU sweep."""
+    import oracle
+    from paper_1412_7580_amd import synth
+    x = synth.fft_sweep_input(2, n, 0, count)
+    t0 = time.perf_counter()
+    oracle.dft_r2c_2d(x, n)
+    dt = max(time.perf_counter() - t0, 1e-6)
+    nbytes = count * (4 * (n - 3) ** 2 + 8 * n * (n // 2 + 1))
+    return {"value": round(nbytes / dt / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"fp64 DFT by definition, 2-D R2C n={n}: first {count} of the sweep's planes in {dt:.2f}s"}
+
+
+def device_copy_bandwidth(reps=20, sizes_mib=(256, 1024)):
     """Plain device-to-device copy of 256 MiB and 1 GiB (read + write bytes over time): what the
     memory system delivers to the simplest kernel, for reading the FFT stages' GB/s against."""
     import torch
     out = {}
-    for mib in (256, 1024):
+    for mib in sizes_mib:
         a = torch.ones(mib * (1 << 20) // 4, device="cuda")
         b = torch.empty_like(a)
         for _ in range(3):
@@ -645,6 +659,14 @@ def measure_config(hd, name, steps, warmup, prof_steps, separate=False, library_
         "launches_per_step": len(km), "kernel_ms_sum": round(sum(km.values()), 5),
         "dominant": dom, "stages": stages,
     }
+    if reuse:
+        # the passes one by one, each an independent call that transforms both of its operands (the
+        # per-pass layout of the paper's Table 4): median of 20 event-timed calls after 5
+        per = {}
+        for p in passes:
+            m1, _, _ = time_steps_events(hd, t, cfg, (p,), 20, 5, False, basis)
+            per[p] = {"ms": round(m1, 5), "effective_TFLOPs": round(direct_flops(cfg) / m1 / 1e9, 2)}
+        ent["per_pass_independent_calls"] = per
     del t
     torch.cuda.empty_cache()
     return ent, cfg, host, passes, flops
@@ -778,7 +800,15 @@ def main():
     }
     if "flops" in model:
         roof["executed_flops"] = model["flops"]
+    if "per_pass_independent_calls" in head:
+        roof["per_pass_independent_calls"] = head.pop("per_pass_independent_calls")
     if not args.no_others:
+        # what a plain device copy of 256 MiB moves on this machine (read + write), and the dominant
+        # kernel's rate against it: the nominal 8 TB/s is not what the simplest kernel gets
+        copy = device_copy_bandwidth(sizes_mib=(256,))["256MiB"]
+        roof["device_copy_GBps"] = copy
+        if "GBps" in d:
+            roof["frac_of_device_copy"] = round(d["GBps"] / copy, 4)
         others = {}
         for other in ("C1", "C2", "C3", "C4"):
             if other == name:
@@ -802,6 +832,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, host)
+        out["cpu_baseline"]["fft_oracle"] = cpu_fft_baseline()
     if args.extra:
         extra = {}
         extra["C1_fprop_hip_graph"] = graph_replay_c1(hd)
