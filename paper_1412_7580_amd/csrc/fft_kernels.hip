@@ -74,7 +74,13 @@ hipError_t launch_fft2d_r2c(const float *in, float *out, long planes, int h_in, 
         case 8: return run_fwd2d<8, 1, 64>(in, out, planes, h_in, w_in, conv, st, view);
         case 16: return run_fwd2d<16, 1, 32>(in, out, planes, h_in, w_in, conv, st, view);   // (8,2): 12 % slower
         case 32: return run_fwd2d<8, 4, 8>(in, out, planes, h_in, w_in, conv, st, view);   // 16 planes: (16,2) 5 % slower, (32,1) 8 %
-        case 64: return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st, view);   // (64,1): 25 % slower, (16,4): 5 % slower
+        case 64:
+            // Lane pairs ((64,1): 25 % slower), except for inputs of more than 52 rows: their four
+            // planes of row-transformed data (1 KB per row) leave room for two workgroups per compute
+            // unit only, and twice the waves on four lanes per line then hide more latency
+            // (4096 planes 64x64: 45.7 -> 41.2 us; but 34x34: 25.8 -> 31.5, 31x31: 74 -> 84)
+            if (conv && h_in > 52) return run_fwd2d<16, 4, 4>(in, out, planes, h_in, w_in, conv, st, view);
+            return run_fwd2d<32, 2, 4>(in, out, planes, h_in, w_in, conv, st, view);
         case 128: return run_fwd2d<16, 8, 1>(in, out, planes, h_in, w_in, conv, st, view);
         default: return launch_fft2d_r2c_mixed(in, out, planes, h_in, w_in, N, conv, st, view);
     }
