@@ -44,12 +44,12 @@ MEASURED_TRAFFIC_BYTES = {
         "backward.ifft": (2.619e4 * 2.0 + 2.373e4) * 1024,
     },
     "C4": {
-        "fprop.fft_a": (3.301e4 * 2.0 + 6.966e4) * 1024,
-        "fprop.fft_b": (3.120e4 * 2.0 + 2.815e5) * 1024,
+        "fprop.fft_a": (3.294e4 * 2.0 + 6.889e4) * 1024,
+        "fprop.fft_b": (3.119e4 * 2.0 + 2.823e5) * 1024,
         "fprop.contraction": (1.702e5 * 2.0 + 6.758e4) * 1024,
         "fprop.ifft": (3.388e4 * 2.0 + 1.850e4) * 1024,
-        "backward.fft": (9.523e3 * 2.0 + 7.069e4) * 1024,
-        "bprop.contraction": (1.691e5 * 2.0 + 6.758e4) * 1024,
+        "backward.fft": (9.515e3 * 2.0 + 7.152e4) * 1024,
+        "bprop.contraction": (1.692e5 * 2.0 + 6.758e4) * 1024,
         "bprop.ifft": (3.389e4 * 2.0 + 6.554e4) * 1024,
         "accgrad.contraction": (6.763e4 * 2.0 + 2.703e5) * 1024,
         "accgrad.ifft": (1.353e5 * 2.0 + 6.157e4) * 1024,
@@ -625,7 +625,7 @@ QUOTED_TRAFFIC = {
 }
 
 
-def measure_config(hd, name, steps, warmup, prof_steps, separate=False, library_basis_=False):
+def measure_config(hd, name, steps, warmup, prof_steps, separate=False, library_basis_=False, per_pass=True):
     """Step time (median of per-step event pairs) and per-kernel rooflines of configuration `name`
     on the Fourier basis it names.  Returns (entry dict, cfg, host inputs)."""
     import torch
@@ -659,7 +659,7 @@ def measure_config(hd, name, steps, warmup, prof_steps, separate=False, library_
         "launches_per_step": len(km), "kernel_ms_sum": round(sum(km.values()), 5),
         "dominant": dom, "stages": stages,
     }
-    if reuse:
+    if reuse and per_pass:
         # the passes one by one, each an independent call that transforms both of its operands (the
         # per-pass layout of the paper's Table 4): median of 20 event-timed calls after 5
         per = {}
@@ -725,7 +725,7 @@ def main():
                     help="leave the Fourier basis to the library (28x28 for the 27x27 layer) instead of the "
                          "one the configuration names")
     ap.add_argument("--no-others", action="store_true",
-                    help="skip the other configurations and the FFT sweep of the roofline object (profiling runs)")
+                    help="skip the other configurations, the per-pass calls, the device copy and the FFT sweep of the roofline object (profiling runs)")
     ap.add_argument("--extra", action="store_true",
                     help="also time tiled layers, the paper's Table 4 shapes, weights transformed ahead, the 3x3 "
                          "sweep of Section 5.4, rectangular bases, odd-factor FFT sizes (an `extra` object)")
@@ -775,7 +775,8 @@ def main():
     name = args.workload
     prof_steps = max(1, min(args.steps, 50))
     head, cfg, host, passes, flops = measure_config(hd, name, args.steps, args.warmup, prof_steps,
-                                                    args.separate_passes, args.library_basis)
+                                                    args.separate_passes, args.library_basis,
+                                                    per_pass=not args.no_others)
     stages = head["stages"]
     dom = head["dominant"]
     d = stages[dom]
